@@ -1,0 +1,150 @@
+/* hbcsf.h -- C ABI of the MI355X (gfx950) sparse-MTTKRP library.
+ *
+ * The library computes mode-n sparse MTTKRP on 3- and 4-order tensors,
+ *
+ *     Y(i_n, :) = sum over nonzeros X(i_1..i_N) * hadamard_{m != n} A_m(i_m, :)
+ *
+ * (Section II-C, Eq. 4-7), from a load-balanced hybrid compressed-sparse-fiber
+ * representation (Sections IV and V: B-CSF with fbr-split and slc-split, CSL, and
+ * the three-group HB-CSF partition), one representation per mode (the "ALLMODE"
+ * setting of Section VI-A).
+ *
+ * Conventions (Algorithm "COO-MTTKRP" inputs and Section VI-A): indices are
+ * 0-based uint32, values and factor matrices fp32, factor matrices and the
+ * output are dense row-major [dims[m]][rank] with leading dimension = rank.
+ *
+ * Every function returns 0 on success or a negative HBCSF_E* code; the text of
+ * the last failure on the calling thread is kept for hbcsf_last_error().  No
+ * C++ exception crosses this boundary.  "host" / "device" on a pointer says
+ * which memory it must point to.  The library never frees caller memory.
+ */
+#ifndef HBCSF_H_
+#define HBCSF_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HBCSF_OK       0
+#define HBCSF_EINVAL  -1  /* null pointer, unsupported order / mode / rank, bad option      */
+#define HBCSF_ERANGE  -2  /* an index is >= its dimension, or a dimension is too large      */
+#define HBCSF_ENOMEM  -3  /* host allocation failed, or the device arena is too small        */
+#define HBCSF_ESTATE  -4  /* hbcsf_mttkrp before hbcsf_upload                                */
+#define HBCSF_EHIP    -5  /* a HIP call failed; hbcsf_last_error() names it                  */
+
+#define HBCSF_MAX_ORDER 4
+
+typedef struct hbcsf_tensor hbcsf_tensor; /* opaque, owned by the library, freed by hbcsf_free */
+
+/* Build options (all result-invariant: they change scheduling and storage only).
+ * A zero field selects the default. */
+typedef struct hbcsf_opts {
+  uint32_t fiber_threshold;   /* T_f of fbr-split (Section IV-B, VI-B): no fiber segment holds more
+                                 than T_f nonzeros.  Cuts fall on multiples of T_f in a group's
+                                 nonzero stream.  Multiple of 8, 8..64.  Default 32.               */
+  uint32_t slice_threshold;   /* T_s of slc-split (Section IV-A): nonzeros one wavefront works
+                                 through before it merges its partial rows; a slice of n nonzeros
+                                 is shared by at most ceil(n/T_s)+1 wavefronts.  0 = sized from
+                                 the device at launch.                                             */
+  uint32_t mode_order_policy; /* order of the non-root modes in each per-mode tree (the paper
+                                 leaves it open): 0 = shorter dimension nearer the root,
+                                 1 = longer dimension nearer the root, 2 = increasing mode number. */
+  uint32_t group_mask;        /* HB-CSF groups in use (Section V): bit0 = COO group, bit1 = CSL
+                                 group.  Default (0) = 3 = both.  4 = neither (plain B-CSF),
+                                 for ablation.  Slices of a disabled group go to the CSF group.    */
+} hbcsf_opts;
+
+/* Per-mode statistics of the built representation.  "words" are 4-byte index words as the
+ * paper counts storage (values excluded): COO 3M (Section III-A), CSF 2S+2F+M (Section III-B),
+ * HB-CSF the sum over its three groups (Section V, the 24 / 24 / 19-word example). */
+typedef struct hbcsf_stats {
+  uint64_t nnz;               /* M                                                            */
+  uint64_t slices;            /* S: non-empty slices of this mode                             */
+  uint64_t fibers[2];         /* F per fiber level before fbr-split ([1] only for order 4)    */
+  uint64_t segments[2];       /* fiber segments per fiber level in the CSF group (F')         */
+  uint64_t group_nnz[3];      /* nonzeros in the COO, CSL, CSF groups                         */
+  uint64_t group_slices[3];   /* slices in the COO, CSL, CSF groups                           */
+  uint64_t shared_slices;     /* slices merged with atomic adds (they span several runs)      */
+  uint64_t runs[3];           /* lane-group runs (T_f nonzeros each) per group                */
+  uint64_t words_coo;         /* N*M                                                          */
+  uint64_t words_csf;         /* plain CSF of the whole tensor, no splitting                  */
+  uint64_t words_hbcsf;       /* the three groups, no splitting (the paper's accounting)      */
+  uint64_t stream_bytes[3];   /* bytes of device arrays each group kernel reads, as built     */
+  uint64_t distinct_rows[3][HBCSF_MAX_ORDER]; /* [group][level]: distinct factor rows gathered */
+  uint64_t owned_rows;        /* output rows written by one plain store (no zero-fill needed) */
+  uint64_t flops_real;        /* multiply-adds actually done x2 (Section III-B's count)       */
+  uint32_t level_mode[HBCSF_MAX_ORDER]; /* tensor mode at tree level 0 (root) .. N-1 (leaf)   */
+  uint32_t fiber_threshold;   /* T_f in use                                                   */
+  double   build_seconds;     /* host time to build this mode's representation                */
+} hbcsf_stats;
+
+/* Builds the per-mode HB-CSF representations on the host (sort by mode, CSF, fbr-split,
+ * slice classification into the COO / CSL / CSF groups, run tables for slc-split).
+ *   order  3 or 4.         dims   host [order].          nnz  number of stored nonzeros (>= 0).
+ *   inds   host [order] pointers to host [nnz] index arrays, inds[m][z] < dims[m].
+ *   vals   host [nnz].     opts   host, may be NULL.
+ *   out    receives the handle.  The inputs are not referenced after the call returns.
+ * Duplicate coordinates are legal and act as separate nonzeros.
+ * Limits: dims[m] <= 2^31 - 2, nnz < 2^32 - 2^16. */
+int hbcsf_build_format(int order, const uint64_t *dims, uint64_t nnz,
+                       const uint32_t *const *inds, const float *vals,
+                       const hbcsf_opts *opts, hbcsf_tensor **out);
+
+/* Size in bytes of the device arena that holds all modes' arrays. */
+int hbcsf_device_bytes(const hbcsf_tensor *t, uint64_t *bytes);
+
+/* Copies all modes' arrays into the caller's device arena (device, 256-byte aligned, at least
+ * hbcsf_device_bytes bytes) on hip_stream (a hipStream_t, NULL = the default stream) and
+ * waits for the copy.  The arena must stay valid while the handle is used for hbcsf_mttkrp. */
+int hbcsf_upload(hbcsf_tensor *t, void *device_arena, uint64_t bytes, void *hip_stream);
+
+/* Mode-`mode` (0-based) MTTKRP, asynchronous on hip_stream.
+ *   rank     4, 8, 16, 32, 64 or 128.
+ *   factors  host array of `order` device pointers; factors[m] is [dims[m]][rank] row-major,
+ *            16-byte aligned; factors[mode] is ignored (may be NULL).
+ *   out      device [dims[mode]][rank], 16-byte aligned, OVERWRITTEN: every row is defined
+ *            (rows of empty slices are zero), as Algorithm "COO-MTTKRP" returns Y from zero.
+ * Launches the output-definition kernel, then the COO-group, CSL-group and B-CSF-group
+ * kernels (Algorithm "HB-CSF-MTTKRP", execute step).  Slices that span several work units
+ * are merged with fp32 atomic adds (Section IV-A), so results can differ between runs in
+ * the last bits.  NaN / Inf inputs propagate. */
+int hbcsf_mttkrp(const hbcsf_tensor *t, int mode, int rank, const float *const *factors,
+                 float *out, void *hip_stream);
+
+int hbcsf_get_stats(const hbcsf_tensor *t, int mode, hbcsf_stats *stats);
+
+/* Read-only view of one host-side format array of a mode, for inspection and tests.
+ * array ids: HBCSF_ARR_*; `group` 0 = COO, 1 = CSL, 2 = CSF; `level` 0 = root .. order-1 = leaf.
+ * Returns HBCSF_EINVAL for an array the group does not have.  *count is in elements
+ * (uint32 or float). */
+#define HBCSF_ARR_IND        0 /* uint32: index array of `level` (per slice / segment / nonzero) */
+#define HBCSF_ARR_PTR        1 /* uint32: start of each slice / segment in the group's nonzero
+                                  stream, n+1 entries (levels above the leaf of CSF; level 0 of CSL) */
+#define HBCSF_ARR_VAL        2 /* float : values in stream order                                 */
+#define HBCSF_ARR_RUNFIRST   3 /* uint32: slice / segment holding the first nonzero of each run,
+                                  runs+1 entries                                                  */
+#define HBCSF_ARR_OWNED_BITS 4 /* uint32 bitmap over output rows: 1 = written by one plain store */
+int hbcsf_host_array(const hbcsf_tensor *t, int mode, int group, int level, int array_id,
+                     const void **ptr, uint64_t *count);
+
+/* Tuning knobs that need no rebuild.  key: HBCSF_TUNE_*. */
+#define HBCSF_TUNE_SLICE_THRESHOLD 0 /* T_s, nonzeros per wavefront span; 0 = automatic */
+#define HBCSF_TUNE_PROFILE         1 /* 1 = bracket each kernel with HIP events          */
+int hbcsf_tune(hbcsf_tensor *t, int key, uint64_t value);
+
+/* With HBCSF_TUNE_PROFILE on: milliseconds of the four kernels of the last hbcsf_mttkrp call
+ * on this handle (define, COO, CSL, CSF; 0 for a kernel that was not launched).  Synchronises
+ * with the last call's events. */
+int hbcsf_last_kernel_ms(hbcsf_tensor *t, float ms[4]);
+
+void hbcsf_free(hbcsf_tensor *t);
+
+const char *hbcsf_strerror(int code);
+const char *hbcsf_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HBCSF_H_ */

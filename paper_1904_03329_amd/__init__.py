@@ -1,0 +1,74 @@
+"""MI355X-native sparse MTTKRP with a load-balanced hybrid CSF format (HB-CSF).
+
+`binding` mirrors the C ABI of include/hbcsf.h one to one.  `HbcsfTensor` is a small
+convenience wrapper that lets PyTorch supply device memory and the current stream; all
+computation happens in libhbcsf.so.
+"""
+from __future__ import annotations
+
+from . import binding
+
+__all__ = ["binding", "HbcsfTensor"]
+
+
+class HbcsfTensor:
+    """A sparse tensor built into per-mode HB-CSF, optionally resident on the current GPU."""
+
+    def __init__(self, dims, inds, vals, **opts):
+        self.dims = tuple(int(d) for d in dims)
+        self.order = len(self.dims)
+        self.handle = binding.build_format(self.dims, inds, vals, **opts)
+        self._arena = None
+
+    def stats(self, mode: int) -> dict:
+        return binding.get_stats(self.handle, mode)
+
+    def to_device(self):
+        import torch
+
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: hbcsf_upload needs a HIP device")
+        n = binding.device_bytes(self.handle)
+        self._arena = torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
+        binding.upload(self.handle, self._arena.data_ptr(), self._arena.numel(),
+                       torch.cuda.current_stream().cuda_stream)
+        return self
+
+    def mttkrp(self, mode: int, factors, out=None):
+        """factors: one CUDA float32 [dims[m], R] tensor per mode (entry `mode` may be None)."""
+        import torch
+
+        rank = None
+        ptrs = []
+        for m in range(self.order):
+            f = factors[m]
+            if m == mode or f is None:
+                ptrs.append(0)
+                continue
+            if f.dtype != torch.float32 or not f.is_cuda or not f.is_contiguous():
+                raise ValueError("factors must be contiguous float32 CUDA tensors")
+            if f.shape[0] != self.dims[m]:
+                raise ValueError(f"factor {m} must have {self.dims[m]} rows")
+            rank = f.shape[1] if rank is None else rank
+            if f.shape[1] != rank:
+                raise ValueError("factor matrices disagree on the rank")
+            ptrs.append(f.data_ptr())
+        if out is None:
+            out = torch.empty((self.dims[mode], rank), dtype=torch.float32, device="cuda")
+        elif (out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous()
+              or tuple(out.shape) != (self.dims[mode], rank)):
+            raise ValueError("out must be a contiguous float32 CUDA tensor [dims[mode], R]")
+        binding.mttkrp(self.handle, mode, rank, ptrs, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        return out
+
+    def close(self):
+        if self.handle is not None:
+            binding.free(self.handle)
+            self.handle = None
+        self._arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,178 @@
+"""ctypes binding of libhbcsf.so: the same entry points as include/hbcsf.h, argument marshalling only.
+
+Every step of the MTTKRP path runs inside the library (host format builder and gfx950
+kernels).  PyTorch is used by callers for device memory and streams only.  There is no
+fallback: if the library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhbcsf.so")
+
+HBCSF_MAX_ORDER = 4
+ARR_IND, ARR_PTR, ARR_VAL, ARR_RUNFIRST, ARR_OWNED_BITS = 0, 1, 2, 3, 4
+TUNE_SLICE_THRESHOLD, TUNE_PROFILE = 0, 1
+GROUP_COO, GROUP_CSL, GROUP_CSF = 0, 1, 2
+OWNED_BIT = 0x80000000
+
+EXPORTS = (
+    "hbcsf_build_format", "hbcsf_device_bytes", "hbcsf_upload", "hbcsf_mttkrp", "hbcsf_get_stats",
+    "hbcsf_host_array", "hbcsf_tune", "hbcsf_last_kernel_ms", "hbcsf_free", "hbcsf_strerror",
+    "hbcsf_last_error",
+)
+
+
+class hbcsf_opts(ctypes.Structure):
+    _fields_ = [("fiber_threshold", ctypes.c_uint32), ("slice_threshold", ctypes.c_uint32),
+                ("mode_order_policy", ctypes.c_uint32), ("group_mask", ctypes.c_uint32)]
+
+
+class hbcsf_stats(ctypes.Structure):
+    _fields_ = [
+        ("nnz", ctypes.c_uint64), ("slices", ctypes.c_uint64), ("fibers", ctypes.c_uint64 * 2),
+        ("segments", ctypes.c_uint64 * 2), ("group_nnz", ctypes.c_uint64 * 3),
+        ("group_slices", ctypes.c_uint64 * 3), ("shared_slices", ctypes.c_uint64),
+        ("runs", ctypes.c_uint64 * 3), ("words_coo", ctypes.c_uint64), ("words_csf", ctypes.c_uint64),
+        ("words_hbcsf", ctypes.c_uint64), ("stream_bytes", ctypes.c_uint64 * 3),
+        ("distinct_rows", (ctypes.c_uint64 * HBCSF_MAX_ORDER) * 3), ("owned_rows", ctypes.c_uint64),
+        ("flops_real", ctypes.c_uint64), ("level_mode", ctypes.c_uint32 * HBCSF_MAX_ORDER),
+        ("fiber_threshold", ctypes.c_uint32), ("build_seconds", ctypes.c_double),
+    ]
+
+
+class HbcsfError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"hbcsf error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Loads libhbcsf.so (built by paper_1904_03329_amd.build.build()); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run paper_1904_03329_amd.build.build() first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u64, i32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int
+        L.hbcsf_build_format.restype = i32
+        L.hbcsf_build_format.argtypes = [i32, vp, u64, vp, vp, vp, ctypes.POINTER(vp)]
+        L.hbcsf_device_bytes.restype = i32
+        L.hbcsf_device_bytes.argtypes = [vp, ctypes.POINTER(u64)]
+        L.hbcsf_upload.restype = i32
+        L.hbcsf_upload.argtypes = [vp, vp, u64, vp]
+        L.hbcsf_mttkrp.restype = i32
+        L.hbcsf_mttkrp.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.hbcsf_get_stats.restype = i32
+        L.hbcsf_get_stats.argtypes = [vp, i32, ctypes.POINTER(hbcsf_stats)]
+        L.hbcsf_host_array.restype = i32
+        L.hbcsf_host_array.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(u64)]
+        L.hbcsf_tune.restype = i32
+        L.hbcsf_tune.argtypes = [vp, i32, u64]
+        L.hbcsf_last_kernel_ms.restype = i32
+        L.hbcsf_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4)]
+        L.hbcsf_free.restype = None
+        L.hbcsf_free.argtypes = [vp]
+        L.hbcsf_strerror.restype = ctypes.c_char_p
+        L.hbcsf_strerror.argtypes = [i32]
+        L.hbcsf_last_error.restype = ctypes.c_char_p
+        L.hbcsf_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise HbcsfError(rc, (lib().hbcsf_last_error() or b"").decode())
+
+
+def build_format(dims, inds, vals, fiber_threshold=0, slice_threshold=0, mode_order_policy=0, group_mask=0):
+    """hbcsf_build_format: host numpy index arrays (uint32) and values (float32) -> handle."""
+    order = len(dims)
+    d = np.asarray(dims, dtype=np.uint64)
+    inds = [np.ascontiguousarray(x, dtype=np.uint32) for x in inds]
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    nnz = int(vals.shape[0])
+    for x in inds:
+        if x.shape[0] != nnz:
+            raise ValueError("index arrays and vals must have the same length")
+    ptrs = (ctypes.c_void_p * max(order, 1))(*[x.ctypes.data for x in inds])
+    opts = hbcsf_opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask)
+    h = ctypes.c_void_p()
+    _check(lib().hbcsf_build_format(order, d.ctypes.data, nnz, ctypes.cast(ptrs, ctypes.c_void_p),
+                                    vals.ctypes.data, ctypes.cast(ctypes.pointer(opts), ctypes.c_void_p),
+                                    ctypes.byref(h)))
+    return h
+
+
+def device_bytes(h) -> int:
+    n = ctypes.c_uint64()
+    _check(lib().hbcsf_device_bytes(h, ctypes.byref(n)))
+    return int(n.value)
+
+
+def upload(h, arena_ptr: int, nbytes: int, stream: int = 0):
+    """hbcsf_upload: arena_ptr is a device address (e.g. torch_tensor.data_ptr())."""
+    _check(lib().hbcsf_upload(h, ctypes.c_void_p(arena_ptr), nbytes, ctypes.c_void_p(stream)))
+
+
+def mttkrp(h, mode: int, rank: int, factor_ptrs, out_ptr: int, stream: int = 0):
+    """hbcsf_mttkrp: factor_ptrs are device addresses (0 / None allowed at position `mode`)."""
+    arr = (ctypes.c_void_p * len(factor_ptrs))(*[(p if p else None) for p in factor_ptrs])
+    _check(lib().hbcsf_mttkrp(h, mode, rank, ctypes.cast(arr, ctypes.c_void_p), ctypes.c_void_p(out_ptr),
+                              ctypes.c_void_p(stream)))
+
+
+def get_stats(h, mode: int) -> dict:
+    st = hbcsf_stats()
+    _check(lib().hbcsf_get_stats(h, mode, ctypes.byref(st)))
+    out = {}
+    for name, _ in hbcsf_stats._fields_:
+        v = getattr(st, name)
+        if name == "distinct_rows":
+            v = [list(row) for row in v]
+        elif hasattr(v, "__len__"):
+            v = list(v)
+        out[name] = v
+    return out
+
+
+def host_array(h, mode: int, group: int, level: int, array_id: int) -> np.ndarray:
+    """Copy of one host-side format array (uint32, or float32 for ARR_VAL)."""
+    p = ctypes.c_void_p()
+    n = ctypes.c_uint64()
+    _check(lib().hbcsf_host_array(h, mode, group, level, array_id, ctypes.byref(p), ctypes.byref(n)))
+    ctype = ctypes.c_float if array_id == ARR_VAL else ctypes.c_uint32
+    if n.value == 0:
+        return np.zeros(0, dtype=np.float32 if array_id == ARR_VAL else np.uint32)
+    buf = (ctype * n.value).from_address(p.value)
+    return np.frombuffer(buf, dtype=np.float32 if array_id == ARR_VAL else np.uint32).copy()
+
+
+def tune(h, key: int, value: int):
+    _check(lib().hbcsf_tune(h, key, value))
+
+
+def last_kernel_ms(h):
+    ms = (ctypes.c_float * 4)()
+    _check(lib().hbcsf_last_kernel_ms(h, ctypes.byref(ms)))
+    return [float(x) for x in ms]
+
+
+def free(h):
+    lib().hbcsf_free(h)
+
+
+def strerror(code: int) -> str:
+    return lib().hbcsf_strerror(code).decode()
+
+
+def last_error() -> str:
+    return (lib().hbcsf_last_error() or b"").decode()

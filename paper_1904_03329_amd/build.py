@@ -1,0 +1,41 @@
+"""Builds libhbcsf.so (host format builder + gfx950 kernels + C ABI) in-tree."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+INCLUDE = os.path.join(os.path.dirname(HERE), "include")
+SO = os.path.join(HERE, "libhbcsf.so")
+
+HIP_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
+    # keep the compiler from forming packed-fp32 instructions
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+]
+
+
+def build(verbose: bool = False) -> str:
+    """Compiles every source each time it is called and links the shared library."""
+    objs = []
+    inc = ["-I", INCLUDE, "-I", CSRC]
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+
+    o = os.path.join(CSRC, "hbcsf_format.o")
+    run(["g++", "-O3", "-std=c++17", "-fPIC", "-fopenmp", "-c", os.path.join(CSRC, "hbcsf_format.cpp"), "-o", o] + inc)
+    objs.append(o)
+    for name in ("hbcsf_kernels", "hbcsf_capi"):
+        o = os.path.join(CSRC, name + ".o")
+        run(["hipcc"] + HIP_FLAGS + inc + ["-c", os.path.join(CSRC, name + ".hip"), "-o", o])
+        objs.append(o)
+    run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", SO] + objs + ["-lgomp"])
+    return SO
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,313 @@
+// C-ABI layer: argument checks, device arena bookkeeping and kernel launches.
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+
+#include "hbcsf.h"
+#include "hbcsf_device.h"
+#include "hbcsf_internal.h"
+
+using namespace hbcsf;
+
+struct hbcsf_tensor {
+  int order = 0;
+  uint64_t dims[HBCSF_MAX_ORDER] = {0, 0, 0, 0};
+  uint64_t nnz = 0;
+  hbcsf_opts opts{};
+  std::unique_ptr<ModeFormat> modes[HBCSF_MAX_ORDER];
+  uint64_t arenaBytes = 0;
+  uint8_t* arena = nullptr;  // caller's device memory
+  bool uploaded = false;
+  int numCU = 256;
+  uint64_t sliceThreshold = 0;
+  bool profile = false;
+  bool eventsMade = false;
+  bool eventsValid = false;
+  hipEvent_t ev[5];
+  bool launched[4] = {false, false, false, false};
+};
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string& msg) {
+  g_err = msg;
+  return code;
+}
+
+int fail_hip(hipError_t e, const char* what) {
+  g_err = std::string(what) + ": " + hipGetErrorString(e);
+  return HBCSF_EHIP;
+}
+
+bool pow2_in(uint32_t v, uint32_t lo, uint32_t hi) { return v >= lo && v <= hi && (v & (v - 1)) == 0; }
+
+uint32_t round_up8(uint64_t v) { return (uint32_t)((v + 7) / 8 * 8); }
+
+}  // namespace
+
+extern "C" {
+
+int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* const* inds,
+                       const float* vals, const hbcsf_opts* opts, hbcsf_tensor** out) {
+  if (!out) return fail(HBCSF_EINVAL, "out is null");
+  *out = nullptr;
+  if (order != 3 && order != 4) return fail(HBCSF_EINVAL, "order must be 3 or 4");
+  if (!dims) return fail(HBCSF_EINVAL, "dims is null");
+  if (nnz > 0 && (!inds || !vals)) return fail(HBCSF_EINVAL, "inds or vals is null");
+  if (nnz >= 0xffff0000ull) return fail(HBCSF_ERANGE, "nnz must be below 2^32 - 2^16");
+  for (int m = 0; m < order; ++m) {
+    if (dims[m] == 0 || dims[m] > 0x7ffffffeull) return fail(HBCSF_ERANGE, "each dimension must be in 1 .. 2^31-2");
+    if (nnz > 0 && !inds[m]) return fail(HBCSF_EINVAL, "an index array is null");
+  }
+  hbcsf_opts o{};
+  if (opts) o = *opts;
+  if (o.fiber_threshold == 0) o.fiber_threshold = 32;
+  if (!pow2_in(o.fiber_threshold, 8, 64)) return fail(HBCSF_EINVAL, "fiber_threshold must be 8, 16, 32 or 64");
+  if (o.mode_order_policy > 2) return fail(HBCSF_EINVAL, "mode_order_policy must be 0, 1 or 2");
+  if (o.group_mask > 4) return fail(HBCSF_EINVAL, "group_mask must be 0..4");
+  std::unique_ptr<hbcsf_tensor> t(new (std::nothrow) hbcsf_tensor);
+  if (!t) return fail(HBCSF_ENOMEM, "out of host memory");
+  t->order = order;
+  t->nnz = nnz;
+  t->opts = o;
+  t->sliceThreshold = o.slice_threshold;
+  for (int m = 0; m < order; ++m) t->dims[m] = dims[m];
+  uint64_t off = 0;
+  for (int m = 0; m < order; ++m) {
+    t->modes[m].reset(new (std::nothrow) ModeFormat);
+    if (!t->modes[m]) return fail(HBCSF_ENOMEM, "out of host memory");
+    std::string err;
+    const int rc = build_mode(order, dims, nnz, inds, vals, o, m, t->modes[m].get(), &err);
+    if (rc != HBCSF_OK) return fail(rc, err);
+    t->modes[m]->devOffset = off;
+    off += t->modes[m]->blobBytes;
+  }
+  t->arenaBytes = off;
+  *out = t.release();
+  return HBCSF_OK;
+}
+
+int hbcsf_device_bytes(const hbcsf_tensor* t, uint64_t* bytes) {
+  if (!t || !bytes) return fail(HBCSF_EINVAL, "null argument");
+  *bytes = t->arenaBytes;
+  return HBCSF_OK;
+}
+
+int hbcsf_upload(hbcsf_tensor* t, void* device_arena, uint64_t bytes, void* hip_stream) {
+  if (!t || !device_arena) return fail(HBCSF_EINVAL, "null argument");
+  if (bytes < t->arenaBytes) return fail(HBCSF_ENOMEM, "device arena is smaller than hbcsf_device_bytes");
+  if (((uintptr_t)device_arena & (kAlign - 1)) != 0) return fail(HBCSF_EINVAL, "device arena must be 256-byte aligned");
+  hipStream_t s = (hipStream_t)hip_stream;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  int cu = 0;
+  e = hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return fail_hip(e, "hipDeviceGetAttribute");
+  t->numCU = cu > 0 ? cu : 256;
+  for (int m = 0; m < t->order; ++m) {
+    const ModeFormat& f = *t->modes[m];
+    e = hipMemcpyAsync((uint8_t*)device_arena + f.devOffset, f.blob, f.blobBytes, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync");
+  }
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+  t->arena = (uint8_t*)device_arena;
+  t->uploaded = true;
+  return HBCSF_OK;
+}
+
+int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const* factors, float* out,
+                 void* hip_stream) {
+  hbcsf_tensor* t = const_cast<hbcsf_tensor*>(tc);
+  if (!t || !factors || !out) return fail(HBCSF_EINVAL, "null argument");
+  if (mode < 0 || mode >= t->order) return fail(HBCSF_EINVAL, "mode out of range");
+  if (!(rank == 8 || rank == 16 || rank == 32 || rank == 64 || rank == 128))
+    return fail(HBCSF_EINVAL, "rank must be 8, 16, 32, 64 or 128");
+  if (!t->uploaded) return fail(HBCSF_ESTATE, "hbcsf_upload has not been called");
+  if (((uintptr_t)out & 15) != 0) return fail(HBCSF_EINVAL, "out must be 16-byte aligned");
+  for (int m = 0; m < t->order; ++m) {
+    if (m == mode) continue;
+    if (!factors[m]) return fail(HBCSF_EINVAL, "a factor pointer is null");
+    if (((uintptr_t)factors[m] & 15) != 0) return fail(HBCSF_EINVAL, "factors must be 16-byte aligned");
+  }
+  const ModeFormat& f = *t->modes[mode];
+  const int N = t->order;
+  const int G = rank / 4;
+  const int NG = 64 / G;
+  const uint32_t L = f.L;
+  uint32_t lshift = 0;
+  while ((1u << lshift) < L) ++lshift;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const uint8_t* base = t->arena + f.devOffset;
+  hipError_t e;
+
+  if (t->profile) {
+    if (!t->eventsMade) {
+      for (int i = 0; i < 5; ++i) {
+        e = hipEventCreate(&t->ev[i]);
+        if (e != hipSuccess) return fail_hip(e, "hipEventCreate");
+      }
+      t->eventsMade = true;
+    }
+    e = hipEventRecord(t->ev[0], s);
+    if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
+  }
+
+  // 1. define every output row that no plain store will write
+  {
+    const uint64_t nvec = f.rows * (uint64_t)G;
+    uint64_t blocks = (nvec + 255) / 256;
+    const uint64_t cap = (uint64_t)t->numCU * 32;
+    if (blocks > cap) blocks = cap;
+    if (blocks == 0) blocks = 1;
+    e = launch_define(out, (const uint32_t*)(base + f.ownedBits.off), f.rows, G, (uint32_t)blocks, s);
+    if (e != hipSuccess) return fail_hip(e, "launch of the output-definition kernel");
+    t->launched[0] = true;
+    if (t->profile) (void)hipEventRecord(t->ev[1], s);
+  }
+
+  // 2. the three group kernels (execute step of Algorithm "HB-CSF-MTTKRP")
+  for (int g = 0; g < 3; ++g) {
+    const GroupFormat& gf = f.g[g];
+    t->launched[1 + g] = false;
+    if (gf.nnz > 0) {
+      GroupArgs a;
+      std::memset(&a, 0, sizeof(a));
+      for (int l = 0; l < N; ++l) {
+        a.ind[l] = gf.ind[l].present ? (const uint32_t*)(base + gf.ind[l].off) : nullptr;
+        a.ptr[l] = gf.ptr[l].present ? (const uint32_t*)(base + gf.ptr[l].off) : nullptr;
+        a.runFirst[l] = gf.runFirst[l].present ? (const uint32_t*)(base + gf.runFirst[l].off) : nullptr;
+        a.fac[l] = l == 0 ? nullptr : factors[f.levelMode[l]];
+      }
+      a.val = (const float*)(base + gf.val.off);
+      a.out = out;
+      a.nnz = (uint32_t)gf.nnz;
+      a.runs = (uint32_t)gf.runs;
+      a.lshift = lshift;
+      a.nUnits = (uint32_t)((gf.runs + NG - 1) / NG);
+      uint32_t blocks, threads;
+      size_t lds = 0;
+      if (g == kCoo) {
+        threads = 256;
+        const uint64_t perBlock = (uint64_t)NG * 4 * 4;
+        uint64_t b = (gf.nnz + perBlock - 1) / perBlock;
+        const uint64_t cap = (uint64_t)t->numCU * 16;
+        if (b > cap) b = cap;
+        blocks = round_up8(b);
+        a.unitsPerWave = 0;
+      } else {
+        const int RW = N == 3 ? 4 : 8;
+        const size_t ldsWave = (size_t)NG * (L + 1) * RW * 4;
+        int wpb = 4;
+        while (wpb > 1 && ldsWave * wpb > 48 * 1024) wpb >>= 1;
+        threads = 64 * wpb;
+        lds = ldsWave * wpb;
+        uint64_t upw;
+        if (t->sliceThreshold) {
+          upw = t->sliceThreshold / ((uint64_t)NG * L);
+        } else {
+          const uint64_t target = (uint64_t)t->numCU * 32;
+          upw = (a.nUnits + target - 1) / target;
+        }
+        if (upw == 0) upw = 1;
+        a.unitsPerWave = (uint32_t)upw;
+        const uint64_t waves = (a.nUnits + upw - 1) / upw;
+        blocks = round_up8((waves + wpb - 1) / wpb);
+      }
+      e = launch_group(g, N, G, a, blocks, threads, lds, s);
+      if (e != hipSuccess) return fail_hip(e, "launch of a group kernel");
+      t->launched[1 + g] = true;
+    }
+    if (t->profile) (void)hipEventRecord(t->ev[2 + g], s);
+  }
+  t->eventsValid = t->profile;
+  return HBCSF_OK;
+}
+
+int hbcsf_get_stats(const hbcsf_tensor* t, int mode, hbcsf_stats* stats) {
+  if (!t || !stats) return fail(HBCSF_EINVAL, "null argument");
+  if (mode < 0 || mode >= t->order) return fail(HBCSF_EINVAL, "mode out of range");
+  *stats = t->modes[mode]->stats;
+  return HBCSF_OK;
+}
+
+int hbcsf_host_array(const hbcsf_tensor* t, int mode, int group, int level, int array_id,
+                     const void** ptr, uint64_t* count) {
+  if (!t || !ptr || !count) return fail(HBCSF_EINVAL, "null argument");
+  if (mode < 0 || mode >= t->order) return fail(HBCSF_EINVAL, "mode out of range");
+  const ModeFormat& f = *t->modes[mode];
+  const ArrayRef* r = nullptr;
+  if (array_id == HBCSF_ARR_OWNED_BITS) {
+    r = &f.ownedBits;
+  } else {
+    if (group < 0 || group > 2 || level < 0 || level >= t->order) return fail(HBCSF_EINVAL, "group or level out of range");
+    const GroupFormat& g = f.g[group];
+    if (array_id == HBCSF_ARR_IND) r = &g.ind[level];
+    else if (array_id == HBCSF_ARR_PTR) r = &g.ptr[level];
+    else if (array_id == HBCSF_ARR_VAL) r = &g.val;
+    else if (array_id == HBCSF_ARR_RUNFIRST) r = &g.runFirst[level];
+  }
+  if (!r || !r->present) return fail(HBCSF_EINVAL, "this group has no such array");
+  *ptr = f.blob + r->off;
+  *count = r->count;
+  return HBCSF_OK;
+}
+
+int hbcsf_tune(hbcsf_tensor* t, int key, uint64_t value) {
+  if (!t) return fail(HBCSF_EINVAL, "null argument");
+  if (key == HBCSF_TUNE_SLICE_THRESHOLD) {
+    t->sliceThreshold = value;
+    return HBCSF_OK;
+  }
+  if (key == HBCSF_TUNE_PROFILE) {
+    t->profile = value != 0;
+    t->eventsValid = false;
+    return HBCSF_OK;
+  }
+  return fail(HBCSF_EINVAL, "unknown tuning key");
+}
+
+int hbcsf_last_kernel_ms(hbcsf_tensor* t, float ms[4]) {
+  if (!t || !ms) return fail(HBCSF_EINVAL, "null argument");
+  if (!t->eventsValid) return fail(HBCSF_ESTATE, "no profiled hbcsf_mttkrp call to report");
+  hipError_t e = hipEventSynchronize(t->ev[4]);
+  if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
+  for (int i = 0; i < 4; ++i) {
+    ms[i] = 0.f;
+    if (!t->launched[i]) continue;
+    e = hipEventElapsedTime(&ms[i], t->ev[i], t->ev[i + 1]);
+    if (e != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
+  }
+  return HBCSF_OK;
+}
+
+void hbcsf_free(hbcsf_tensor* t) {
+  if (!t) return;
+  if (t->eventsMade)
+    for (int i = 0; i < 5; ++i) (void)hipEventDestroy(t->ev[i]);
+  delete t;
+}
+
+const char* hbcsf_strerror(int code) {
+  switch (code) {
+    case HBCSF_OK: return "ok";
+    case HBCSF_EINVAL: return "invalid argument";
+    case HBCSF_ERANGE: return "index or size out of range";
+    case HBCSF_ENOMEM: return "out of memory or arena too small";
+    case HBCSF_ESTATE: return "call out of order";
+    case HBCSF_EHIP: return "HIP call failed";
+    default: return "unknown error code";
+  }
+}
+
+const char* hbcsf_last_error(void) { return g_err.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,36 @@
+// Kernel argument block and launch entry points shared by the kernels and the C-ABI layer.
+#ifndef HBCSF_DEVICE_H_
+#define HBCSF_DEVICE_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hbcsf {
+
+enum KernelKind { kCooKernel = 0, kCslKernel = 1, kCsfKernel = 2 };
+
+// Device pointers of one slice group of one mode, by tree level (0 = root .. order-1 = leaf).
+struct GroupArgs {
+  const uint32_t* ind[4];       // index arrays (per slice / segment / nonzero, by group kind)
+  const uint32_t* ptr[4];       // starts in the group's nonzero stream (n+1 entries)
+  const uint32_t* runFirst[4];  // slice / segment holding the first nonzero of each run
+  const float* val;             // values in stream order
+  const float* fac[4];          // factor matrix of each tree level (fac[0] unused)
+  float* out;                   // [rows][rank]
+  uint32_t nnz;                 // nonzeros in the group
+  uint32_t runs;                // ceil(nnz / L)
+  uint32_t lshift;              // log2 L
+  uint32_t nUnits;              // ceil(runs / lane groups per wavefront)
+  uint32_t unitsPerWave;        // contiguous units one wavefront works through
+};
+
+// kind: KernelKind; order 3 or 4; G = rank / 4 lanes per factor row (2, 4, 8, 16 or 32).
+hipError_t launch_group(int kind, int order, int G, const GroupArgs& a, uint32_t blocks,
+                        uint32_t threads, size_t ldsBytes, hipStream_t s);
+
+hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, int G,
+                         uint32_t blocks, hipStream_t s);
+
+}  // namespace hbcsf
+
+#endif  // HBCSF_DEVICE_H_

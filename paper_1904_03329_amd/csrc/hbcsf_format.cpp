@@ -1,0 +1,472 @@
+// Host-side format builder: COO -> per-mode HB-CSF (Sections III-B, IV, V).
+//
+// For the root mode n the nonzeros are sorted by (root, middle level(s), leaf) index, which
+// gives the compressed-sparse-fiber tree (Section III-B).  Each slice is then put into one of
+// three groups (Section V and Section VI-D: one nonzero -> COO; every fiber a single nonzero
+// -> CSL; otherwise CSF).  Inside the CSL and CSF groups the group's nonzero stream is cut
+// into runs of T_f nonzeros: a fiber is cut wherever it crosses a run boundary (fbr-split,
+// Sections IV-B and VI-B, so no segment exceeds T_f nonzeros), and a slice that crosses a run
+// boundary is handled by several lane groups whose partial rows are merged with atomic adds
+// (slc-split, Section IV-A: slices stay whole in the arrays, more workers are assigned).
+// The run tables say which slice / segment holds the first nonzero of each run.
+
+#include "hbcsf_internal.h"
+
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+#include <memory>
+
+#include <omp.h>
+
+namespace hbcsf {
+namespace {
+
+inline int bits_for(uint64_t dim) {
+  int b = 1;
+  while (b < 63 && (1ull << b) < dim) ++b;
+  return b;
+}
+
+// Stable parallel LSD radix sort of (key, payload) pairs on the low `totalBits` bits.
+// On return k / v point at the sorted data (either the first or the second buffer pair).
+template <typename Key>
+void radix_sort_pairs(Key*& k, uint32_t*& v, Key*& k2, uint32_t*& v2, size_t n, int totalBits) {
+  if (n < 2 || totalBits <= 0) return;
+  const int passes = (totalBits + 11) / 12;
+  const int digit = (totalBits + passes - 1) / passes;
+  const size_t buckets = (size_t)1 << digit;
+  const int nt = omp_get_max_threads();
+  std::vector<size_t> hist((size_t)nt * buckets);
+  for (int pass = 0; pass < passes; ++pass) {
+    const int shift = pass * digit;
+    std::fill(hist.begin(), hist.end(), 0);
+    const Key* src = k;
+    const uint32_t* srcv = v;
+    Key* dst = k2;
+    uint32_t* dstv = v2;
+#pragma omp parallel num_threads(nt)
+    {
+      const int t = omp_get_thread_num();
+      const size_t lo = n * (size_t)t / nt, hi = n * (size_t)(t + 1) / nt;
+      size_t* h = &hist[(size_t)t * buckets];
+      for (size_t i = lo; i < hi; ++i) ++h[(size_t)(src[i] >> shift) & (buckets - 1)];
+#pragma omp barrier
+#pragma omp single
+      {
+        size_t run = 0;
+        for (size_t d = 0; d < buckets; ++d)
+          for (int tt = 0; tt < nt; ++tt) {
+            const size_t c = hist[(size_t)tt * buckets + d];
+            hist[(size_t)tt * buckets + d] = run;
+            run += c;
+          }
+      }
+      for (size_t i = lo; i < hi; ++i) {
+        const size_t at = h[(size_t)(src[i] >> shift) & (buckets - 1)]++;
+        dst[at] = src[i];
+        dstv[at] = srcv[i];
+      }
+    }
+    std::swap(k, k2);
+    std::swap(v, v2);
+  }
+}
+
+struct Layout {
+  uint64_t bytes = 0;
+  ArrayRef add(uint64_t count) {
+    ArrayRef r;
+    r.off = bytes;
+    r.count = count;
+    r.present = true;
+    bytes += ((count * 4 + kAlign - 1) / kAlign) * kAlign;
+    if (count == 0) bytes += kAlign;
+    return r;
+  }
+};
+
+template <typename Key>
+int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* const* inds,
+                 const float* vals, const hbcsf_opts& opts, int mode, ModeFormat* out,
+                 std::string* err) {
+  const auto t_begin = std::chrono::steady_clock::now();
+  const int N = order;
+  const uint32_t L = opts.fiber_threshold ? opts.fiber_threshold : 32;
+  const uint32_t gmask = opts.group_mask == 0 ? 3u : (opts.group_mask & 3u);
+  const bool cooOn = gmask & 1u, cslOn = gmask & 2u;
+
+  // Tree levels: root = the target mode; the other modes ordered by the policy.
+  int lv[HBCSF_MAX_ORDER];
+  lv[0] = mode;
+  {
+    std::vector<int> rest;
+    for (int m = 0; m < N; ++m)
+      if (m != mode) rest.push_back(m);
+    if (opts.mode_order_policy == 0)
+      std::stable_sort(rest.begin(), rest.end(), [&](int a, int b) { return dims[a] < dims[b]; });
+    else if (opts.mode_order_policy == 1)
+      std::stable_sort(rest.begin(), rest.end(), [&](int a, int b) { return dims[a] > dims[b]; });
+    for (int l = 1; l < N; ++l) lv[l] = rest[l - 1];
+  }
+  int bits[HBCSF_MAX_ORDER], shift[HBCSF_MAX_ORDER];
+  uint64_t mask[HBCSF_MAX_ORDER];
+  int total = 0;
+  for (int l = N - 1; l >= 0; --l) {
+    bits[l] = bits_for(dims[lv[l]]);
+    shift[l] = total;
+    mask[l] = (1ull << bits[l]) - 1;
+    total += bits[l];
+  }
+
+  out->order = N;
+  out->mode = mode;
+  out->L = L;
+  out->rows = dims[mode];
+  for (int l = 0; l < N; ++l) out->levelMode[l] = lv[l];
+
+  // ---- sort by packed (root, ..., leaf) key; the value rides along as payload ----
+  const size_t M = (size_t)nnz;
+  std::unique_ptr<Key[]> kbuf1(new (std::nothrow) Key[M + 1]), kbuf2(new (std::nothrow) Key[M + 1]);
+  std::unique_ptr<uint32_t[]> vbuf1(new (std::nothrow) uint32_t[M + 1]), vbuf2(new (std::nothrow) uint32_t[M + 1]);
+  if (!kbuf1 || !kbuf2 || !vbuf1 || !vbuf2) {
+    *err = "out of host memory while sorting";
+    return HBCSF_ENOMEM;
+  }
+  Key* K = kbuf1.get();
+  Key* K2 = kbuf2.get();
+  uint32_t* V = vbuf1.get();
+  uint32_t* V2 = vbuf2.get();
+  int bad = 0;
+  int unsorted = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+  for (int64_t z = 0; z < (int64_t)M; ++z) {
+    Key key = 0;
+    for (int l = 0; l < N; ++l) {
+      const uint32_t i = inds[lv[l]][z];
+      if ((uint64_t)i >= dims[lv[l]]) bad |= 1;
+      key |= (Key)i << shift[l];
+    }
+    K[z] = key;
+    uint32_t vb;
+    std::memcpy(&vb, &vals[z], 4);
+    V[z] = vb;
+  }
+  if (bad) {
+    *err = "an index is not below its dimension";
+    return HBCSF_ERANGE;
+  }
+#pragma omp parallel for schedule(static) reduction(| : unsorted)
+  for (int64_t z = 1; z < (int64_t)M; ++z)
+    if (K[z] < K[z - 1]) unsorted |= 1;
+  if (unsorted) radix_sort_pairs<Key>(K, V, K2, V2, M, total);
+  if (K == kbuf1.get()) { kbuf2.reset(); vbuf2.reset(); } else { kbuf1.reset(); vbuf1.reset(); }
+
+  auto idx = [&](int l, size_t p) -> uint32_t { return (uint32_t)((uint64_t)(K[p] >> shift[l]) & mask[l]); };
+  auto fresh = [&](int l, size_t p) -> bool { return p == 0 || (K[p] >> shift[l]) != (K[p - 1] >> shift[l]); };
+
+  // ---- slices ----
+  const int nt = omp_get_max_threads();
+  std::vector<uint64_t> tcount(nt + 1, 0);
+#pragma omp parallel num_threads(nt)
+  {
+    const int t = omp_get_thread_num();
+    const size_t lo = M * (size_t)t / nt, hi = M * (size_t)(t + 1) / nt;
+    uint64_t c = 0;
+    for (size_t p = lo; p < hi; ++p) c += fresh(0, p);
+    tcount[t + 1] = c;
+  }
+  for (int t = 0; t < nt; ++t) tcount[t + 1] += tcount[t];
+  const uint64_t S = tcount[nt];
+  std::vector<uint32_t> sStart(S + 1);
+#pragma omp parallel num_threads(nt)
+  {
+    const int t = omp_get_thread_num();
+    const size_t lo = M * (size_t)t / nt, hi = M * (size_t)(t + 1) / nt;
+    uint64_t at = tcount[t];
+    for (size_t p = lo; p < hi; ++p)
+      if (fresh(0, p)) sStart[at++] = (uint32_t)p;
+  }
+  sStart[S] = (uint32_t)M;
+
+  // ---- classify slices (Section V; Section VI-D) ----
+  const int NF = N - 2;  // fiber levels 1..NF
+  std::vector<uint8_t> grp(S);
+  uint64_t fibNat[2] = {0, 0};
+  uint64_t fibNatCsf[2] = {0, 0};
+  {
+    uint64_t f0 = 0, f1 = 0, c0 = 0, c1 = 0;
+#pragma omp parallel for schedule(dynamic, 512) reduction(+ : f0, f1, c0, c1)
+    for (int64_t s = 0; s < (int64_t)S; ++s) {
+      const size_t b = sStart[s], e = sStart[s + 1];
+      uint64_t nf[2] = {0, 0};
+      for (size_t p = b; p < e; ++p) {
+        nf[0] += fresh(1, p);
+        if (NF == 2) nf[1] += fresh(2, p);
+      }
+      const uint64_t n = e - b, deep = nf[NF - 1];
+      uint8_t g;
+      if (n == 1 && cooOn) g = kCoo;
+      else if (deep == n && cslOn) g = kCsl;
+      else g = kCsf;
+      grp[s] = g;
+      f0 += nf[0];
+      f1 += nf[1];
+      if (g == kCsf) { c0 += nf[0]; c1 += nf[1]; }
+    }
+    fibNat[0] = f0; fibNat[1] = f1; fibNatCsf[0] = c0; fibNatCsf[1] = c1;
+  }
+
+  // ---- position of each slice inside its group ----
+  std::vector<uint32_t> ord(S), off(S);
+  uint64_t gS[3] = {0, 0, 0}, gM[3] = {0, 0, 0};
+  for (uint64_t s = 0; s < S; ++s) {
+    const int g = grp[s];
+    ord[s] = (uint32_t)gS[g];
+    off[s] = (uint32_t)gM[g];
+    gS[g] += 1;
+    gM[g] += sStart[s + 1] - sStart[s];
+  }
+
+  // ---- count fiber segments of the CSF group (fbr-split on the run grid) ----
+  std::vector<uint32_t> segOff[2];
+  uint64_t nSeg[2] = {0, 0};
+  for (int f = 0; f < NF; ++f) segOff[f].assign(S + 1, 0);
+#pragma omp parallel for schedule(dynamic, 512)
+  for (int64_t s = 0; s < (int64_t)S; ++s) {
+    if (grp[s] != kCsf) continue;
+    const size_t b = sStart[s], e = sStart[s + 1];
+    uint32_t c[2] = {0, 0};
+    for (size_t p = b; p < e; ++p) {
+      const bool cut = ((off[s] + (uint32_t)(p - b)) % L) == 0;
+      c[0] += cut || fresh(1, p);
+      if (NF == 2) c[1] += cut || fresh(2, p);
+    }
+    segOff[0][s + 1] = c[0];
+    if (NF == 2) segOff[1][s + 1] = c[1];
+  }
+  for (int f = 0; f < NF; ++f) {
+    uint64_t run = 0;
+    for (uint64_t s = 0; s < S; ++s) {
+      const uint32_t c = segOff[f][s + 1];
+      segOff[f][s] = (uint32_t)run;
+      run += c;
+    }
+    segOff[f][S] = (uint32_t)run;
+    nSeg[f] = run;
+  }
+
+  // ---- lay the arrays out in one blob ----
+  Layout lay;
+  for (int g = 0; g < 3; ++g) {
+    GroupFormat& G = out->g[g];
+    G.nnz = gM[g];
+    G.runs = (gM[g] + L - 1) / L;
+  }
+  {
+    GroupFormat& G = out->g[kCoo];
+    for (int l = 0; l < N; ++l) G.ind[l] = lay.add(G.nnz);
+    G.val = lay.add(G.nnz);
+  }
+  {
+    GroupFormat& G = out->g[kCsl];
+    G.n[0] = gS[kCsl];
+    G.ind[0] = lay.add(G.n[0] + 1);
+    G.ptr[0] = lay.add(G.n[0] + 1);
+    G.runFirst[0] = lay.add(G.runs + 1);
+    for (int l = 1; l < N; ++l) G.ind[l] = lay.add(G.nnz);
+    G.val = lay.add(G.nnz);
+  }
+  {
+    GroupFormat& G = out->g[kCsf];
+    G.n[0] = gS[kCsf];
+    for (int f = 0; f < NF; ++f) G.n[1 + f] = nSeg[f];
+    for (int l = 0; l < N - 1; ++l) {
+      G.ind[l] = lay.add(G.n[l] + 1);
+      G.ptr[l] = lay.add(G.n[l] + 1);
+      G.runFirst[l] = lay.add(G.runs + 1);
+    }
+    G.ind[N - 1] = lay.add(G.nnz);
+    G.val = lay.add(G.nnz);
+  }
+  const uint64_t ownedWords = (out->rows + 31) / 32;
+  out->ownedBits = lay.add(ownedWords);
+  out->blobBytes = lay.bytes;
+  void* mem = nullptr;
+  if (posix_memalign(&mem, kAlign, (size_t)lay.bytes) != 0 || !mem) {
+    *err = "out of host memory for the format arrays";
+    return HBCSF_ENOMEM;
+  }
+  out->blob = (uint8_t*)mem;
+  auto U32 = [&](const ArrayRef& r) { return (uint32_t*)(out->blob + r.off); };
+  uint32_t* owned = U32(out->ownedBits);
+  std::memset(owned, 0, ownedWords * 4);
+
+  GroupFormat& Go = out->g[kCoo];
+  GroupFormat& Gl = out->g[kCsl];
+  GroupFormat& Gc = out->g[kCsf];
+  uint32_t* cooInd[HBCSF_MAX_ORDER];
+  uint32_t* cslInd[HBCSF_MAX_ORDER];
+  uint32_t* csfInd[HBCSF_MAX_ORDER];
+  uint32_t* csfPtr[HBCSF_MAX_ORDER];
+  uint32_t* csfRun[HBCSF_MAX_ORDER];
+  for (int l = 0; l < N; ++l) {
+    cooInd[l] = U32(Go.ind[l]);
+    cslInd[l] = U32(Gl.ind[l]);
+    csfInd[l] = U32(Gc.ind[l]);
+    csfPtr[l] = l < N - 1 ? U32(Gc.ptr[l]) : nullptr;
+    csfRun[l] = l < N - 1 ? U32(Gc.runFirst[l]) : nullptr;
+  }
+  uint32_t* cooVal = U32(Go.val);
+  uint32_t* cslVal = U32(Gl.val);
+  uint32_t* csfVal = U32(Gc.val);
+  uint32_t* cslPtr = U32(Gl.ptr[0]);
+  uint32_t* cslRun = U32(Gl.runFirst[0]);
+
+  uint64_t sharedSlices = 0;
+#pragma omp parallel for schedule(dynamic, 512) reduction(+ : sharedSlices)
+  for (int64_t s = 0; s < (int64_t)S; ++s) {
+    const size_t b = sStart[s], e = sStart[s + 1];
+    const uint32_t n = (uint32_t)(e - b), a = off[s], o = ord[s];
+    const uint32_t root = idx(0, b);
+    const int g = grp[s];
+    bool own = true;
+    if (g == kCoo) {
+      for (int l = 0; l < N; ++l) cooInd[l][a] = idx(l, b);
+      cooVal[a] = V[b];
+    } else {
+      own = (a / L) == ((a + n - 1) / L);
+      uint32_t* run0 = g == kCsl ? cslRun : csfRun[0];
+      for (uint32_t r = (a + L - 1) / L; r <= (a + n - 1) / L; ++r) run0[r] = o;
+      if (g == kCsl) {
+        cslInd[0][o] = root | (own ? kOwnedBit : 0u);
+        cslPtr[o] = a;
+        for (size_t p = b; p < e; ++p) {
+          const uint32_t pos = a + (uint32_t)(p - b);
+          for (int l = 1; l < N; ++l) cslInd[l][pos] = idx(l, p);
+          cslVal[pos] = V[p];
+        }
+      } else {
+        csfInd[0][o] = root | (own ? kOwnedBit : 0u);
+        csfPtr[0][o] = a;
+        uint32_t f[2] = {segOff[0][s], NF == 2 ? segOff[1][s] : 0u};
+        for (size_t p = b; p < e; ++p) {
+          const uint32_t pos = a + (uint32_t)(p - b);
+          const bool cut = (pos % L) == 0;
+          for (int l = 1; l <= NF; ++l) {
+            if (cut || fresh(l, p)) {
+              csfInd[l][f[l - 1]] = idx(l, p);
+              csfPtr[l][f[l - 1]] = pos;
+              if (cut) csfRun[l][pos / L] = f[l - 1];
+              ++f[l - 1];
+            }
+          }
+          csfInd[N - 1][pos] = idx(N - 1, p);
+          csfVal[pos] = V[p];
+        }
+      }
+      if (!own) ++sharedSlices;
+    }
+    if (own) __atomic_fetch_or(&owned[root >> 5], 1u << (root & 31), __ATOMIC_RELAXED);
+  }
+  // sentinels and pads
+  cslInd[0][Gl.n[0]] = 0;
+  cslPtr[Gl.n[0]] = (uint32_t)Gl.nnz;
+  cslRun[Gl.runs] = (uint32_t)Gl.n[0];
+  for (int l = 0; l < N - 1; ++l) {
+    csfInd[l][Gc.n[l]] = 0;
+    csfPtr[l][Gc.n[l]] = (uint32_t)Gc.nnz;
+    csfRun[l][Gc.runs] = (uint32_t)Gc.n[l];
+  }
+
+  // ---- statistics ----
+  hbcsf_stats& st = out->stats;
+  std::memset(&st, 0, sizeof(st));
+  st.nnz = M;
+  st.slices = S;
+  for (int f = 0; f < NF; ++f) {
+    st.fibers[f] = fibNat[f];
+    st.segments[f] = nSeg[f];
+  }
+  for (int g = 0; g < 3; ++g) {
+    st.group_nnz[g] = gM[g];
+    st.group_slices[g] = gS[g];
+    st.runs[g] = out->g[g].runs;
+  }
+  st.shared_slices = sharedSlices;
+  st.words_coo = (uint64_t)N * M;
+  st.words_csf = 2 * S + M;
+  st.words_hbcsf = (uint64_t)N * gM[kCoo] + 2 * gS[kCsl] + (uint64_t)(N - 1) * gM[kCsl] + 2 * gS[kCsf] + gM[kCsf];
+  for (int f = 0; f < NF; ++f) {
+    st.words_csf += 2 * fibNat[f];
+    st.words_hbcsf += 2 * fibNatCsf[f];
+  }
+  for (int g = 0; g < 3; ++g) {
+    const GroupFormat& G = out->g[g];
+    uint64_t words = G.val.count;
+    for (int l = 0; l < N; ++l) {
+      if (G.ind[l].present) words += G.ind[l].count;
+      if (G.ptr[l].present) words += G.ptr[l].count;
+      if (G.runFirst[l].present) words += G.runFirst[l].count;
+    }
+    st.stream_bytes[g] = G.nnz ? words * 4 : 0;
+  }
+  {
+    uint64_t cnt = 0;
+#pragma omp parallel for schedule(static) reduction(+ : cnt)
+    for (int64_t w = 0; w < (int64_t)ownedWords; ++w) cnt += (uint64_t)__builtin_popcount(owned[w]);
+    st.owned_rows = cnt;
+  }
+  {
+    // distinct factor rows each group gathers, per tree level
+    std::vector<uint8_t> seen;
+    for (int g = 0; g < 3; ++g) {
+      const GroupFormat& G = out->g[g];
+      for (int l = 1; l < N; ++l) {
+        const uint32_t* a = U32(G.ind[l]);
+        const uint64_t cnt = (g == kCsf && l < N - 1) ? G.n[l] : G.nnz;
+        seen.assign(dims[lv[l]], 0);
+        uint8_t* sp = seen.data();
+#pragma omp parallel for schedule(static)
+        for (int64_t t = 0; t < (int64_t)cnt; ++t) __atomic_store_n(&sp[a[t]], (uint8_t)1, __ATOMIC_RELAXED);
+        uint64_t d = 0;
+#pragma omp parallel for schedule(static) reduction(+ : d)
+        for (int64_t t = 0; t < (int64_t)seen.size(); ++t) d += sp[t];
+        st.distinct_rows[g][l] = d;
+      }
+      st.distinct_rows[g][0] = gS[g];
+    }
+  }
+  {
+    uint64_t fl = (uint64_t)(N - 1) * gM[kCoo] + (uint64_t)N * gM[kCsl];
+    uint64_t csf = gM[kCsf];
+    for (int f = 0; f < NF; ++f) csf += nSeg[f];
+    st.flops_real = fl + 2 * csf;
+  }
+  for (int l = 0; l < N; ++l) st.level_mode[l] = (uint32_t)lv[l];
+  st.fiber_threshold = L;
+  st.build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_begin).count();
+  return HBCSF_OK;
+}
+
+}  // namespace
+
+int build_mode(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* const* inds,
+               const float* vals, const hbcsf_opts& opts, int mode, ModeFormat* out,
+               std::string* err) {
+  int total = 0;
+  for (int m = 0; m < order; ++m) total += bits_for(dims[m]);
+  try {
+    if (total <= 64)
+      return build_mode_t<uint64_t>(order, dims, nnz, inds, vals, opts, mode, out, err);
+    return build_mode_t<unsigned __int128>(order, dims, nnz, inds, vals, opts, mode, out, err);
+  } catch (const std::bad_alloc&) {
+    *err = "out of host memory while building the format";
+    return HBCSF_ENOMEM;
+  } catch (...) {
+    *err = "unexpected failure while building the format";
+    return HBCSF_EINVAL;
+  }
+}
+
+}  // namespace hbcsf

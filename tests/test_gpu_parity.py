@@ -1,0 +1,152 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same inputs."""
+import numpy as np
+import pytest
+
+import gpu_util as GU
+from paper_1904_03329_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+
+
+def _skewed(rng, dims, nnz, a=1.3):
+    inds = []
+    for d in dims:
+        w = 1.0 / np.arange(1, d + 1) ** a
+        inds.append(rng.permutation(d)[rng.choice(d, size=nnz, p=w / w.sum())].astype(np.uint32))
+    key = np.zeros(nnz, dtype=np.int64)
+    for d, x in zip(dims, inds):
+        key = key * d + x
+    _, first = np.unique(key, return_index=True)
+    first = rng.permutation(first)
+    return [x[first] for x in inds], rng.uniform(-1, 1, size=first.shape[0]).astype(np.float32)
+
+
+def _factors(rng, dims, rank):
+    return [rng.uniform(0, 1, size=(d, rank)).astype(np.float32) for d in dims]
+
+
+def _check_all_modes(oracle, dims, inds, vals, facs, what, **kw):
+    outs, stats = GU.gpu_mttkrp_all_modes(dims, inds, vals, facs, **kw)
+    for mode, got in enumerate(outs):
+        want = oracle.mttkrp(dims, inds, vals, facs, mode)
+        GU.assert_close(got, want, f"{what} mode {mode}")
+    return stats
+
+
+def test_cfg1_every_element(oracle, synth):
+    t, facs, rank = synth.workload("cfg1")
+    print("cfg1", t.dims, t.nnz, rank, flush=True)
+    _check_all_modes(oracle, t.dims, t.inds, t.vals, facs, "cfg1")
+
+
+@pytest.mark.parametrize("rank", [8, 16, 32, 64, 128])
+@pytest.mark.parametrize("dims,nnz", [((3000, 700, 90), 60_000), ((900, 300, 40, 25), 50_000)])
+def test_ranks_and_orders(oracle, dims, nnz, rank):
+    rng = np.random.default_rng(rank * 10 + len(dims))
+    inds, vals = _skewed(rng, dims, nnz)
+    facs = _factors(rng, dims, rank)
+    print("ranks_and_orders", dims, vals.shape[0], rank, flush=True)
+    stats = _check_all_modes(oracle, dims, inds, vals, facs, f"R={rank} order={len(dims)}")
+    assert all(s["group_nnz"][2] > 0 for s in stats)
+
+
+@pytest.mark.parametrize("opts", [dict(fiber_threshold=8), dict(fiber_threshold=64), dict(group_mask=4),
+                                  dict(group_mask=1), dict(group_mask=2), dict(mode_order_policy=1),
+                                  dict(mode_order_policy=2), dict(tune_ts=256), dict(tune_ts=100_000)])
+@pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000)])
+def test_build_options_do_not_change_the_result(oracle, dims, nnz, opts):
+    rng = np.random.default_rng(len(dims) + 7)
+    inds, vals = _skewed(rng, dims, nnz)
+    facs = _factors(rng, dims, 32)
+    print("options", dims, vals.shape[0], opts, flush=True)
+    _check_all_modes(oracle, dims, inds, vals, facs, f"{opts}", **opts)
+
+
+def test_hypersparse_groups(oracle, synth):
+    """Long-tail tensor: most slices hold one or two nonzeros, so the COO and CSL groups carry work."""
+    t = synth.tensor((400_000, 400_000, 100), 600_000, (1.05, 1.05, 0.0), seed=77)
+    facs = synth.factors(t.dims, 32, seed=77)
+    print("hypersparse", t.dims, t.nnz, flush=True)
+    stats = _check_all_modes(oracle, t.dims, t.inds, t.vals, facs, "hypersparse")
+    assert stats[0]["group_nnz"][0] > 0 and stats[0]["group_nnz"][1] > 0 and stats[0]["group_nnz"][2] > 0
+
+
+def test_degenerate_shapes(oracle):
+    rng = np.random.default_rng(31)
+    # one heavy slice only (every partial row merged with atomics), ragged tail
+    n = 10_007
+    dims = (3, 50, 4000)
+    inds = [np.full(n, 1, np.uint32), rng.integers(0, 50, n).astype(np.uint32), rng.integers(0, 4000, n).astype(np.uint32)]
+    vals = rng.uniform(-1, 1, n).astype(np.float32)
+    facs = _factors(rng, dims, 32)
+    print("one heavy slice", flush=True)
+    _check_all_modes(oracle, dims, inds, vals, facs, "one heavy slice")
+    # every slice a single nonzero (COO group only) and empty rows in between
+    dims = (5000, 7, 9)
+    rows = rng.permutation(5000)[:1234].astype(np.uint32)
+    inds = [rows, rng.integers(0, 7, 1234).astype(np.uint32), rng.integers(0, 9, 1234).astype(np.uint32)]
+    vals = rng.uniform(-1, 1, 1234).astype(np.float32)
+    facs = _factors(rng, dims, 8)
+    print("singleton slices", flush=True)
+    stats = _check_all_modes(oracle, dims, inds, vals, facs, "singleton slices")
+    assert stats[0]["group_nnz"] == [1234, 0, 0]
+    # a single nonzero; and an empty tensor (the result must be all zeros, not stale memory)
+    print("single nonzero / empty", flush=True)
+    _check_all_modes(oracle, (4, 5, 6), [np.array([3], np.uint32), np.array([0], np.uint32), np.array([5], np.uint32)],
+                     np.array([0.5], np.float32), _factors(rng, (4, 5, 6), 16), "single nonzero")
+    outs, _ = GU.gpu_mttkrp_all_modes((40, 5, 6, 3), [np.zeros(0, np.uint32)] * 4, np.zeros(0, np.float32),
+                                      _factors(rng, (40, 5, 6, 3), 32))
+    assert all(np.array_equal(o, np.zeros_like(o)) for o in outs)
+    # duplicate coordinates act as separate nonzeros
+    dims = (30, 20, 10)
+    inds = [rng.integers(0, d, 5000).astype(np.uint32) for d in dims]
+    vals = rng.uniform(-1, 1, 5000).astype(np.float32)
+    print("duplicates", flush=True)
+    _check_all_modes(oracle, dims, inds, vals, _factors(rng, dims, 32), "duplicates")
+
+
+def test_nan_and_inf_propagate_to_their_rows_only(oracle):
+    rng = np.random.default_rng(37)
+    dims = (200, 30, 20)
+    inds, vals = _skewed(rng, dims, 4000)
+    vals = vals.copy()
+    vals[10] = np.nan
+    vals[20] = np.inf
+    facs = _factors(rng, dims, 32)
+    import torch
+    from paper_1904_03329_amd import HbcsfTensor
+    t = HbcsfTensor(dims, inds, vals).to_device()
+    out = t.mttkrp(0, [torch.from_numpy(f).cuda() for f in facs]).cpu().numpy()
+    bad_rows = {int(inds[0][10]), int(inds[0][20])}
+    for r in range(dims[0]):
+        assert np.all(np.isfinite(out[r])) == (r not in bad_rows)
+    t.close()
+
+
+def test_repeated_calls_overwrite(oracle):
+    rng = np.random.default_rng(41)
+    dims = (800, 90, 40)
+    inds, vals = _skewed(rng, dims, 30_000)
+    facs = _factors(rng, dims, 32)
+    import torch
+    from paper_1904_03329_amd import HbcsfTensor
+    t = HbcsfTensor(dims, inds, vals).to_device()
+    d = [torch.from_numpy(f).cuda() for f in facs]
+    out = torch.full((dims[1], 32), 123.0, device="cuda")
+    want = oracle.mttkrp(dims, inds, vals, facs, 1)
+    for _ in range(3):
+        t.mttkrp(1, d, out)
+        torch.cuda.synchronize()
+        GU.assert_close(out.cpu().numpy(), want, "repeat")
+    # a side stream works too
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        out2 = t.mttkrp(1, d)
+    s.synchronize()
+    GU.assert_close(out2.cpu().numpy(), want, "side stream")
+    # profiling hooks report the four kernels
+    B.tune(t.handle, B.TUNE_PROFILE, 1)
+    t.mttkrp(1, d, out)
+    ms = B.last_kernel_ms(t.handle)
+    assert len(ms) == 4 and ms[0] > 0 and ms[3] > 0
+    t.close()
