@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-MTTKRP hot path on one MI355X.
+
+One step = mode-n MTTKRP for every mode n of one synthetic tensor (output definition, COO-group,
+CSL-group and B-CSF-group kernels per mode), inputs resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5]
+
+GFLOP/s uses 3*R*nnz floating-point operations per mode (the COO operation count of Section
+III-A), R = 32.  The roofline entry is for the B-CSF-group kernel and prices its algorithmic
+bytes (its format arrays once + each distinct factor row it gathers once + each output row it
+writes once) against the 8 TB/s HBM peak.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+KERNELS = ("define", "coo", "csl", "csf")
+
+# HBM bytes per B-CSF-kernel launch (mean over the modes) measured with rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size; see profiles/.  None = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def algorithmic_bytes(st: dict, rank: int, order: int) -> dict:
+    """Algorithmic HBM bytes of one mode's kernels from the builder's statistics."""
+    row = 4 * rank
+    rows_total = st["rows"]
+    out = {}
+    for g, name in enumerate(("coo", "csl", "csf")):
+        if st["group_nnz"][g] == 0:
+            out[name] = 0
+            continue
+        gathered = sum(st["distinct_rows"][g][l] for l in range(1, order))
+        out[name] = st["stream_bytes"][g] + row * gathered + row * st["group_slices"][g]
+    # define kernel: the owned-row bitmap once + every row no kernel stores (zero fill)
+    out["define"] = 4 * ((rows_total + 31) // 32) + row * (rows_total - st["owned_rows"])
+    # rows merged with atomics are counted once in their kernel above and once as zero fill;
+    # take the zero fill out again so that the dense output is counted exactly once in the total
+    out["total"] = sum(out[k] for k in KERNELS) - row * st["shared_slices"]
+    return out
+
+
+def calibrate(torch, log) -> int:
+    """Attainable bandwidth of plain streaming kernels, and a known-size copy for counter scaling."""
+    n = 1 << 28  # 2^28 floats = 1 GiB
+    src = torch.ones(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    res = {}
+    for name, fn, nbytes in (("copy_1GiB", lambda: dst.copy_(src), 2 * 4 * n),
+                             ("fill_1GiB", lambda: dst.zero_(), 4 * n),
+                             ("read_1GiB", lambda: src.sum(), 4 * n)):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 10
+        res[name] = {"ms": round(dt * 1e3, 4), "GB/s": round(nbytes / dt / 1e9, 1), "bytes": nbytes}
+        log(f"[calibrate] {name}: {res[name]}")
+    print(json.dumps({"calibrate": res}), flush=True)
+    return 0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5 (default: the largest, cfg5)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fiber-threshold", type=int, default=0)
+    ap.add_argument("--slice-threshold", type=int, default=0)
+    ap.add_argument("--mode-order-policy", type=int, default=0)
+    ap.add_argument("--group-mask", type=int, default=0)
+    ap.add_argument("--waves-per-cu", type=int, default=0)
+    ap.add_argument("--kernel-steps", type=int, default=0)
+    ap.add_argument("--calibrate", action="store_true",
+                    help="time a plain 1 GiB device copy, fill and read instead of the benchmark "
+                         "(also the known-size kernel that scales the rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import synthgen
+    from paper_1904_03329_amd import HbcsfTensor, binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    if args.calibrate:
+        return calibrate(torch, log)
+
+    w = synthgen.WORKLOADS[args.workload]
+    t0 = time.time()
+    t, facs, rank = synthgen.workload(args.workload)
+    gen_s = time.time() - t0
+    log(f"[bench] {args.workload}: dims={t.dims} nnz={t.nnz} draws={t.draws} R={rank} generated in {gen_s:.1f}s")
+    t0 = time.time()
+    ht = HbcsfTensor(t.dims, t.inds, t.vals, fiber_threshold=args.fiber_threshold,
+                     slice_threshold=args.slice_threshold, mode_order_policy=args.mode_order_policy,
+                     group_mask=args.group_mask)
+    build_s = time.time() - t0
+    t0 = time.time()
+    ht.to_device()
+    upload_s = time.time() - t0
+    order = t.order
+    stats = []
+    for m in range(order):
+        st = ht.stats(m)
+        st["rows"] = t.dims[m]
+        stats.append(st)
+    log(f"[bench] format built in {build_s:.1f}s, uploaded {B.device_bytes(ht.handle) / 1e9:.2f} GB in {upload_s:.1f}s")
+    dfacs = [torch.from_numpy(f).cuda() for f in facs]
+    outs = [torch.empty((t.dims[m], rank), dtype=torch.float32, device="cuda") for m in range(order)]
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for m in range(order):
+            ht.mttkrp(m, dfacs, outs[m])
+
+    if args.waves_per_cu:
+        B.tune(ht.handle, B.TUNE_WAVES_PER_CU, args.waves_per_cu)
+    if args.kernel_steps:
+        B.tune(ht.handle, B.TUNE_STEPS, args.kernel_steps)
+    B.tune(ht.handle, B.TUNE_PROFILE, order * args.steps)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.tune(ht.handle, B.TUNE_PROFILE, order * args.steps)  # restart the ring: timed calls only
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_begin
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    # per-kernel durations of every timed call, from the HIP events the library recorded on the
+    # launch stream inside the timed region
+    kms = np.zeros((args.steps, order, 4))
+    for s in range(args.steps):
+        for m in range(order):
+            back = (args.steps - 1 - s) * order + (order - 1 - m)
+            kms[s, m] = B.kernel_ms(ht.handle, back)
+    kmean = kms.mean(axis=0)  # [mode][kernel]
+
+    flops_mode = 3.0 * rank * t.nnz
+    value = flops_mode * order / (ms_per_step * 1e-3) / 1e9
+    per_mode = []
+    csf_bytes, csf_ms, csf_launches = 0.0, 0.0, 0
+    for m in range(order):
+        ab = algorithmic_bytes(stats[m], rank, order)
+        tot_ms = float(kmean[m].sum())
+        entry = {
+            "mode": m,
+            "level_modes": stats[m]["level_mode"][:order],
+            "ms": round(tot_ms, 4),
+            "gflops_3Rnnz": round(flops_mode / (tot_ms * 1e-3) / 1e9, 1),
+            "model_bytes": ab["total"],
+            "hbm_gbs_model": round(ab["total"] / (tot_ms * 1e-3) / 1e9, 1),
+            "hbm_frac": round(ab["total"] / (tot_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "kernel_ms": {k: round(float(kmean[m][i]), 4) for i, k in enumerate(KERNELS)},
+            "kernel_model_bytes": {k: ab[k] for k in KERNELS},
+            "group_nnz": stats[m]["group_nnz"],
+            "slices": stats[m]["slices"],
+            "segments": stats[m]["segments"][: order - 2],
+            "shared_slices": stats[m]["shared_slices"],
+            "real_gflops": round(stats[m]["flops_real"] * rank / (tot_ms * 1e-3) / 1e9, 1),
+        }
+        if order == 4:
+            entry["gflops_4Rnnz"] = round(4.0 * rank * t.nnz / (tot_ms * 1e-3) / 1e9, 1)
+        per_mode.append(entry)
+        if stats[m]["group_nnz"][2] > 0:
+            csf_bytes += ab["csf"]
+            csf_ms += float(kmean[m][3])
+            csf_launches += 1
+        log(f"[bench] mode {m}: {json.dumps(entry)}")
+
+    achieved = csf_bytes / (csf_ms * 1e-3) / 1e9 if csf_ms > 0 else 0.0
+    roofline = {
+        "kernel": f"csf_group_kernel<{rank // 4},{order}>",
+        "bound": "hbm",
+        "achieved": round(achieved, 1),
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": MEASURED_TRAFFIC.get(args.workload),
+        "bytes_per_launch": round(csf_bytes / max(csf_launches, 1)),
+        "ms_per_launch": round(csf_ms / max(csf_launches, 1), 4),
+        "launches_per_step": csf_launches,
+    }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle  # test infrastructure: used here for the reported CPU baseline only
+
+        sample = min(t.nnz, 12_000_000)
+        si = [x[:sample] for x in t.inds]
+        sv = t.vals[:sample]
+        t0 = time.perf_counter()
+        for m in range(order):
+            oracle.mttkrp(t.dims, si, sv, facs, m)
+        cpu_s = time.perf_counter() - t0
+        cpu_baseline = {
+            "value": round(3.0 * rank * sample * order / cpu_s / 1e9, 3),
+            "unit": "GFLOP/s",
+            "cores": 1,
+            "kind": "oracle",
+            "sample": f"first {sample} of {t.nnz} nonzeros (generator order), all {order} modes, {cpu_s:.1f}s",
+        }
+        log(f"[bench] cpu baseline: {cpu_baseline}")
+
+    line = {
+        "metric": "sparse MTTKRP GFLOP/s (3*R*nnz per mode, all modes) at rank R=32",
+        "value": round(value, 1),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{args.workload}: order {order}, dims {'x'.join(str(d) for d in t.dims)}, nnz {t.nnz}, "
+                        f"Zipf alphas {list(w.alpha)}, R={rank}",
+            "fiber_threshold": stats[0]["fiber_threshold"],
+            "step": f"MTTKRP on all {order} modes",
+            "hbm_gbs_model_all_modes": round(sum(p["model_bytes"] for p in per_mode) / (ms_per_step * 1e-3) / 1e9, 1),
+            "build_seconds": round(build_s, 2),
+            "upload_seconds": round(upload_s, 2),
+            "generate_seconds": round(gen_s, 2),
+        },
+        "per_mode": per_mode,
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(line), flush=True)
+    ht.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

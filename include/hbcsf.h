@@ -43,7 +43,7 @@ typedef struct hbcsf_tensor hbcsf_tensor; /* opaque, owned by the library, freed
 typedef struct hbcsf_opts {
   uint32_t fiber_threshold;   /* T_f of fbr-split (Section IV-B, VI-B): no fiber segment holds more
                                  than T_f nonzeros.  Cuts fall on multiples of T_f in a group's
-                                 nonzero stream.  Multiple of 8, 8..64.  Default 32.               */
+                                 nonzero stream.  8, 16, 32 or 64.  Default 64.                     */
   uint32_t slice_threshold;   /* T_s of slc-split (Section IV-A): nonzeros one wavefront works
                                  through before it merges its partial rows; a slice of n nonzeros
                                  is shared by at most ceil(n/T_s)+1 wavefronts.  0 = sized from
@@ -101,7 +101,7 @@ int hbcsf_device_bytes(const hbcsf_tensor *t, uint64_t *bytes);
 int hbcsf_upload(hbcsf_tensor *t, void *device_arena, uint64_t bytes, void *hip_stream);
 
 /* Mode-`mode` (0-based) MTTKRP, asynchronous on hip_stream.
- *   rank     4, 8, 16, 32, 64 or 128.
+ *   rank     8, 16, 32, 64 or 128.
  *   factors  host array of `order` device pointers; factors[m] is [dims[m]][rank] row-major,
  *            16-byte aligned; factors[mode] is ignored (may be NULL).
  *   out      device [dims[mode]][rank], 16-byte aligned, OVERWRITTEN: every row is defined
@@ -131,13 +131,18 @@ int hbcsf_host_array(const hbcsf_tensor *t, int mode, int group, int level, int 
 
 /* Tuning knobs that need no rebuild.  key: HBCSF_TUNE_*. */
 #define HBCSF_TUNE_SLICE_THRESHOLD 0 /* T_s, nonzeros per wavefront span; 0 = automatic */
-#define HBCSF_TUNE_PROFILE         1 /* 1 = bracket each kernel with HIP events          */
+#define HBCSF_TUNE_PROFILE         1 /* n > 0: bracket the kernels of each call with HIP events and
+                                        keep the last n calls' event sets; 0 = off              */
+#define HBCSF_TUNE_WAVES_PER_CU     2 /* wavefront spans launched per compute unit when T_s is
+                                        automatic (default 128)                                 */
+#define HBCSF_TUNE_STEPS            3 /* gathers a lane group keeps in flight: 4 or 8 (default 4;
+                                        ranks other than 32 always use 8)                       */
 int hbcsf_tune(hbcsf_tensor *t, int key, uint64_t value);
 
-/* With HBCSF_TUNE_PROFILE on: milliseconds of the four kernels of the last hbcsf_mttkrp call
- * on this handle (define, COO, CSL, CSF; 0 for a kernel that was not launched).  Synchronises
- * with the last call's events. */
-int hbcsf_last_kernel_ms(hbcsf_tensor *t, float ms[4]);
+/* With HBCSF_TUNE_PROFILE on: milliseconds of the four kernels (define, COO, CSL, CSF; 0 for a
+ * kernel that was not launched) of the hbcsf_mttkrp call made `calls_back` profiled calls ago
+ * on this handle (0 = the last one).  Waits for that call's last event. */
+int hbcsf_kernel_ms(hbcsf_tensor *t, uint32_t calls_back, float ms[4]);
 
 void hbcsf_free(hbcsf_tensor *t);
 

@@ -16,13 +16,13 @@ LIB_PATH = os.path.join(_HERE, "libhbcsf.so")
 
 HBCSF_MAX_ORDER = 4
 ARR_IND, ARR_PTR, ARR_VAL, ARR_RUNFIRST, ARR_OWNED_BITS = 0, 1, 2, 3, 4
-TUNE_SLICE_THRESHOLD, TUNE_PROFILE = 0, 1
+TUNE_SLICE_THRESHOLD, TUNE_PROFILE, TUNE_WAVES_PER_CU, TUNE_STEPS = 0, 1, 2, 3
 GROUP_COO, GROUP_CSL, GROUP_CSF = 0, 1, 2
 OWNED_BIT = 0x80000000
 
 EXPORTS = (
     "hbcsf_build_format", "hbcsf_device_bytes", "hbcsf_upload", "hbcsf_mttkrp", "hbcsf_get_stats",
-    "hbcsf_host_array", "hbcsf_tune", "hbcsf_last_kernel_ms", "hbcsf_free", "hbcsf_strerror",
+    "hbcsf_host_array", "hbcsf_tune", "hbcsf_kernel_ms", "hbcsf_free", "hbcsf_strerror",
     "hbcsf_last_error",
 )
 
@@ -76,8 +76,8 @@ def lib():
         L.hbcsf_host_array.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(u64)]
         L.hbcsf_tune.restype = i32
         L.hbcsf_tune.argtypes = [vp, i32, u64]
-        L.hbcsf_last_kernel_ms.restype = i32
-        L.hbcsf_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4)]
+        L.hbcsf_kernel_ms.restype = i32
+        L.hbcsf_kernel_ms.argtypes = [vp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_float * 4)]
         L.hbcsf_free.restype = None
         L.hbcsf_free.argtypes = [vp]
         L.hbcsf_strerror.restype = ctypes.c_char_p
@@ -160,9 +160,10 @@ def tune(h, key: int, value: int):
     _check(lib().hbcsf_tune(h, key, value))
 
 
-def last_kernel_ms(h):
+def kernel_ms(h, calls_back: int = 0):
+    """Milliseconds of the define / COO / CSL / CSF kernels of a profiled call."""
     ms = (ctypes.c_float * 4)()
-    _check(lib().hbcsf_last_kernel_ms(h, ctypes.byref(ms)))
+    _check(lib().hbcsf_kernel_ms(h, calls_back, ctypes.byref(ms)))
     return [float(x) for x in ms]
 
 

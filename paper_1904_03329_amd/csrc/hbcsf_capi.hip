@@ -7,6 +7,7 @@
 #include <memory>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "hbcsf.h"
 #include "hbcsf_device.h"
@@ -25,11 +26,16 @@ struct hbcsf_tensor {
   bool uploaded = false;
   int numCU = 256;
   uint64_t sliceThreshold = 0;
-  bool profile = false;
-  bool eventsMade = false;
-  bool eventsValid = false;
-  hipEvent_t ev[5];
-  bool launched[4] = {false, false, false, false};
+  uint64_t wavesPerCU = 0;   // launch sizing override, 0 = default
+  int steps = 4;             // records in flight per lane group
+  // profiling: a ring of event sets, one per hbcsf_mttkrp call
+  struct EventSet {
+    hipEvent_t ev[5];
+    bool launched[4] = {false, false, false, false};
+    bool valid = false;
+  };
+  std::vector<EventSet> ring;
+  uint64_t calls = 0;  // profiled calls so far
 };
 
 namespace {
@@ -68,7 +74,7 @@ int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint
   }
   hbcsf_opts o{};
   if (opts) o = *opts;
-  if (o.fiber_threshold == 0) o.fiber_threshold = 32;
+  if (o.fiber_threshold == 0) o.fiber_threshold = 64;
   if (!pow2_in(o.fiber_threshold, 8, 64)) return fail(HBCSF_EINVAL, "fiber_threshold must be 8, 16, 32 or 64");
   if (o.mode_order_policy > 2) return fail(HBCSF_EINVAL, "mode_order_policy must be 0, 1 or 2");
   if (o.group_mask > 4) return fail(HBCSF_EINVAL, "group_mask must be 0..4");
@@ -149,15 +155,11 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
   const uint8_t* base = t->arena + f.devOffset;
   hipError_t e;
 
-  if (t->profile) {
-    if (!t->eventsMade) {
-      for (int i = 0; i < 5; ++i) {
-        e = hipEventCreate(&t->ev[i]);
-        if (e != hipSuccess) return fail_hip(e, "hipEventCreate");
-      }
-      t->eventsMade = true;
-    }
-    e = hipEventRecord(t->ev[0], s);
+  hbcsf_tensor::EventSet* es = nullptr;
+  if (!t->ring.empty()) {
+    es = &t->ring[t->calls % t->ring.size()];
+    es->valid = false;
+    e = hipEventRecord(es->ev[0], s);
     if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
   }
 
@@ -170,14 +172,16 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
     if (blocks == 0) blocks = 1;
     e = launch_define(out, (const uint32_t*)(base + f.ownedBits.off), f.rows, G, (uint32_t)blocks, s);
     if (e != hipSuccess) return fail_hip(e, "launch of the output-definition kernel");
-    t->launched[0] = true;
-    if (t->profile) (void)hipEventRecord(t->ev[1], s);
+    if (es) {
+      es->launched[0] = true;
+      (void)hipEventRecord(es->ev[1], s);
+    }
   }
 
   // 2. the three group kernels (execute step of Algorithm "HB-CSF-MTTKRP")
   for (int g = 0; g < 3; ++g) {
     const GroupFormat& gf = f.g[g];
-    t->launched[1 + g] = false;
+    bool launched = false;
     if (gf.nnz > 0) {
       GroupArgs a;
       std::memset(&a, 0, sizeof(a));
@@ -214,7 +218,7 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
         if (t->sliceThreshold) {
           upw = t->sliceThreshold / ((uint64_t)NG * L);
         } else {
-          const uint64_t target = (uint64_t)t->numCU * 32;
+          const uint64_t target = (uint64_t)t->numCU * (t->wavesPerCU ? t->wavesPerCU : 128);
           upw = (a.nUnits + target - 1) / target;
         }
         if (upw == 0) upw = 1;
@@ -222,13 +226,22 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
         const uint64_t waves = (a.nUnits + upw - 1) / upw;
         blocks = round_up8((waves + wpb - 1) / wpb);
       }
-      e = launch_group(g, N, G, a, blocks, threads, lds, s);
+      bool wide = false;
+      for (int l = 1; l < N; ++l)
+        wide = wide || t->dims[f.levelMode[l]] * (uint64_t)rank * 4ull >= (1ull << 32);
+      e = launch_group(g, N, G, t->steps, wide, a, blocks, threads, lds, s);
       if (e != hipSuccess) return fail_hip(e, "launch of a group kernel");
-      t->launched[1 + g] = true;
+      launched = true;
     }
-    if (t->profile) (void)hipEventRecord(t->ev[2 + g], s);
+    if (es) {
+      es->launched[1 + g] = launched;
+      (void)hipEventRecord(es->ev[2 + g], s);
+    }
   }
-  t->eventsValid = t->profile;
+  if (es) {
+    es->valid = true;
+    ++t->calls;
+  }
   return HBCSF_OK;
 }
 
@@ -268,22 +281,47 @@ int hbcsf_tune(hbcsf_tensor* t, int key, uint64_t value) {
     return HBCSF_OK;
   }
   if (key == HBCSF_TUNE_PROFILE) {
-    t->profile = value != 0;
-    t->eventsValid = false;
+    if (value > 65536) return fail(HBCSF_EINVAL, "at most 65536 profiled calls are kept");
+    for (auto& es : t->ring)
+      for (int i = 0; i < 5; ++i) (void)hipEventDestroy(es.ev[i]);
+    t->ring.clear();
+    t->calls = 0;
+    t->ring.resize((size_t)value);
+    for (auto& es : t->ring)
+      for (int i = 0; i < 5; ++i) {
+        hipError_t e = hipEventCreate(&es.ev[i]);
+        if (e != hipSuccess) {
+          t->ring.clear();
+          return fail_hip(e, "hipEventCreate");
+        }
+      }
+    return HBCSF_OK;
+  }
+  if (key == HBCSF_TUNE_WAVES_PER_CU) {
+    if (value > 1024) return fail(HBCSF_EINVAL, "waves per CU must be at most 1024");
+    t->wavesPerCU = value;
+    return HBCSF_OK;
+  }
+  if (key == HBCSF_TUNE_STEPS) {
+    if (value != 4 && value != 8) return fail(HBCSF_EINVAL, "steps must be 4 or 8");
+    t->steps = (int)value;
     return HBCSF_OK;
   }
   return fail(HBCSF_EINVAL, "unknown tuning key");
 }
 
-int hbcsf_last_kernel_ms(hbcsf_tensor* t, float ms[4]) {
+int hbcsf_kernel_ms(hbcsf_tensor* t, uint32_t calls_back, float ms[4]) {
   if (!t || !ms) return fail(HBCSF_EINVAL, "null argument");
-  if (!t->eventsValid) return fail(HBCSF_ESTATE, "no profiled hbcsf_mttkrp call to report");
-  hipError_t e = hipEventSynchronize(t->ev[4]);
+  if (t->ring.empty() || calls_back >= t->ring.size() || calls_back >= t->calls)
+    return fail(HBCSF_ESTATE, "no profiled hbcsf_mttkrp call that far back");
+  const hbcsf_tensor::EventSet& es = t->ring[(t->calls - 1 - calls_back) % t->ring.size()];
+  if (!es.valid) return fail(HBCSF_ESTATE, "that call did not complete its launches");
+  hipError_t e = hipEventSynchronize(es.ev[4]);
   if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
   for (int i = 0; i < 4; ++i) {
     ms[i] = 0.f;
-    if (!t->launched[i]) continue;
-    e = hipEventElapsedTime(&ms[i], t->ev[i], t->ev[i + 1]);
+    if (!es.launched[i]) continue;
+    e = hipEventElapsedTime(&ms[i], es.ev[i], es.ev[i + 1]);
     if (e != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
   }
   return HBCSF_OK;
@@ -291,8 +329,8 @@ int hbcsf_last_kernel_ms(hbcsf_tensor* t, float ms[4]) {
 
 void hbcsf_free(hbcsf_tensor* t) {
   if (!t) return;
-  if (t->eventsMade)
-    for (int i = 0; i < 5; ++i) (void)hipEventDestroy(t->ev[i]);
+  for (auto& es : t->ring)
+    for (int i = 0; i < 5; ++i) (void)hipEventDestroy(es.ev[i]);
   delete t;
 }
 

@@ -24,9 +24,11 @@ struct GroupArgs {
   uint32_t unitsPerWave;        // contiguous units one wavefront works through
 };
 
-// kind: KernelKind; order 3 or 4; G = rank / 4 lanes per factor row (2, 4, 8, 16 or 32).
-hipError_t launch_group(int kind, int order, int G, const GroupArgs& a, uint32_t blocks,
-                        uint32_t threads, size_t ldsBytes, hipStream_t s);
+// kind: KernelKind; order 3 or 4; G = rank / 4 lanes per factor row (2, 4, 8, 16 or 32);
+// steps = records a lane group keeps in flight (4 or 8); wide = some gathered factor matrix
+// is 4 GiB or larger (64-bit row addressing).
+hipError_t launch_group(int kind, int order, int G, int steps, bool wide, const GroupArgs& a,
+                        uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s);
 
 hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, int G,
                          uint32_t blocks, hipStream_t s);

@@ -92,7 +92,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
                  std::string* err) {
   const auto t_begin = std::chrono::steady_clock::now();
   const int N = order;
-  const uint32_t L = opts.fiber_threshold ? opts.fiber_threshold : 32;
+  const uint32_t L = opts.fiber_threshold ? opts.fiber_threshold : 64;
   const uint32_t gmask = opts.group_mask == 0 ? 3u : (opts.group_mask & 3u);
   const bool cooOn = gmask & 1u, cslOn = gmask & 2u;
 

@@ -41,7 +41,7 @@ struct GroupFormat {
 struct ModeFormat {
   int order = 0;
   int mode = 0;
-  uint32_t L = 32;                 // run length = fiber threshold T_f
+  uint32_t L = 64;                 // run length = fiber threshold T_f
   int levelMode[HBCSF_MAX_ORDER] = {0, 0, 0, 0};
   uint64_t rows = 0;               // dims[mode]
   GroupFormat g[3];

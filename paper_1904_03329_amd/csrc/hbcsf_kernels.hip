@@ -27,13 +27,19 @@ namespace hbcsf {
 
 namespace {
 
-constexpr int kSteps = 8;  // records in flight per lane group
 
 __device__ __forceinline__ float4 f4zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
 
-template <int G>
+// WIDE = false: the factor matrix is smaller than 4 GiB, so a 32-bit byte offset from a
+// scalar base is enough (one VALU instruction per gather); WIDE = true: 64-bit arithmetic.
+template <int G, bool WIDE>
 __device__ __forceinline__ float4 row_load(const float* __restrict__ base, uint32_t row, int c) {
-  return *reinterpret_cast<const float4*>(base + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c)));
+  if (WIDE) {
+    return *reinterpret_cast<const float4*>(base + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c)));
+  } else {
+    const uint32_t off = row * (uint32_t)(16 * G) + (uint32_t)(16 * c);
+    return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(base) + off);
+  }
 }
 
 template <int G>
@@ -103,6 +109,200 @@ __device__ __forceinline__ uint32_t mark_of_slice(uint32_t si) {
   return ((si & 0x7fffffffu) + 1u) | (si & 0x80000000u);
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Unit staging shared by the B-CSF and CSL kernels.
+//
+// All global loads a unit needs before its inner loop (stream data, fiber-segment and slice
+// arrays, the rows at the ends of the runs) are issued back to back and awaited once, then the
+// LDS records are written and the end marks scattered into them.  The run-table entries of
+// the next unit are fetched one unit ahead (UnitBounds), so nothing here waits on a chain of
+// dependent loads.
+// ---------------------------------------------------------------------------------------
+struct UnitBounds {
+  uint32_t rf;      // lane t <= NG: slice holding the first nonzero of run r0 + t (clipped to runs)
+  uint32_t fHi[2];  // fiber levels 1, 2: first segment of the next unit (wave-uniform)
+};
+
+template <int G, int N, bool CSF>
+__device__ __forceinline__ UnitBounds load_bounds(const GroupArgs& a, uint32_t u, int lane) {
+  constexpr int NG = 64 / G;
+  UnitBounds b;
+  const uint32_t r0 = u * NG;
+  b.rf = a.runFirst[0][min(r0 + (uint32_t)min(lane, NG), a.runs)];
+  b.fHi[0] = b.fHi[1] = 0;
+  if (CSF) {
+    const uint32_t rN = min(r0 + NG, a.runs);
+#pragma unroll
+    for (int l = 1; l <= N - 2; ++l) b.fHi[l - 1] = a.runFirst[l][rN];
+  }
+  return b;
+}
+
+struct UnitEnds {
+  uint32_t headRow;  // output row of the slice holding this lane group's first nonzero
+  uint32_t tailRow;  // output row of the slice holding the first nonzero of the next run
+  uint32_t ng;       // nonzeros in this lane group's run (0 beyond the end of the stream)
+};
+
+// fLo: first segment of this unit per fiber level (wave-uniform; = previous unit's fHi).
+template <int G, int N, bool CSF>
+__device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __restrict__ rec, uint32_t u,
+                                               const UnitBounds& b, const uint32_t (&fLo)[2], int lane) {
+  constexpr int NG = 64 / G;
+  constexpr int NF = N - 2;
+  constexpr int RW = (N == 3) ? 4 : 8;
+  constexpr int KV = 8;  // stream loads per lane issued together (covers 512 nonzeros)
+  constexpr int KF = 4;  // segment loads per lane and level issued together (256 segments)
+  constexpr int KS = 2;  // slice loads per lane issued together (128 slices)
+  constexpr int markWord = (N == 3) ? 3 : 4;
+  const uint32_t ls = a.lshift, L = 1u << ls;
+  const uint32_t slots = (uint32_t)NG << ls;
+  const uint32_t r0 = u * NG;
+  const uint32_t z0 = r0 << ls;
+  const int g = lane / G;
+  const uint32_t* __restrict__ valb = reinterpret_cast<const uint32_t*>(a.val);
+
+  // -- issue: rows at the ends of this lane group's run
+  const uint32_t hs = __shfl(b.rf, g), ts = __shfl(b.rf, g + 1);
+  const uint32_t headRaw = a.ind[0][hs], tailRaw = a.ind[0][ts];
+  // -- issue: stream data
+  uint32_t w0[KV], w1[KV], w2[KV], w3[KV];
+#pragma unroll
+  for (int t = 0; t < KV; ++t) {
+    const uint32_t p = (uint32_t)t * 64u + lane;
+    const uint32_t z = z0 + p;
+    w0[t] = w1[t] = w2[t] = w3[t] = 0;
+    if (p < slots && z < a.nnz) {
+      if (CSF) {
+        w0[t] = __builtin_nontemporal_load(a.ind[N - 1] + z);
+        w1[t] = __builtin_nontemporal_load(valb + z);
+      } else {
+        w0[t] = __builtin_nontemporal_load(a.ind[1] + z);
+        w1[t] = __builtin_nontemporal_load(a.ind[2] + z);
+        if (N == 4) w2[t] = __builtin_nontemporal_load(a.ind[3] + z);
+        w3[t] = __builtin_nontemporal_load(valb + z);
+      }
+    }
+  }
+  // -- issue: fiber-segment ends and indices
+  uint32_t fe[2][KF], fi[2][KF];
+  if (CSF) {
+#pragma unroll
+    for (int l = 1; l <= NF; ++l) {
+#pragma unroll
+      for (int t = 0; t < KF; ++t) {
+        const uint32_t f = fLo[l - 1] + (uint32_t)t * 64u + lane;
+        fe[l - 1][t] = 0;
+        fi[l - 1][t] = 0;
+        if (f < b.fHi[l - 1]) {
+          fe[l - 1][t] = __builtin_nontemporal_load(a.ptr[l] + f + 1);
+          fi[l - 1][t] = __builtin_nontemporal_load(a.ind[l] + f);
+        }
+      }
+    }
+  }
+  // -- issue: slice ends and indices
+  const uint32_t s0 = __builtin_amdgcn_readfirstlane(b.rf);
+  const uint32_t s1 = __shfl(b.rf, NG);
+  uint32_t se[KS], si[KS];
+#pragma unroll
+  for (int t = 0; t < KS; ++t) {
+    const uint32_t sl = s0 + (uint32_t)t * 64u + lane;
+    se[t] = 0;
+    si[t] = 0;
+    if (sl < s1) {
+      se[t] = a.ptr[0][sl + 1];
+      si[t] = a.ind[0][sl];
+    }
+  }
+
+  // -- records: stream data in, marks cleared
+#pragma unroll
+  for (int t = 0; t < KV; ++t) {
+    const uint32_t p = (uint32_t)t * 64u + lane;
+    if (p < slots) {
+      uint4* dst = reinterpret_cast<uint4*>(rec + (size_t)(p + (p >> ls)) * RW);
+      if (CSF) {
+        dst[0] = make_uint4(w0[t], w1[t], 0u, 0u);
+        if (N == 4) dst[1] = make_uint4(0u, 0u, 0u, 0u);
+      } else if (N == 3) {
+        dst[0] = make_uint4(w0[t], w1[t], w3[t], 0u);
+      } else {
+        dst[0] = make_uint4(w0[t], w1[t], w2[t], w3[t]);
+        dst[1] = make_uint4(0u, 0u, 0u, 0u);
+      }
+    }
+  }
+  for (uint32_t p = (uint32_t)KV * 64u + lane; p < slots; p += 64) {  // units above 512 nonzeros
+    const uint32_t z = z0 + p;
+    uint32_t x0 = 0, x1 = 0, x2 = 0, x3 = 0;
+    if (z < a.nnz) {
+      if (CSF) {
+        x0 = a.ind[N - 1][z];
+        x1 = valb[z];
+      } else {
+        x0 = a.ind[1][z];
+        x1 = a.ind[2][z];
+        if (N == 4) x2 = a.ind[3][z];
+        x3 = valb[z];
+      }
+    }
+    uint4* dst = reinterpret_cast<uint4*>(rec + (size_t)(p + (p >> ls)) * RW);
+    if (CSF) {
+      dst[0] = make_uint4(x0, x1, 0u, 0u);
+      if (N == 4) dst[1] = make_uint4(0u, 0u, 0u, 0u);
+    } else if (N == 3) {
+      dst[0] = make_uint4(x0, x1, x3, 0u);
+    } else {
+      dst[0] = make_uint4(x0, x1, x2, x3);
+      dst[1] = make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+
+  // -- segment end marks
+  if (CSF) {
+#pragma unroll
+    for (int l = 1; l <= NF; ++l) {
+      const int word = 2 + (NF - l);
+#pragma unroll
+      for (int t = 0; t < KF; ++t) {
+        const uint32_t f = fLo[l - 1] + (uint32_t)t * 64u + lane;
+        if (f < b.fHi[l - 1]) {
+          const uint32_t p = fe[l - 1][t] - 1u - z0;
+          rec[(size_t)(p + (p >> ls)) * RW + word] = fi[l - 1][t] + 1u;
+        }
+      }
+      for (uint32_t f = fLo[l - 1] + (uint32_t)KF * 64u + lane; f < b.fHi[l - 1]; f += 64) {
+        const uint32_t p = a.ptr[l][f + 1] - 1u - z0;
+        rec[(size_t)(p + (p >> ls)) * RW + word] = a.ind[l][f] + 1u;
+      }
+    }
+  }
+  // -- slice end marks
+#pragma unroll
+  for (int t = 0; t < KS; ++t) {
+    const uint32_t sl = s0 + (uint32_t)t * 64u + lane;
+    if (sl < s1) {
+      const uint32_t p = se[t] - 1u - z0;
+      rec[(size_t)(p + (p >> ls)) * RW + markWord] = mark_of_slice(si[t]);
+    }
+  }
+  for (uint32_t sl = s0 + (uint32_t)KS * 64u + lane; sl < s1; sl += 64) {
+    const uint32_t p = a.ptr[0][sl + 1] - 1u - z0;
+    rec[(size_t)(p + (p >> ls)) * RW + markWord] = mark_of_slice(a.ind[0][sl]);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+  UnitEnds e;
+  const uint32_t r = r0 + g;
+  e.headRow = headRaw & 0x7fffffffu;
+  e.tailRow = tailRaw & 0x7fffffffu;
+  e.ng = r < a.runs ? min(L, a.nnz - (r << ls)) : 0u;
+  return e;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------
@@ -127,7 +327,7 @@ __global__ __launch_bounds__(256) void define_rows_kernel(float4* __restrict__ o
 // A segment mark is index+1 at the segment's last nonzero, else 0.  A slice mark is
 // (row+1) | owned bit at the slice's last nonzero, else 0.
 // ---------------------------------------------------------------------------------------
-template <int G, int N>
+template <int G, int N, int kSteps, bool WIDE>
 __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
   constexpr int NG = 64 / G;
   constexpr int NF = N - 2;
@@ -144,8 +344,6 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
   uint32_t u = wave * a.unitsPerWave;
   const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
 
-  const uint32_t* __restrict__ leaf = a.ind[N - 1];
-  const uint32_t* __restrict__ valb = reinterpret_cast<const uint32_t*>(a.val);
   const float* __restrict__ facLeaf = a.fac[N - 1];
   const float* __restrict__ facDeep = a.fac[N - 2];   // deepest fiber level
   const float* __restrict__ facTop = a.fac[1];        // level 1 (same as facDeep when N = 3)
@@ -154,58 +352,26 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
   bool pend = false;
   uint32_t pendRow = 0;
 
-  for (; u < uEnd; ++u) {
-    const uint32_t r0 = u * NG;
-    const uint32_t z0 = r0 << ls;
-    const uint32_t rN = min(r0 + NG, a.runs);
-
-    // -- stage leaf indices and values (coalesced), marks cleared
-    for (uint32_t p = lane; p < (uint32_t)NG << ls; p += 64) {
-      const uint32_t z = z0 + p;
-      uint32_t k = 0, v = 0;
-      if (z < a.nnz) {
-        k = __builtin_nontemporal_load(leaf + z);
-        v = __builtin_nontemporal_load(valb + z);
-      }
-      uint4* dst = reinterpret_cast<uint4*>(rec + (size_t)(p + (p >> ls)) * RW);
-      dst[0] = make_uint4(k, v, 0u, 0u);
-      if (N == 4) dst[1] = make_uint4(0u, 0u, 0u, 0u);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    // -- segment end marks
+  if (u >= uEnd) return;
+  UnitBounds cur = load_bounds<G, N, true>(a, u, lane);
+  uint32_t fLo[2] = {0, 0};
 #pragma unroll
-    for (int l = 1; l <= NF; ++l) {
-      const uint32_t f0 = a.runFirst[l][r0], f1 = a.runFirst[l][rN];
-      const int word = 2 + (NF - l);
-      for (uint32_t f = f0 + lane; f < f1; f += 64) {
-        const uint32_t p = a.ptr[l][f + 1] - 1u - z0;
-        rec[(size_t)(p + (p >> ls)) * RW + word] = a.ind[l][f] + 1u;
-      }
-    }
-    // -- slice end marks
-    {
-      const uint32_t s0 = a.runFirst[0][r0], s1 = a.runFirst[0][rN];
-      for (uint32_t s = s0 + lane; s < s1; s += 64) {
-        const uint32_t p = a.ptr[0][s + 1] - 1u - z0;
-        rec[(size_t)(p + (p >> ls)) * RW + (N == 3 ? 3 : 4)] = mark_of_slice(a.ind[0][s]);
-      }
-    }
-    // -- rows at the two ends of this lane group's run
-    const uint32_t r = r0 + g;
-    uint32_t headRow = 0, tailRow = 0, ng = 0;
-    if (r < a.runs) {
-      headRow = a.ind[0][a.runFirst[0][r]] & 0x7fffffffu;
-      tailRow = a.ind[0][a.runFirst[0][r + 1]] & 0x7fffffffu;
-      ng = min(L, a.nnz - (r << ls));
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  for (int l = 1; l <= NF; ++l) fLo[l - 1] = a.runFirst[l][u * NG];
+
+  for (; u < uEnd; ++u) {
+    // run-table entries of the next unit: in flight while this unit is staged and processed
+    const UnitBounds nxt = load_bounds<G, N, true>(a, min(u + 1, a.nUnits - 1), lane);
+    const UnitEnds ends = stage_unit<G, N, true>(a, rec, u, cur, fLo, lane);
+    const uint32_t headRow = ends.headRow, tailRow = ends.tailRow, ng = ends.ng;
+    fLo[0] = cur.fHi[0];
+    fLo[1] = cur.fHi[1];
+    cur = nxt;
 
     if (ng > 0) {
       if (pend && pendRow != headRow) {
         row_atomic<G>(a.out, pendRow, c, acc);
         acc = f4zero();
       }
-      bool open = true;
       float4 tmp = f4zero();
       float4 tmp1 = f4zero();
       const uint32_t* myrec = rec + (size_t)g * (L + 1) * RW;
@@ -219,13 +385,15 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
           rr[t] = src[0];
           mi[t] = (N == 3) ? rr[t].w : reinterpret_cast<const uint32_t*>(src)[4];
         }
-#pragma unroll
-        for (int t = 0; t < kSteps; ++t) cr[t] = row_load<G>(facLeaf, rr[t].x, c);
+        // Conditional loads first: loads return in order, so once a leaf row has arrived every
+        // load issued before it has arrived too, and the leaf rows can be awaited one by one.
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
-          if (rr[t].z) br[t] = row_load<G>(facDeep, rr[t].z - 1u, c);
-          if (N == 4 && rr[t].w) ar[t] = row_load<G>(facTop, rr[t].w - 1u, c);
+          if (rr[t].z) br[t] = row_load<G, WIDE>(facDeep, rr[t].z - 1u, c);
+          if (N == 4 && rr[t].w) ar[t] = row_load<G, WIDE>(facTop, rr[t].w - 1u, c);
         }
+#pragma unroll
+        for (int t = 0; t < kSteps; ++t) cr[t] = row_load<G, WIDE>(facLeaf, rr[t].x, c);
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
           fma4(tmp, __uint_as_float(rr[t].y), cr[t]);
@@ -247,10 +415,10 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
             else row_atomic<G>(a.out, row, c, acc);
             acc = f4zero();
           }
-          if (sb + t < ng) open = (mi[t] == 0u);
         }
       }
-      pend = open;
+      // the run leaves a partial row behind unless its last nonzero ends a slice
+      pend = myrec[(size_t)(ng - 1) * RW + (N == 3 ? 3 : 4)] == 0u;
       pendRow = tailRow;
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -263,7 +431,7 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
 // slice pointer goes straight to the nonzeros.
 // LDS record: N = 3: {j, k, val, slice mark}; N = 4: {a, b, l, val, slice mark, -, -, -}.
 // ---------------------------------------------------------------------------------------
-template <int G, int N>
+template <int G, int N, int kSteps, bool WIDE>
 __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
   constexpr int NG = 64 / G;
   constexpr int RW = (N == 3) ? 4 : 8;
@@ -278,56 +446,26 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
   const uint32_t wave = logical_block() * wpb + wib;
   uint32_t u = wave * a.unitsPerWave;
   const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
-  const uint32_t* __restrict__ valb = reinterpret_cast<const uint32_t*>(a.val);
 
   float4 acc = f4zero();
   bool pend = false;
   uint32_t pendRow = 0;
 
+  if (u >= uEnd) return;
+  UnitBounds cur = load_bounds<G, N, false>(a, u, lane);
+  const uint32_t fLo[2] = {0, 0};
+
   for (; u < uEnd; ++u) {
-    const uint32_t r0 = u * NG;
-    const uint32_t z0 = r0 << ls;
-    const uint32_t rN = min(r0 + NG, a.runs);
-    for (uint32_t p = lane; p < (uint32_t)NG << ls; p += 64) {
-      const uint32_t z = z0 + p;
-      uint32_t i1 = 0, i2 = 0, i3 = 0, v = 0;
-      if (z < a.nnz) {
-        i1 = __builtin_nontemporal_load(a.ind[1] + z);
-        i2 = __builtin_nontemporal_load(a.ind[2] + z);
-        if (N == 4) i3 = __builtin_nontemporal_load(a.ind[3] + z);
-        v = __builtin_nontemporal_load(valb + z);
-      }
-      uint4* dst = reinterpret_cast<uint4*>(rec + (size_t)(p + (p >> ls)) * RW);
-      if (N == 3) {
-        dst[0] = make_uint4(i1, i2, v, 0u);
-      } else {
-        dst[0] = make_uint4(i1, i2, i3, v);
-        dst[1] = make_uint4(0u, 0u, 0u, 0u);
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    {
-      const uint32_t s0 = a.runFirst[0][r0], s1 = a.runFirst[0][rN];
-      for (uint32_t s = s0 + lane; s < s1; s += 64) {
-        const uint32_t p = a.ptr[0][s + 1] - 1u - z0;
-        rec[(size_t)(p + (p >> ls)) * RW + (N == 3 ? 3 : 4)] = mark_of_slice(a.ind[0][s]);
-      }
-    }
-    const uint32_t r = r0 + g;
-    uint32_t headRow = 0, tailRow = 0, ng = 0;
-    if (r < a.runs) {
-      headRow = a.ind[0][a.runFirst[0][r]] & 0x7fffffffu;
-      tailRow = a.ind[0][a.runFirst[0][r + 1]] & 0x7fffffffu;
-      ng = min(L, a.nnz - (r << ls));
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    const UnitBounds nxt = load_bounds<G, N, false>(a, min(u + 1, a.nUnits - 1), lane);
+    const UnitEnds ends = stage_unit<G, N, false>(a, rec, u, cur, fLo, lane);
+    const uint32_t headRow = ends.headRow, tailRow = ends.tailRow, ng = ends.ng;
+    cur = nxt;
 
     if (ng > 0) {
       if (pend && pendRow != headRow) {
         row_atomic<G>(a.out, pendRow, c, acc);
         acc = f4zero();
       }
-      bool open = true;
       const uint32_t* myrec = rec + (size_t)g * (L + 1) * RW;
       for (uint32_t sb = 0; sb < L; sb += kSteps) {
         uint4 rr[kSteps];
@@ -341,9 +479,9 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
         }
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
-          x1[t] = row_load<G>(a.fac[1], rr[t].x, c);
-          x2[t] = row_load<G>(a.fac[2], rr[t].y, c);
-          if (N == 4) x3[t] = row_load<G>(a.fac[3], rr[t].z, c);
+          x1[t] = row_load<G, WIDE>(a.fac[1], rr[t].x, c);
+          x2[t] = row_load<G, WIDE>(a.fac[2], rr[t].y, c);
+          if (N == 4) x3[t] = row_load<G, WIDE>(a.fac[3], rr[t].z, c);
         }
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
@@ -356,10 +494,10 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
             else row_atomic<G>(a.out, row, c, acc);
             acc = f4zero();
           }
-          if (sb + t < ng) open = (mi[t] == 0u);
         }
       }
-      pend = open;
+      // the run leaves a partial row behind unless its last nonzero ends a slice
+      pend = myrec[(size_t)(ng - 1) * RW + (N == 3 ? 3 : 4)] == 0u;
       pendRow = tailRow;
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -372,7 +510,7 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
 // its output row, so the row is written with a plain store and no atomic is needed.
 // Lane group g of a wavefront takes nonzero z = base + step*NG + g.
 // ---------------------------------------------------------------------------------------
-template <int G, int N>
+template <int G, int N, bool WIDE>
 __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
   constexpr int NG = 64 / G;
   constexpr int kU = 4;
@@ -401,9 +539,9 @@ __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
 #pragma unroll
     for (int t = 0; t < kU; ++t) {
       if (ok[t]) {
-        x1[t] = row_load<G>(a.fac[1], i1[t], c);
-        x2[t] = row_load<G>(a.fac[2], i2[t], c);
-        if (N == 4) x3[t] = row_load<G>(a.fac[3], i3[t], c);
+        x1[t] = row_load<G, WIDE>(a.fac[1], i1[t], c);
+        x2[t] = row_load<G, WIDE>(a.fac[2], i2[t], c);
+        if (N == 4) x3[t] = row_load<G, WIDE>(a.fac[3], i3[t], c);
       }
     }
 #pragma unroll
@@ -422,34 +560,43 @@ __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
 // ---------------------------------------------------------------------------------------
 namespace {
 
-template <int N>
-hipError_t launch_group_n(int kind, int G, const GroupArgs& a, dim3 grid, dim3 block, size_t lds,
-                          hipStream_t s) {
-#define HBCSF_CASE(GV)                                                                          \
-  case GV:                                                                                      \
-    if (kind == kCsfKernel) hipLaunchKernelGGL((csf_group_kernel<GV, N>), grid, block, lds, s, a); \
-    else if (kind == kCslKernel) hipLaunchKernelGGL((csl_group_kernel<GV, N>), grid, block, lds, s, a); \
-    else hipLaunchKernelGGL((coo_group_kernel<GV, N>), grid, block, 0, s, a);                    \
-    break;
-  switch (G) {
-    HBCSF_CASE(2)
-    HBCSF_CASE(4)
-    HBCSF_CASE(8)
-    HBCSF_CASE(16)
-    HBCSF_CASE(32)
-    default:
-      return hipErrorInvalidValue;
-  }
-#undef HBCSF_CASE
+template <int G, int N, int S, bool WIDE>
+hipError_t launch_one(int kind, const GroupArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
+  if (kind == kCsfKernel) hipLaunchKernelGGL((csf_group_kernel<G, N, S, WIDE>), grid, block, lds, s, a);
+  else if (kind == kCslKernel) hipLaunchKernelGGL((csl_group_kernel<G, N, S, WIDE>), grid, block, lds, s, a);
+  else hipLaunchKernelGGL((coo_group_kernel<G, N, WIDE>), grid, block, 0, s, a);
   return hipGetLastError();
+}
+
+template <int G, int N>
+hipError_t launch_g(int kind, int steps, bool wide, const GroupArgs& a, dim3 grid, dim3 block, size_t lds,
+                    hipStream_t s) {
+  if (G == 8 && steps == 4)
+    return wide ? launch_one<G, N, 4, true>(kind, a, grid, block, lds, s)
+                : launch_one<G, N, 4, false>(kind, a, grid, block, lds, s);
+  return wide ? launch_one<G, N, 8, true>(kind, a, grid, block, lds, s)
+              : launch_one<G, N, 8, false>(kind, a, grid, block, lds, s);
+}
+
+template <int N>
+hipError_t launch_n(int kind, int G, int steps, bool wide, const GroupArgs& a, dim3 grid, dim3 block,
+                    size_t lds, hipStream_t s) {
+  switch (G) {
+    case 2: return launch_g<2, N>(kind, steps, wide, a, grid, block, lds, s);
+    case 4: return launch_g<4, N>(kind, steps, wide, a, grid, block, lds, s);
+    case 8: return launch_g<8, N>(kind, steps, wide, a, grid, block, lds, s);
+    case 16: return launch_g<16, N>(kind, steps, wide, a, grid, block, lds, s);
+    case 32: return launch_g<32, N>(kind, steps, wide, a, grid, block, lds, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace
 
-hipError_t launch_group(int kind, int order, int G, const GroupArgs& a, uint32_t blocks,
-                        uint32_t threads, size_t ldsBytes, hipStream_t s) {
-  if (order == 3) return launch_group_n<3>(kind, G, a, dim3(blocks), dim3(threads), ldsBytes, s);
-  return launch_group_n<4>(kind, G, a, dim3(blocks), dim3(threads), ldsBytes, s);
+hipError_t launch_group(int kind, int order, int G, int steps, bool wide, const GroupArgs& a,
+                        uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s) {
+  if (order == 3) return launch_n<3>(kind, G, steps, wide, a, dim3(blocks), dim3(threads), ldsBytes, s);
+  return launch_n<4>(kind, G, steps, wide, a, dim3(blocks), dim3(threads), ldsBytes, s);
 }
 
 hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, int G, uint32_t blocks,

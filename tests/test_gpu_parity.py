@@ -145,8 +145,12 @@ def test_repeated_calls_overwrite(oracle):
     s.synchronize()
     GU.assert_close(out2.cpu().numpy(), want, "side stream")
     # profiling hooks report the four kernels
-    B.tune(t.handle, B.TUNE_PROFILE, 1)
-    t.mttkrp(1, d, out)
-    ms = B.last_kernel_ms(t.handle)
-    assert len(ms) == 4 and ms[0] > 0 and ms[3] > 0
+    B.tune(t.handle, B.TUNE_PROFILE, 4)
+    for mode in (0, 1):
+        t.mttkrp(mode, d)
+    for back in (0, 1):
+        ms = B.kernel_ms(t.handle, back)
+        assert len(ms) == 4 and ms[0] > 0 and ms[3] > 0
+    with pytest.raises(B.HbcsfError):
+        B.kernel_ms(t.handle, 2)
     t.close()
