@@ -165,9 +165,9 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
 
   // 1. define every output row that no plain store will write
   {
-    const uint64_t nvec = f.rows * (uint64_t)G;
-    uint64_t blocks = (nvec + 255) / 256;
-    const uint64_t cap = (uint64_t)t->numCU * 32;
+    // one wavefront per 32 rows, capped at 64 wavefronts per compute unit
+    uint64_t blocks = ((f.rows + 31) / 32 + 3) / 4;
+    const uint64_t cap = (uint64_t)t->numCU * 16;
     if (blocks > cap) blocks = cap;
     if (blocks == 0) blocks = 1;
     e = launch_define(out, (const uint32_t*)(base + f.ownedBits.off), f.rows, G, (uint32_t)blocks, s);
@@ -201,7 +201,7 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
       size_t lds = 0;
       if (g == kCoo) {
         threads = 256;
-        const uint64_t perBlock = (uint64_t)NG * 4 * 4;
+        const uint64_t perBlock = 64 * 4;  // 64 nonzeros per wavefront and iteration
         uint64_t b = (gf.nnz + perBlock - 1) / perBlock;
         const uint64_t cap = (uint64_t)t->numCU * 16;
         if (b > cap) b = cap;

@@ -30,6 +30,14 @@ namespace {
 
 __device__ __forceinline__ float4 f4zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Streaming 16-byte store: the data is not read again by the kernel that writes it.
+__device__ __forceinline__ void store_streaming(float4* p, const float4& a) {
+  f32x4 v = {a.x, a.y, a.z, a.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+}
+
 // WIDE = false: the factor matrix is smaller than 4 GiB, so a 32-bit byte offset from a
 // scalar base is enough (one VALU instruction per gather); WIDE = true: 64-bit arithmetic.
 template <int G, bool WIDE>
@@ -44,7 +52,7 @@ __device__ __forceinline__ float4 row_load(const float* __restrict__ base, uint3
 
 template <int G>
 __device__ __forceinline__ void row_store(float* __restrict__ out, uint32_t row, int c, float4 a) {
-  *reinterpret_cast<float4*>(out + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c))) = a;
+  store_streaming(reinterpret_cast<float4*>(out + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c))), a);
 }
 
 template <int G>
@@ -309,14 +317,25 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
 // Output definition: rows that no plain store will write (empty slices and rows merged with
 // atomic adds) are set to zero; the others are left to their single store.
 // ---------------------------------------------------------------------------------------
+// One wavefront takes one bitmap word (32 rows) at a time: the word is read once through the
+// scalar path and each lane then stores its share of the 32 rows' float4s.
 __global__ __launch_bounds__(256) void define_rows_kernel(float4* __restrict__ out,
                                                           const uint32_t* __restrict__ ownedBits,
                                                           uint64_t nvec, int gshift) {
-  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-  for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < nvec; t += stride) {
-    const uint64_t row = t >> gshift;
-    const uint32_t w = ownedBits[row >> 5];
-    if (!((w >> (row & 31)) & 1u)) out[t] = f4zero();
+  const int lane = threadIdx.x & 63;
+  const uint32_t waves = (gridDim.x * blockDim.x) >> 6;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+  const uint64_t perWord = (uint64_t)32 << gshift;      // float4s covered by one bitmap word
+  const uint64_t words = (nvec + perWord - 1) / perWord;
+  const int reps = (int)(perWord >> 6);                  // stores per lane per word (G / 2)
+  for (uint64_t wd = wave; wd < words; wd += waves) {
+    const uint32_t w = ownedBits[wd];
+    const uint64_t base = wd * perWord;
+    for (int q = 0; q < reps; ++q) {
+      const uint32_t f = (uint32_t)q * 64u + lane;        // float4 within the word's 32 rows
+      const uint64_t t = base + f;
+      if (t < nvec && !((w >> (f >> gshift)) & 1u)) store_streaming(out + t, f4zero());
+    }
   }
 }
 
@@ -513,43 +532,51 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
 template <int G, int N, bool WIDE>
 __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
   constexpr int NG = 64 / G;
-  constexpr int kU = 4;
+  constexpr int kU = G < 4 ? G : 4;  // nonzeros per lane group in flight
   const int lane = threadIdx.x & 63;
   const int g = lane / G, c = lane % G;
   const uint32_t waves = (gridDim.x * blockDim.x) >> 6;
   const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const uint32_t* __restrict__ valb = reinterpret_cast<const uint32_t*>(a.val);
-  for (uint64_t base = (uint64_t)wave * (NG * kU); base < a.nnz; base += (uint64_t)waves * (NG * kU)) {
-    uint32_t i0[kU], i1[kU], i2[kU], i3[kU], v[kU];
-    bool ok[kU];
-#pragma unroll
-    for (int t = 0; t < kU; ++t) {
-      const uint64_t z = base + (uint64_t)t * NG + g;
-      ok[t] = z < a.nnz;
-      i0[t] = i1[t] = i2[t] = i3[t] = v[t] = 0;
-      if (ok[t]) {
-        i0[t] = a.ind[0][z];
-        i1[t] = a.ind[1][z];
-        i2[t] = a.ind[2][z];
-        if (N == 4) i3[t] = a.ind[3][z];
-        v[t] = valb[z];
-      }
+  // 64 nonzeros per wavefront and iteration: lane l loads the coordinates of nonzero base + l
+  // (coalesced), then lane group g takes nonzero base + step*NG + g from lane step*NG + g.
+  for (uint64_t base = (uint64_t)wave * 64u; base < a.nnz; base += (uint64_t)waves * 64u) {
+    const uint64_t z = base + lane;
+    uint32_t m0 = 0, m1 = 0, m2 = 0, m3 = 0, mv = 0;
+    if (z < a.nnz) {
+      m0 = __builtin_nontemporal_load(a.ind[0] + z);
+      m1 = __builtin_nontemporal_load(a.ind[1] + z);
+      m2 = __builtin_nontemporal_load(a.ind[2] + z);
+      if (N == 4) m3 = __builtin_nontemporal_load(a.ind[3] + z);
+      mv = __builtin_nontemporal_load(valb + z);
     }
-    float4 x1[kU], x2[kU], x3[kU];
+    const uint32_t left = (uint32_t)min((uint64_t)64, a.nnz - base);
 #pragma unroll
-    for (int t = 0; t < kU; ++t) {
-      if (ok[t]) {
-        x1[t] = row_load<G, WIDE>(a.fac[1], i1[t], c);
-        x2[t] = row_load<G, WIDE>(a.fac[2], i2[t], c);
-        if (N == 4) x3[t] = row_load<G, WIDE>(a.fac[3], i3[t], c);
+    for (int sb = 0; sb < G; sb += kU) {
+      uint32_t i0[kU], v[kU];
+      float4 x1[kU], x2[kU], x3[kU];
+      bool ok[kU];
+#pragma unroll
+      for (int t = 0; t < kU; ++t) {
+        const int src = (sb + t) * NG + g;
+        ok[t] = (uint32_t)src < left;
+        i0[t] = __shfl(m0, src);
+        v[t] = __shfl(mv, src);
+        const uint32_t i1 = __shfl(m1, src), i2 = __shfl(m2, src);
+        const uint32_t i3 = N == 4 ? __shfl(m3, src) : 0u;
+        if (ok[t]) {
+          x1[t] = row_load<G, WIDE>(a.fac[1], i1, c);
+          x2[t] = row_load<G, WIDE>(a.fac[2], i2, c);
+          if (N == 4) x3[t] = row_load<G, WIDE>(a.fac[3], i3, c);
+        }
       }
-    }
 #pragma unroll
-    for (int t = 0; t < kU; ++t) {
-      if (ok[t]) {
-        float4 pr = mul4(x1[t], x2[t]);
-        if (N == 4) pr = mul4(pr, x3[t]);
-        row_store<G>(a.out, i0[t], c, scale4(__uint_as_float(v[t]), pr));
+      for (int t = 0; t < kU; ++t) {
+        if (ok[t]) {
+          float4 pr = mul4(x1[t], x2[t]);
+          if (N == 4) pr = mul4(pr, x3[t]);
+          row_store<G>(a.out, i0[t], c, scale4(__uint_as_float(v[t]), pr));
+        }
       }
     }
   }
