@@ -135,8 +135,8 @@ int hbcsf_host_array(const hbcsf_tensor *t, int mode, int group, int level, int 
                                         keep the last n calls' event sets; 0 = off              */
 #define HBCSF_TUNE_WAVES_PER_CU     2 /* wavefront spans launched per compute unit when T_s is
                                         automatic (default 128)                                 */
-#define HBCSF_TUNE_STEPS            3 /* gathers a lane group keeps in flight: 4 or 8 (default 4;
-                                        ranks other than 32 always use 8)                       */
+#define HBCSF_TUNE_STEPS            3 /* gathers a lane group keeps in flight: 4 or 8 (default 8;
+                                        4 is only available at rank 32)                         */
 int hbcsf_tune(hbcsf_tensor *t, int key, uint64_t value);
 
 /* With HBCSF_TUNE_PROFILE on: milliseconds of the four kernels (define, COO, CSL, CSF; 0 for a

@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -29,10 +30,20 @@ def build(verbose: bool = False) -> str:
     o = os.path.join(CSRC, "hbcsf_format.o")
     run(["g++", "-O3", "-std=c++17", "-fPIC", "-fopenmp", "-c", os.path.join(CSRC, "hbcsf_format.cpp"), "-o", o] + inc)
     objs.append(o)
-    for name in ("hbcsf_kernels", "hbcsf_capi"):
-        o = os.path.join(CSRC, name + ".o")
-        run(["hipcc"] + HIP_FLAGS + inc + ["-c", os.path.join(CSRC, name + ".hip"), "-o", o])
-        objs.append(o)
+    # the kernels are compiled once per (lanes per row, order) pair, in parallel
+    jobs = []
+    for g in (2, 4, 8, 16, 32):
+        for n in (3, 4):
+            o = os.path.join(CSRC, f"hbcsf_kernels_g{g}_n{n}.o")
+            defs = [f"-DHBCSF_G={g}", f"-DHBCSF_N={n}"] + (["-DHBCSF_WITH_DEFINE"] if (g, n) == (8, 3) else [])
+            jobs.append(["hipcc"] + HIP_FLAGS + inc + defs + ["-c", os.path.join(CSRC, "hbcsf_kernels.hip"), "-o", o])
+            objs.append(o)
+    o = os.path.join(CSRC, "hbcsf_capi.o")
+    jobs.append(["hipcc"] + HIP_FLAGS + inc + ["-c", os.path.join(CSRC, "hbcsf_capi.hip"), "-o", o])
+    objs.append(o)
+    workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 4))))
+    with ThreadPoolExecutor(workers) as pool:
+        list(pool.map(run, jobs))
     run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", SO] + objs + ["-lgomp"])
     return SO
 

@@ -27,7 +27,7 @@ struct hbcsf_tensor {
   int numCU = 256;
   uint64_t sliceThreshold = 0;
   uint64_t wavesPerCU = 0;   // launch sizing override, 0 = default
-  int steps = 4;             // records in flight per lane group
+  int steps = 8;             // records in flight per lane group
   // profiling: a ring of event sets, one per hbcsf_mttkrp call
   struct EventSet {
     hipEvent_t ev[5];

@@ -26,9 +26,40 @@ struct GroupArgs {
 
 // kind: KernelKind; order 3 or 4; G = rank / 4 lanes per factor row (2, 4, 8, 16 or 32);
 // steps = records a lane group keeps in flight (4 or 8); wide = some gathered factor matrix
-// is 4 GiB or larger (64-bit row addressing).
-hipError_t launch_group(int kind, int order, int G, int steps, bool wide, const GroupArgs& a,
-                        uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s);
+// is 4 GiB or larger (64-bit row addressing).  One launch function per (G, order) pair, each
+// compiled in its own object file.
+#define HBCSF_DECLARE_LAUNCH(G, N)                                                                  \
+  hipError_t launch_group_g##G##_n##N(int kind, int steps, bool wide, const GroupArgs& a,          \
+                                      uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s);
+HBCSF_DECLARE_LAUNCH(2, 3)
+HBCSF_DECLARE_LAUNCH(4, 3)
+HBCSF_DECLARE_LAUNCH(8, 3)
+HBCSF_DECLARE_LAUNCH(16, 3)
+HBCSF_DECLARE_LAUNCH(32, 3)
+HBCSF_DECLARE_LAUNCH(2, 4)
+HBCSF_DECLARE_LAUNCH(4, 4)
+HBCSF_DECLARE_LAUNCH(8, 4)
+HBCSF_DECLARE_LAUNCH(16, 4)
+HBCSF_DECLARE_LAUNCH(32, 4)
+#undef HBCSF_DECLARE_LAUNCH
+
+inline hipError_t launch_group(int kind, int order, int G, int steps, bool wide, const GroupArgs& a,
+                               uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s) {
+#define HBCSF_CASE(GV)                                                                              \
+  case GV:                                                                                          \
+    return order == 3 ? launch_group_g##GV##_n3(kind, steps, wide, a, blocks, threads, ldsBytes, s) \
+                      : launch_group_g##GV##_n4(kind, steps, wide, a, blocks, threads, ldsBytes, s);
+  switch (G) {
+    HBCSF_CASE(2)
+    HBCSF_CASE(4)
+    HBCSF_CASE(8)
+    HBCSF_CASE(16)
+    HBCSF_CASE(32)
+    default:
+      return hipErrorInvalidValue;
+  }
+#undef HBCSF_CASE
+}
 
 hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, int G,
                          uint32_t blocks, hipStream_t s);

@@ -425,13 +425,21 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
       for (int l = 1; l < N; ++l) {
         const uint32_t* a = U32(G.ind[l]);
         const uint64_t cnt = (g == kCsf && l < N - 1) ? G.n[l] : G.nnz;
-        seen.assign(dims[lv[l]], 0);
-        uint8_t* sp = seen.data();
-#pragma omp parallel for schedule(static)
-        for (int64_t t = 0; t < (int64_t)cnt; ++t) __atomic_store_n(&sp[a[t]], (uint8_t)1, __ATOMIC_RELAXED);
         uint64_t d = 0;
+        if (cnt == 0) {
+          d = 0;
+        } else if (cnt * 16 < dims[lv[l]]) {  // few indices in a long mode: sort and count
+          std::vector<uint32_t> tmp(a, a + cnt);
+          std::sort(tmp.begin(), tmp.end());
+          d = (uint64_t)(std::unique(tmp.begin(), tmp.end()) - tmp.begin());
+        } else {
+          seen.assign(dims[lv[l]], 0);
+          uint8_t* sp = seen.data();
+#pragma omp parallel for schedule(static)
+          for (int64_t t = 0; t < (int64_t)cnt; ++t) __atomic_store_n(&sp[a[t]], (uint8_t)1, __ATOMIC_RELAXED);
 #pragma omp parallel for schedule(static) reduction(+ : d)
-        for (int64_t t = 0; t < (int64_t)seen.size(); ++t) d += sp[t];
+          for (int64_t t = 0; t < (int64_t)seen.size(); ++t) d += sp[t];
+        }
         st.distinct_rows[g][l] = d;
       }
       st.distinct_rows[g][0] = gS[g];

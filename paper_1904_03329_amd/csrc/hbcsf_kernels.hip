@@ -154,7 +154,7 @@ struct UnitEnds {
 };
 
 // fLo: first segment of this unit per fiber level (wave-uniform; = previous unit's fHi).
-template <int G, int N, bool CSF>
+template <int G, int N, int LS, bool CSF>
 __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __restrict__ rec, uint32_t u,
                                                const UnitBounds& b, const uint32_t (&fLo)[2], int lane) {
   constexpr int NG = 64 / G;
@@ -164,8 +164,8 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
   constexpr int KF = 4;  // segment loads per lane and level issued together (256 segments)
   constexpr int KS = 2;  // slice loads per lane issued together (128 slices)
   constexpr int markWord = (N == 3) ? 3 : 4;
-  const uint32_t ls = a.lshift, L = 1u << ls;
-  const uint32_t slots = (uint32_t)NG << ls;
+  constexpr uint32_t ls = LS, L = 1u << LS;
+  constexpr uint32_t slots = (uint32_t)NG << LS;
   const uint32_t r0 = u * NG;
   const uint32_t z0 = r0 << ls;
   const int g = lane / G;
@@ -176,20 +176,39 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
   const uint32_t headRaw = a.ind[0][hs], tailRaw = a.ind[0][ts];
   // -- issue: stream data
   uint32_t w0[KV], w1[KV], w2[KV], w3[KV];
+  if (z0 + slots <= a.nnz) {  // wave-uniform: every slot of the unit holds a nonzero
 #pragma unroll
-  for (int t = 0; t < KV; ++t) {
-    const uint32_t p = (uint32_t)t * 64u + lane;
-    const uint32_t z = z0 + p;
-    w0[t] = w1[t] = w2[t] = w3[t] = 0;
-    if (p < slots && z < a.nnz) {
-      if (CSF) {
-        w0[t] = __builtin_nontemporal_load(a.ind[N - 1] + z);
-        w1[t] = __builtin_nontemporal_load(valb + z);
-      } else {
-        w0[t] = __builtin_nontemporal_load(a.ind[1] + z);
-        w1[t] = __builtin_nontemporal_load(a.ind[2] + z);
-        if (N == 4) w2[t] = __builtin_nontemporal_load(a.ind[3] + z);
-        w3[t] = __builtin_nontemporal_load(valb + z);
+    for (int t = 0; t < KV; ++t) {
+      const uint32_t p = (uint32_t)t * 64u + lane;
+      w0[t] = w1[t] = w2[t] = w3[t] = 0;
+      if ((uint32_t)t * 64u < slots) {
+        if (CSF) {
+          w0[t] = __builtin_nontemporal_load(a.ind[N - 1] + z0 + p);
+          w1[t] = __builtin_nontemporal_load(valb + z0 + p);
+        } else {
+          w0[t] = __builtin_nontemporal_load(a.ind[1] + z0 + p);
+          w1[t] = __builtin_nontemporal_load(a.ind[2] + z0 + p);
+          if (N == 4) w2[t] = __builtin_nontemporal_load(a.ind[3] + z0 + p);
+          w3[t] = __builtin_nontemporal_load(valb + z0 + p);
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int t = 0; t < KV; ++t) {
+      const uint32_t p = (uint32_t)t * 64u + lane;
+      const uint32_t z = z0 + p;
+      w0[t] = w1[t] = w2[t] = w3[t] = 0;
+      if (p < slots && z < a.nnz) {
+        if (CSF) {
+          w0[t] = __builtin_nontemporal_load(a.ind[N - 1] + z);
+          w1[t] = __builtin_nontemporal_load(valb + z);
+        } else {
+          w0[t] = __builtin_nontemporal_load(a.ind[1] + z);
+          w1[t] = __builtin_nontemporal_load(a.ind[2] + z);
+          if (N == 4) w2[t] = __builtin_nontemporal_load(a.ind[3] + z);
+          w3[t] = __builtin_nontemporal_load(valb + z);
+        }
       }
     }
   }
@@ -317,6 +336,7 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
 // Output definition: rows that no plain store will write (empty slices and rows merged with
 // atomic adds) are set to zero; the others are left to their single store.
 // ---------------------------------------------------------------------------------------
+#ifdef HBCSF_WITH_DEFINE
 // One wavefront takes one bitmap word (32 rows) at a time: the word is read once through the
 // scalar path and each lane then stores its share of the 32 rows' float4s.
 __global__ __launch_bounds__(256) void define_rows_kernel(float4* __restrict__ out,
@@ -338,6 +358,7 @@ __global__ __launch_bounds__(256) void define_rows_kernel(float4* __restrict__ o
     }
   }
 }
+#endif  // HBCSF_WITH_DEFINE
 
 // ---------------------------------------------------------------------------------------
 // B-CSF group.  N = tensor order (3 or 4); G = lanes per factor row.
@@ -346,7 +367,7 @@ __global__ __launch_bounds__(256) void define_rows_kernel(float4* __restrict__ o
 // A segment mark is index+1 at the segment's last nonzero, else 0.  A slice mark is
 // (row+1) | owned bit at the slice's last nonzero, else 0.
 // ---------------------------------------------------------------------------------------
-template <int G, int N, int kSteps, bool WIDE>
+template <int G, int N, int LS, int kSteps, bool WIDE>
 __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
   constexpr int NG = 64 / G;
   constexpr int NF = N - 2;
@@ -356,10 +377,11 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
   const int wib = threadIdx.x >> 6;
   const int wpb = blockDim.x >> 6;
   const int g = lane / G, c = lane % G;
-  const uint32_t ls = a.lshift, L = 1u << ls;
+  constexpr uint32_t L = 1u << LS;
   uint32_t* rec = lds + (size_t)wib * (NG * (L + 1) * RW);
 
-  const uint32_t wave = logical_block() * wpb + wib;
+  // wave-uniform by construction; say so, so that unit bookkeeping runs on the scalar unit
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(logical_block() * wpb + wib);
   uint32_t u = wave * a.unitsPerWave;
   const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
 
@@ -380,7 +402,7 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
   for (; u < uEnd; ++u) {
     // run-table entries of the next unit: in flight while this unit is staged and processed
     const UnitBounds nxt = load_bounds<G, N, true>(a, min(u + 1, a.nUnits - 1), lane);
-    const UnitEnds ends = stage_unit<G, N, true>(a, rec, u, cur, fLo, lane);
+    const UnitEnds ends = stage_unit<G, N, LS, true>(a, rec, u, cur, fLo, lane);
     const uint32_t headRow = ends.headRow, tailRow = ends.tailRow, ng = ends.ng;
     fLo[0] = cur.fHi[0];
     fLo[1] = cur.fHi[1];
@@ -427,12 +449,12 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
               }
             }
             tmp = f4zero();
-          }
-          if (mi[t]) {
-            const uint32_t row = (mi[t] & 0x7fffffffu) - 1u;
-            if (mi[t] & 0x80000000u) row_store<G>(a.out, row, c, acc);
-            else row_atomic<G>(a.out, row, c, acc);
-            acc = f4zero();
+            if (mi[t]) {  // a slice can only end where a segment ends
+              const uint32_t row = (mi[t] & 0x7fffffffu) - 1u;
+              if (mi[t] & 0x80000000u) row_store<G>(a.out, row, c, acc);
+              else row_atomic<G>(a.out, row, c, acc);
+              acc = f4zero();
+            }
           }
         }
       }
@@ -450,7 +472,7 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
 // slice pointer goes straight to the nonzeros.
 // LDS record: N = 3: {j, k, val, slice mark}; N = 4: {a, b, l, val, slice mark, -, -, -}.
 // ---------------------------------------------------------------------------------------
-template <int G, int N, int kSteps, bool WIDE>
+template <int G, int N, int LS, int kSteps, bool WIDE>
 __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
   constexpr int NG = 64 / G;
   constexpr int RW = (N == 3) ? 4 : 8;
@@ -459,10 +481,11 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
   const int wib = threadIdx.x >> 6;
   const int wpb = blockDim.x >> 6;
   const int g = lane / G, c = lane % G;
-  const uint32_t ls = a.lshift, L = 1u << ls;
+  constexpr uint32_t L = 1u << LS;
   uint32_t* rec = lds + (size_t)wib * (NG * (L + 1) * RW);
 
-  const uint32_t wave = logical_block() * wpb + wib;
+  // wave-uniform by construction; say so, so that unit bookkeeping runs on the scalar unit
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(logical_block() * wpb + wib);
   uint32_t u = wave * a.unitsPerWave;
   const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
 
@@ -476,7 +499,7 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
 
   for (; u < uEnd; ++u) {
     const UnitBounds nxt = load_bounds<G, N, false>(a, min(u + 1, a.nUnits - 1), lane);
-    const UnitEnds ends = stage_unit<G, N, false>(a, rec, u, cur, fLo, lane);
+    const UnitEnds ends = stage_unit<G, N, LS, false>(a, rec, u, cur, fLo, lane);
     const uint32_t headRow = ends.headRow, tailRow = ends.tailRow, ng = ends.ng;
     cur = nxt;
 
@@ -587,45 +610,58 @@ __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
 // ---------------------------------------------------------------------------------------
 namespace {
 
-template <int G, int N, int S, bool WIDE>
+template <int G, int N, int LS, int S, bool WIDE>
 hipError_t launch_one(int kind, const GroupArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
-  if (kind == kCsfKernel) hipLaunchKernelGGL((csf_group_kernel<G, N, S, WIDE>), grid, block, lds, s, a);
-  else if (kind == kCslKernel) hipLaunchKernelGGL((csl_group_kernel<G, N, S, WIDE>), grid, block, lds, s, a);
-  else hipLaunchKernelGGL((coo_group_kernel<G, N, WIDE>), grid, block, 0, s, a);
+  if (kind == kCsfKernel) hipLaunchKernelGGL((csf_group_kernel<G, N, LS, S, WIDE>), grid, block, lds, s, a);
+  else hipLaunchKernelGGL((csl_group_kernel<G, N, LS, S, WIDE>), grid, block, lds, s, a);
   return hipGetLastError();
+}
+
+template <int G, int N, int LS>
+hipError_t launch_ls(int kind, int steps, bool wide, const GroupArgs& a, dim3 grid, dim3 block, size_t lds,
+                     hipStream_t s) {
+  if (G == 8 && steps == 4)
+    return wide ? launch_one<G, N, LS, 4, true>(kind, a, grid, block, lds, s)
+                : launch_one<G, N, LS, 4, false>(kind, a, grid, block, lds, s);
+  return wide ? launch_one<G, N, LS, 8, true>(kind, a, grid, block, lds, s)
+              : launch_one<G, N, LS, 8, false>(kind, a, grid, block, lds, s);
 }
 
 template <int G, int N>
 hipError_t launch_g(int kind, int steps, bool wide, const GroupArgs& a, dim3 grid, dim3 block, size_t lds,
                     hipStream_t s) {
-  if (G == 8 && steps == 4)
-    return wide ? launch_one<G, N, 4, true>(kind, a, grid, block, lds, s)
-                : launch_one<G, N, 4, false>(kind, a, grid, block, lds, s);
-  return wide ? launch_one<G, N, 8, true>(kind, a, grid, block, lds, s)
-              : launch_one<G, N, 8, false>(kind, a, grid, block, lds, s);
-}
-
-template <int N>
-hipError_t launch_n(int kind, int G, int steps, bool wide, const GroupArgs& a, dim3 grid, dim3 block,
-                    size_t lds, hipStream_t s) {
-  switch (G) {
-    case 2: return launch_g<2, N>(kind, steps, wide, a, grid, block, lds, s);
-    case 4: return launch_g<4, N>(kind, steps, wide, a, grid, block, lds, s);
-    case 8: return launch_g<8, N>(kind, steps, wide, a, grid, block, lds, s);
-    case 16: return launch_g<16, N>(kind, steps, wide, a, grid, block, lds, s);
-    case 32: return launch_g<32, N>(kind, steps, wide, a, grid, block, lds, s);
+  if (kind == kCooKernel) {
+    if (wide) hipLaunchKernelGGL((coo_group_kernel<G, N, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((coo_group_kernel<G, N, false>), grid, block, 0, s, a);
+    return hipGetLastError();
+  }
+  switch (a.lshift) {
+    case 3: return launch_ls<G, N, 3>(kind, steps, wide, a, grid, block, lds, s);
+    case 4: return launch_ls<G, N, 4>(kind, steps, wide, a, grid, block, lds, s);
+    case 5: return launch_ls<G, N, 5>(kind, steps, wide, a, grid, block, lds, s);
+    case 6: return launch_ls<G, N, 6>(kind, steps, wide, a, grid, block, lds, s);
     default: return hipErrorInvalidValue;
   }
 }
 
 }  // namespace
 
-hipError_t launch_group(int kind, int order, int G, int steps, bool wide, const GroupArgs& a,
-                        uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s) {
-  if (order == 3) return launch_n<3>(kind, G, steps, wide, a, dim3(blocks), dim3(threads), ldsBytes, s);
-  return launch_n<4>(kind, G, steps, wide, a, dim3(blocks), dim3(threads), ldsBytes, s);
+// This file is compiled once per (HBCSF_G, HBCSF_N) pair so that the instantiations build in
+// parallel; each object exports one launch function, and the object built with
+// HBCSF_WITH_DEFINE also holds the output-definition kernel's launcher.
+#ifndef HBCSF_G
+#error "compile with -DHBCSF_G=<lanes per row> -DHBCSF_N=<order>"
+#endif
+#define HBCSF_CAT2(a, b, c, d) a##b##c##d
+#define HBCSF_CAT(a, b, c, d) HBCSF_CAT2(a, b, c, d)
+
+hipError_t HBCSF_CAT(launch_group_g, HBCSF_G, _n, HBCSF_N)(int kind, int steps, bool wide, const GroupArgs& a,
+                                                          uint32_t blocks, uint32_t threads, size_t ldsBytes,
+                                                          hipStream_t s) {
+  return launch_g<HBCSF_G, HBCSF_N>(kind, steps, wide, a, dim3(blocks), dim3(threads), ldsBytes, s);
 }
 
+#ifdef HBCSF_WITH_DEFINE
 hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, int G, uint32_t blocks,
                          hipStream_t s) {
   int gshift = 0;
@@ -634,5 +670,6 @@ hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, i
                      ownedBits, rows * (uint64_t)G, gshift);
   return hipGetLastError();
 }
+#endif  // HBCSF_WITH_DEFINE
 
 }  // namespace hbcsf
