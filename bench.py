@@ -26,9 +26,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 KERNELS = ("define", "coo", "csl", "csf")
 
-# HBM bytes per B-CSF-kernel launch (mean over the modes) measured with rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size; see profiles/.  None = not measured.
-MEASURED_TRAFFIC = {}
+# HBM-side bytes per B-CSF-kernel launch (mean over the modes) measured with rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE in two runs of this script, FETCH_SIZE scaled by 2.0 and WRITE_SIZE by
+# 1.0 (what the counters read for a 1 GiB device copy, --calibrate); profiles/counters_cfg5.md
+# holds the readings.  A workload without an entry reports null.
+MEASURED_TRAFFIC = {"cfg5": 2.0 * 5861633.4 * 1024 + 1.0 * 241882.1 * 1024}
 
 
 def algorithmic_bytes(st: dict, rank: int, order: int) -> dict:
@@ -68,6 +70,26 @@ def calibrate(torch, log) -> int:
         dt = (time.perf_counter() - t0) / 10
         res[name] = {"ms": round(dt * 1e3, 4), "GB/s": round(nbytes / dt / 1e9, 1), "bytes": nbytes}
         log(f"[calibrate] {name}: {res[name]}")
+    # Row-gather ceiling: random 128-byte rows from tables of growing size, no MTTKRP work.
+    from paper_1904_03329_amd import binding as B
+
+    n = 1 << 26
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    for rows in (256, 18_000, 1_000_000, 40_000_000):
+        table = torch.zeros((rows, 32), dtype=torch.float32, device="cuda")
+        idx = torch.randint(0, rows, (n,), dtype=torch.int64, device="cuda").to(torch.int32)
+        stream = torch.cuda.current_stream().cuda_stream
+        got = B.probe_row_gather(idx.data_ptr(), n, table.data_ptr(), rows, sink.data_ptr(), stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            B.probe_row_gather(idx.data_ptr(), n, table.data_ptr(), rows, sink.data_ptr(), stream)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        res[f"gather_rows_{rows}"] = {"ms": round(dt * 1e3, 4), "Grows/s": round(got / dt / 1e9, 1),
+                                      "GB/s": round(got * 128 / dt / 1e9, 1), "table_MB": round(rows * 128 / 1e6, 1)}
+        log(f"[calibrate] gather, uniform over {rows} rows: {res[f'gather_rows_{rows}']}")
+        del table, idx
     print(json.dumps({"calibrate": res}), flush=True)
     return 0
 

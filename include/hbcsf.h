@@ -144,6 +144,16 @@ int hbcsf_tune(hbcsf_tensor *t, int key, uint64_t value);
  * on this handle (0 = the last one).  Waits for that call's last event. */
 int hbcsf_kernel_ms(hbcsf_tensor *t, uint32_t calls_back, float ms[4]);
 
+/* Diagnostic, not part of the MTTKRP path: launches a kernel that only gathers rows of 32 floats
+ * (128 bytes, the R = 32 factor row) with the B-CSF kernel's lane mapping and discards them, so
+ * that the row-gather rate the memory system sustains can be put beside the kernels' rates.
+ *   idx        device [n] row numbers, each < table_rows (the caller guarantees this; n >= 65536).
+ *   table      device [table_rows][32] floats.     sink  device, at least 4 bytes.
+ *   rows_gathered  host, receives the number of rows the launch gathers (<= n).
+ * Asynchronous on hip_stream; the caller times it. */
+int hbcsf_probe_row_gather(const uint32_t *idx, uint64_t n, const float *table, uint64_t table_rows,
+                           float *sink, void *hip_stream, uint64_t *rows_gathered);
+
 void hbcsf_free(hbcsf_tensor *t);
 
 const char *hbcsf_strerror(int code);

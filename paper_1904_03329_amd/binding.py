@@ -22,8 +22,8 @@ OWNED_BIT = 0x80000000
 
 EXPORTS = (
     "hbcsf_build_format", "hbcsf_device_bytes", "hbcsf_upload", "hbcsf_mttkrp", "hbcsf_get_stats",
-    "hbcsf_host_array", "hbcsf_tune", "hbcsf_kernel_ms", "hbcsf_free", "hbcsf_strerror",
-    "hbcsf_last_error",
+    "hbcsf_host_array", "hbcsf_tune", "hbcsf_kernel_ms", "hbcsf_probe_row_gather", "hbcsf_free",
+    "hbcsf_strerror", "hbcsf_last_error",
 )
 
 
@@ -78,6 +78,8 @@ def lib():
         L.hbcsf_tune.argtypes = [vp, i32, u64]
         L.hbcsf_kernel_ms.restype = i32
         L.hbcsf_kernel_ms.argtypes = [vp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_float * 4)]
+        L.hbcsf_probe_row_gather.restype = i32
+        L.hbcsf_probe_row_gather.argtypes = [vp, u64, vp, u64, vp, vp, ctypes.POINTER(u64)]
         L.hbcsf_free.restype = None
         L.hbcsf_free.argtypes = [vp]
         L.hbcsf_strerror.restype = ctypes.c_char_p
@@ -165,6 +167,14 @@ def kernel_ms(h, calls_back: int = 0):
     ms = (ctypes.c_float * 4)()
     _check(lib().hbcsf_kernel_ms(h, calls_back, ctypes.byref(ms)))
     return [float(x) for x in ms]
+
+
+def probe_row_gather(idx_ptr: int, n: int, table_ptr: int, table_rows: int, sink_ptr: int, stream: int = 0) -> int:
+    """hbcsf_probe_row_gather: returns the number of rows the launch gathers."""
+    rows = ctypes.c_uint64()
+    _check(lib().hbcsf_probe_row_gather(ctypes.c_void_p(idx_ptr), n, ctypes.c_void_p(table_ptr), table_rows,
+                                        ctypes.c_void_p(sink_ptr), ctypes.c_void_p(stream), ctypes.byref(rows)))
+    return int(rows.value)
 
 
 def free(h):

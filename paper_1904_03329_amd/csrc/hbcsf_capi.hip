@@ -327,6 +327,29 @@ int hbcsf_kernel_ms(hbcsf_tensor* t, uint32_t calls_back, float ms[4]) {
   return HBCSF_OK;
 }
 
+int hbcsf_probe_row_gather(const uint32_t* idx, uint64_t n, const float* table, uint64_t table_rows,
+                           float* sink, void* hip_stream, uint64_t* rows_gathered) {
+  if (!idx || !table || !sink || !rows_gathered) return fail(HBCSF_EINVAL, "null argument");
+  if (table_rows == 0 || n < 64 * 1024) return fail(HBCSF_EINVAL, "need a table and at least 65536 indices");
+  int dev = 0, cu = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  e = hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return fail_hip(e, "hipDeviceGetAttribute");
+  uint64_t waves = (uint64_t)(cu > 0 ? cu : 256) * 64;
+  uint64_t perWave = n / waves / 64 * 64;
+  while (perWave == 0 && waves > 4) {
+    waves /= 2;
+    perWave = n / waves / 64 * 64;
+  }
+  waves = waves / 4 * 4;
+  if (perWave == 0 || waves == 0) return fail(HBCSF_EINVAL, "too few indices");
+  e = launch_probe_gather(idx, n, table, sink, (uint32_t)waves, (uint32_t)perWave, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail_hip(e, "launch of the gather probe");
+  *rows_gathered = waves * perWave;
+  return HBCSF_OK;
+}
+
 void hbcsf_free(hbcsf_tensor* t) {
   if (!t) return;
   for (auto& es : t->ring)

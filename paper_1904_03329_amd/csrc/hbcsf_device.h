@@ -64,6 +64,11 @@ inline hipError_t launch_group(int kind, int order, int G, int steps, bool wide,
 hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, int G,
                          uint32_t blocks, hipStream_t s);
 
+// Diagnostic row-gather probe: `waves` (a multiple of 4) wavefronts, each gathering `perWave`
+// (a multiple of 64) rows of 32 floats listed in idx.
+hipError_t launch_probe_gather(const uint32_t* idx, uint64_t n, const float* table, float* sink,
+                               uint32_t waves, uint32_t perWave, hipStream_t s);
+
 }  // namespace hbcsf
 
 #endif  // HBCSF_DEVICE_H_

@@ -670,6 +670,47 @@ hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, i
                      ownedBits, rows * (uint64_t)G, gshift);
   return hipGetLastError();
 }
+
+// ---------------------------------------------------------------------------------------
+// Diagnostic: the row-gather rate the memory system sustains for this access shape (128-byte
+// rows, 8 lanes x float4, 8 gathers in flight per lane group), with none of the MTTKRP work
+// around it.  Used to put a measured ceiling beside the kernels' achieved rates.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void probe_gather_kernel(const uint32_t* __restrict__ idx, uint64_t n,
+                                                           const float* __restrict__ table,
+                                                           float* __restrict__ sink, uint32_t perWave) {
+  constexpr int S = 8;
+  const int lane = threadIdx.x & 63;
+  const int g = lane >> 3, c = lane & 7;
+  const uint64_t wave = (uint64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const uint32_t per = perWave / 8;
+  uint64_t p = wave * perWave + (uint64_t)g * per;
+  const uint64_t pEnd = p + per;
+  float4 acc = f4zero();
+  for (; p + S <= pEnd && p + S <= n; p += S) {
+    uint32_t k[S];
+    float4 r[S];
+#pragma unroll
+    for (int t = 0; t < S; ++t) k[t] = idx[p + t];
+#pragma unroll
+    for (int t = 0; t < S; ++t)
+      r[t] = *reinterpret_cast<const float4*>(table + ((size_t)k[t] * 32 + (size_t)(4 * c)));
+#pragma unroll
+    for (int t = 0; t < S; ++t) {
+      acc.x += r[t].x;
+      acc.y += r[t].y;
+      acc.z += r[t].z;
+      acc.w += r[t].w;
+    }
+  }
+  if (acc.x == 123.456f) sink[0] = acc.x + acc.y + acc.z + acc.w;  // keeps the loads alive
+}
+
+hipError_t launch_probe_gather(const uint32_t* idx, uint64_t n, const float* table, float* sink,
+                               uint32_t waves, uint32_t perWave, hipStream_t s) {
+  hipLaunchKernelGGL(probe_gather_kernel, dim3(waves / 4), dim3(256), 0, s, idx, n, table, sink, perWave);
+  return hipGetLastError();
+}
 #endif  // HBCSF_WITH_DEFINE
 
 }  // namespace hbcsf
