@@ -94,6 +94,52 @@ def calibrate(torch, log) -> int:
     return 0
 
 
+def trace_cu_spread(torch, np, B, ht, dfacs, outs, order, log):
+    """Per-CU busy time (union of its wavefronts' [start, end] intervals) of the CSL and B-CSF kernels."""
+    cap = 1 << 20
+    buf = torch.zeros(4 + 4 * cap, dtype=torch.int64, device="cuda")
+    B.tune(ht.handle, B.TUNE_TRACE_CAPACITY, cap)
+    B.tune(ht.handle, B.TUNE_TRACE_BUFFER, buf.data_ptr())
+    result = []
+    for m in range(order):
+        buf[0] = 0
+        ht.mttkrp(m, dfacs, outs[m])
+        torch.cuda.synchronize()
+        n = min(int(buf[0].item()), cap)
+        rec = buf[4:4 + 4 * n].cpu().numpy().reshape(n, 4)
+        for kind, name in ((1, "csl"), (2, "csf")):
+            r = rec[rec[:, 0] == kind]
+            if r.shape[0] == 0:
+                continue
+            hw = r[:, 1] & 0xFFFFFFFF
+            xcc = r[:, 1] >> 32
+            cu_key = (xcc << 8) | (((hw >> 13) & 7) << 5) | (((hw >> 12) & 1) << 4) | ((hw >> 8) & 15)
+            t0 = int(r[:, 2].min())
+            span = (int(r[:, 3].max()) - t0) / 100.0  # wall clock ticks are 10 ns -> microseconds
+            busy = []
+            for key in np.unique(cu_key):
+                iv = r[cu_key == key][:, 2:4]
+                iv = iv[np.argsort(iv[:, 0])]
+                total, cur_s, cur_e = 0, int(iv[0, 0]), int(iv[0, 1])
+                for a, b in iv[1:]:
+                    if a > cur_e:
+                        total += cur_e - cur_s
+                        cur_s, cur_e = int(a), int(b)
+                    else:
+                        cur_e = max(cur_e, int(b))
+                busy.append((total + cur_e - cur_s) / 100.0)
+            busy = np.asarray(busy)
+            entry = {"mode": m, "kernel": name, "wavefronts": int(r.shape[0]), "cus": int(busy.size),
+                     "makespan_us": round(span, 1), "busy_us_mean": round(float(busy.mean()), 1),
+                     "busy_us_min": round(float(busy.min()), 1), "busy_us_max": round(float(busy.max()), 1),
+                     "max_over_mean": round(float(busy.max() / busy.mean()), 4),
+                     "cv": round(float(busy.std() / busy.mean()), 4)}
+            result.append(entry)
+            log(f"[bench] per-CU busy spread: {entry}")
+    B.tune(ht.handle, B.TUNE_TRACE_BUFFER, 0)
+    return result
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,6 +153,9 @@ def main() -> int:
     ap.add_argument("--group-mask", type=int, default=0)
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--kernel-steps", type=int, default=0)
+    ap.add_argument("--cu-spread", action="store_true",
+                    help="after the timed steps, trace every wavefront of one more pass and report the "
+                         "per-CU busy-time spread of the CSL and B-CSF kernels (profiling only)")
     ap.add_argument("--calibrate", action="store_true",
                     help="time a plain 1 GiB device copy, fill and read instead of the benchmark "
                          "(also the known-size kernel that scales the rocprofv3 byte counters)")
@@ -215,6 +264,10 @@ def main() -> int:
             csf_launches += 1
         log(f"[bench] mode {m}: {json.dumps(entry)}")
 
+    cu_spread = None
+    if args.cu_spread:
+        cu_spread = trace_cu_spread(torch, np, B, ht, dfacs, outs, order, log)
+
     achieved = csf_bytes / (csf_ms * 1e-3) / 1e9 if csf_ms > 0 else 0.0
     roofline = {
         "kernel": f"csf_group_kernel<{rank // 4},{order}>",
@@ -276,6 +329,8 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }
+    if cu_spread is not None:
+        line["cu_busy_spread"] = cu_spread
     print(json.dumps(line), flush=True)
     ht.close()
     return 0

@@ -137,6 +137,20 @@ int hbcsf_host_array(const hbcsf_tensor *t, int mode, int group, int level, int 
                                         automatic (default 128)                                 */
 #define HBCSF_TUNE_STEPS            3 /* gathers a lane group keeps in flight: 4 or 8 (default 8;
                                         4 is only available at rank 32)                         */
+#define HBCSF_TUNE_KERNEL_MASK      4 /* which kernels hbcsf_mttkrp launches: bit0 define, bit1 COO,
+                                        bit2 CSL, bit3 CSF (default 15).  For ablation and profiling
+                                        only: with bits cleared the output is incomplete.        */
+#define HBCSF_TUNE_TRACE_BUFFER     5 /* device address (8-byte aligned) of a caller-owned buffer of
+                                        8 * (4 + 4 * capacity) bytes, or 0 = tracing off.  With a
+                                        buffer set, every wavefront of the CSL and B-CSF kernels
+                                        appends one record {kernel (1 = CSL, 2 = CSF), XCC_ID << 32
+                                        | HW_ID, start, end} (four uint64, times from the 100 MHz
+                                        wall clock) after word 0, which counts the records.  The
+                                        caller zeroes word 0 before a call.  Profiling only.       */
+#define HBCSF_TUNE_TRACE_CAPACITY   6 /* records the trace buffer holds; further ones are dropped  */
+#define HBCSF_TUNE_PERSISTENT       7 /* 0 (default): one wavefront per span of T_s nonzeros;
+                                        1: only resident wavefronts are launched and each XCD's
+                                        wavefronts take its spans round-robin                   */
 int hbcsf_tune(hbcsf_tensor *t, int key, uint64_t value);
 
 /* With HBCSF_TUNE_PROFILE on: milliseconds of the four kernels (define, COO, CSL, CSF; 0 for a

@@ -28,6 +28,10 @@ struct hbcsf_tensor {
   uint64_t sliceThreshold = 0;
   uint64_t wavesPerCU = 0;   // launch sizing override, 0 = default
   int steps = 8;             // records in flight per lane group
+  uint32_t kernelMask = 15;  // bit0 define, bit1 COO, bit2 CSL, bit3 CSF
+  bool persistent = false;   // resident wavefronts walk the spans round-robin
+  unsigned long long* trace = nullptr;  // caller's device buffer for wavefront traces
+  uint64_t traceCapacity = 0;
   // profiling: a ring of event sets, one per hbcsf_mttkrp call
   struct EventSet {
     hipEvent_t ev[5];
@@ -164,7 +168,7 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
   }
 
   // 1. define every output row that no plain store will write
-  {
+  if (t->kernelMask & 1u) {
     // one wavefront per 32 rows, capped at 64 wavefronts per compute unit
     uint64_t blocks = ((f.rows + 31) / 32 + 3) / 4;
     const uint64_t cap = (uint64_t)t->numCU * 16;
@@ -172,17 +176,17 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
     if (blocks == 0) blocks = 1;
     e = launch_define(out, (const uint32_t*)(base + f.ownedBits.off), f.rows, G, (uint32_t)blocks, s);
     if (e != hipSuccess) return fail_hip(e, "launch of the output-definition kernel");
-    if (es) {
-      es->launched[0] = true;
-      (void)hipEventRecord(es->ev[1], s);
-    }
+    if (es) es->launched[0] = true;
+  } else if (es) {
+    es->launched[0] = false;
   }
+  if (es) (void)hipEventRecord(es->ev[1], s);
 
   // 2. the three group kernels (execute step of Algorithm "HB-CSF-MTTKRP")
   for (int g = 0; g < 3; ++g) {
     const GroupFormat& gf = f.g[g];
     bool launched = false;
-    if (gf.nnz > 0) {
+    if (gf.nnz > 0 && (t->kernelMask & (2u << g))) {
       GroupArgs a;
       std::memset(&a, 0, sizeof(a));
       for (int l = 0; l < N; ++l) {
@@ -197,6 +201,8 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
       a.runs = (uint32_t)gf.runs;
       a.lshift = lshift;
       a.nUnits = (uint32_t)((gf.runs + NG - 1) / NG);
+      a.trace = t->trace;
+      a.traceCapacity = (uint32_t)t->traceCapacity;
       uint32_t blocks, threads;
       size_t lds = 0;
       if (g == kCoo) {
@@ -223,8 +229,9 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
         }
         if (upw == 0) upw = 1;
         a.unitsPerWave = (uint32_t)upw;
-        const uint64_t waves = (a.nUnits + upw - 1) / upw;
-        blocks = round_up8((waves + wpb - 1) / wpb);
+        a.nSpans = (uint32_t)((a.nUnits + upw - 1) / upw);
+        a.persistent = t->persistent ? 1u : 0u;
+        blocks = (uint32_t)t->numCU;  // the launcher sizes the grid
       }
       bool wide = false;
       for (int l = 1; l < N; ++l)
@@ -300,6 +307,26 @@ int hbcsf_tune(hbcsf_tensor* t, int key, uint64_t value) {
   if (key == HBCSF_TUNE_WAVES_PER_CU) {
     if (value > 1024) return fail(HBCSF_EINVAL, "waves per CU must be at most 1024");
     t->wavesPerCU = value;
+    return HBCSF_OK;
+  }
+  if (key == HBCSF_TUNE_TRACE_BUFFER) {
+    if (value & 7) return fail(HBCSF_EINVAL, "the trace buffer must be 8-byte aligned");
+    t->trace = (unsigned long long*)(uintptr_t)value;
+    if (!t->trace) t->traceCapacity = 0;
+    return HBCSF_OK;
+  }
+  if (key == HBCSF_TUNE_TRACE_CAPACITY) {
+    if (value > 0xffffffffull) return fail(HBCSF_EINVAL, "trace capacity too large");
+    t->traceCapacity = value;
+    return HBCSF_OK;
+  }
+  if (key == HBCSF_TUNE_PERSISTENT) {
+    t->persistent = value != 0;
+    return HBCSF_OK;
+  }
+  if (key == HBCSF_TUNE_KERNEL_MASK) {
+    if (value > 15) return fail(HBCSF_EINVAL, "kernel mask must be 0..15");
+    t->kernelMask = (uint32_t)value;
     return HBCSF_OK;
   }
   if (key == HBCSF_TUNE_STEPS) {

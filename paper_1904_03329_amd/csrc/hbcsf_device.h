@@ -21,13 +21,21 @@ struct GroupArgs {
   uint32_t runs;                // ceil(nnz / L)
   uint32_t lshift;              // log2 L
   uint32_t nUnits;              // ceil(runs / lane groups per wavefront)
-  uint32_t unitsPerWave;        // contiguous units one wavefront works through
+  uint32_t unitsPerWave;        // consecutive units in one span
+  uint32_t nSpans;              // ceil(nUnits / unitsPerWave)
+  uint32_t persistent;          // 1: resident wavefronts take spans round-robin; 0: one wavefront per span
+  // Optional wavefront trace (profiling only, nullptr = off): trace[0] counts records; record i
+  // is the four words at trace[4 + 4 i]: {kernel kind, XCC_ID << 32 | HW_ID, start, end} with
+  // start / end from the constant-rate wall clock.
+  unsigned long long* trace;
+  uint32_t traceCapacity;       // records the buffer can hold
 };
 
 // kind: KernelKind; order 3 or 4; G = rank / 4 lanes per factor row (2, 4, 8, 16 or 32);
 // steps = records a lane group keeps in flight (4 or 8); wide = some gathered factor matrix
 // is 4 GiB or larger (64-bit row addressing).  One launch function per (G, order) pair, each
-// compiled in its own object file.
+// compiled in its own object file.  For the CSL and B-CSF kernels `blocks` is the number of compute
+// units and the launcher sizes the grid (one wavefront per span, or persistent).
 #define HBCSF_DECLARE_LAUNCH(G, N)                                                                  \
   hipError_t launch_group_g##G##_n##N(int kind, int steps, bool wide, const GroupArgs& a,          \
                                       uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s);

@@ -86,11 +86,32 @@ __device__ __forceinline__ float4 scale4(float s, const float4& x) {
   return make_float4(s * x.x, s * x.y, s * x.z, s * x.w);
 }
 
-// Blocks are dealt round-robin to the 8 XCDs; give each XCD a contiguous part of the stream
-// so that one slice's partial rows and its factor rows stay within one L2 where possible.
-__device__ __forceinline__ uint32_t logical_block() {
-  const uint32_t nb = gridDim.x;  // a multiple of 8
-  return (blockIdx.x & 7u) * (nb >> 3) + (blockIdx.x >> 3);
+// Which spans a wavefront works through.  Blocks are dealt round-robin to the 8 XCDs and the
+// grid is a multiple of 8, so XCD x = blockIdx % 8 is given the x-th eighth of the stream: one
+// slice's partial rows and its factor rows then stay within one L2 where possible.
+//   default      one wavefront per span (the grid has as many wavefronts as spans);
+//   persistent   a grid of resident blocks only; an XCD's wavefronts take the spans of its
+//                eighth round-robin, so each gets the same number of spans from all over it.
+struct SpanWalk {
+  uint32_t first, end, stride;
+};
+
+__device__ __forceinline__ SpanWalk span_walk(const GroupArgs& a, int wib, int wpb) {
+  const uint32_t xcd = blockIdx.x & 7u;
+  const uint32_t local = (blockIdx.x >> 3) * (uint32_t)wpb + (uint32_t)wib;  // wavefront within its XCD
+  const uint32_t wavesPerXcd = (gridDim.x >> 3) * (uint32_t)wpb;
+  SpanWalk w;
+  if (a.persistent) {
+    const uint32_t perXcd = (a.nSpans + 7u) >> 3;
+    w.stride = wavesPerXcd;
+    w.first = __builtin_amdgcn_readfirstlane(xcd * perXcd + local);
+    w.end = min((xcd + 1u) * perXcd, a.nSpans);
+  } else {
+    w.stride = 1;
+    w.first = __builtin_amdgcn_readfirstlane(xcd * wavesPerXcd + local);
+    w.end = min(w.first + 1u, a.nSpans);
+  }
+  return w;
 }
 
 // Pending partial row of a lane group, merged at the end of the wavefront's span.
@@ -110,6 +131,23 @@ __device__ __forceinline__ void final_merge(float* __restrict__ out, bool pend, 
     if (g == 0) row_atomic<G>(out, pendRow, c, acc);
   } else if (pend) {
     row_atomic<G>(out, pendRow, c, acc);
+  }
+}
+
+// One trace record per wavefront: which compute unit it ran on and when (profiling only).
+__device__ __forceinline__ void trace_wave(const GroupArgs& a, int kind, unsigned long long t0, int lane) {
+  if (a.trace == nullptr || lane != 0) return;
+  const unsigned long long t1 = wall_clock64();
+  // s_getreg_b32: HW_ID (register 4, 32 bits) = wave / SIMD / CU / SH / SE ids; XCC_ID (register 20, 4 bits)
+  const uint32_t hw = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);
+  const uint32_t xcc = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20);
+  const unsigned long long slot = atomicAdd(a.trace, 1ull);
+  if (slot < a.traceCapacity) {
+    unsigned long long* r = a.trace + 4 + 4 * slot;
+    r[0] = (unsigned long long)kind;
+    r[1] = ((unsigned long long)xcc << 32) | hw;
+    r[2] = t0;
+    r[3] = t1;
   }
 }
 
@@ -380,20 +418,20 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
   constexpr uint32_t L = 1u << LS;
   uint32_t* rec = lds + (size_t)wib * (NG * (L + 1) * RW);
 
-  // wave-uniform by construction; say so, so that unit bookkeeping runs on the scalar unit
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(logical_block() * wpb + wib);
-  uint32_t u = wave * a.unitsPerWave;
-  const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
 
   const float* __restrict__ facLeaf = a.fac[N - 1];
   const float* __restrict__ facDeep = a.fac[N - 2];   // deepest fiber level
   const float* __restrict__ facTop = a.fac[1];        // level 1 (same as facDeep when N = 3)
 
+  const unsigned long long traceStart = a.trace ? wall_clock64() : 0ull;
+  const SpanWalk walk = span_walk(a, wib, wpb);
+  for (uint32_t span = walk.first; span < walk.end; span += walk.stride) {
+  uint32_t u = span * a.unitsPerWave;
+  const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
   float4 acc = f4zero();
   bool pend = false;
   uint32_t pendRow = 0;
 
-  if (u >= uEnd) return;
   UnitBounds cur = load_bounds<G, N, true>(a, u, lane);
   uint32_t fLo[2] = {0, 0};
 #pragma unroll
@@ -465,6 +503,8 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   }
   final_merge<G>(a.out, pend, pendRow, acc, g, c);
+  }  // spans
+  trace_wave(a, kCsfKernel, traceStart, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -484,16 +524,16 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
   constexpr uint32_t L = 1u << LS;
   uint32_t* rec = lds + (size_t)wib * (NG * (L + 1) * RW);
 
-  // wave-uniform by construction; say so, so that unit bookkeeping runs on the scalar unit
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(logical_block() * wpb + wib);
-  uint32_t u = wave * a.unitsPerWave;
-  const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
 
+  const unsigned long long traceStart = a.trace ? wall_clock64() : 0ull;
+  const SpanWalk walk = span_walk(a, wib, wpb);
+  for (uint32_t span = walk.first; span < walk.end; span += walk.stride) {
+  uint32_t u = span * a.unitsPerWave;
+  const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
   float4 acc = f4zero();
   bool pend = false;
   uint32_t pendRow = 0;
 
-  if (u >= uEnd) return;
   UnitBounds cur = load_bounds<G, N, false>(a, u, lane);
   const uint32_t fLo[2] = {0, 0};
 
@@ -545,6 +585,8 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   }
   final_merge<G>(a.out, pend, pendRow, acc, g, c);
+  }  // spans
+  trace_wave(a, kCslKernel, traceStart, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -610,10 +652,31 @@ __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
 // ---------------------------------------------------------------------------------------
 namespace {
 
+// `grid` carries the number of compute units.  Default launch: one wavefront per span.  Persistent
+// launch: (resident blocks per CU) x CUs blocks, capped by the spans.  Both rounded to a multiple of 8.
 template <int G, int N, int LS, int S, bool WIDE>
 hipError_t launch_one(int kind, const GroupArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
-  if (kind == kCsfKernel) hipLaunchKernelGGL((csf_group_kernel<G, N, LS, S, WIDE>), grid, block, lds, s, a);
-  else hipLaunchKernelGGL((csl_group_kernel<G, N, LS, S, WIDE>), grid, block, lds, s, a);
+  auto csf = csf_group_kernel<G, N, LS, S, WIDE>;
+  auto csl = csl_group_kernel<G, N, LS, S, WIDE>;
+  static int perCu[2] = {0, 0};  // resident blocks per CU, asked once per kernel
+  const int which = kind == kCsfKernel ? 1 : 0;
+  if (perCu[which] == 0) {
+    int n = 0;
+    const hipError_t e = which ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, csf, (int)block.x, lds)
+                               : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, csl, (int)block.x, lds);
+    if (e != hipSuccess) return e;
+    perCu[which] = n > 0 ? n : 1;
+  }
+  const uint32_t wpb = block.x >> 6;
+  const uint64_t need = ((uint64_t)a.nSpans + wpb - 1) / wpb;
+  uint64_t blocks = need;
+  if (a.persistent) {
+    blocks = (uint64_t)grid.x * (uint64_t)perCu[which];
+    if (blocks > need) blocks = need;
+  }
+  blocks = (blocks + 7) / 8 * 8;
+  if (which) hipLaunchKernelGGL(csf, dim3((uint32_t)blocks), block, lds, s, a);
+  else hipLaunchKernelGGL(csl, dim3((uint32_t)blocks), block, lds, s, a);
   return hipGetLastError();
 }
 
