@@ -151,6 +151,11 @@ int hbcsf_host_array(const hbcsf_tensor *t, int mode, int group, int level, int 
 #define HBCSF_TUNE_PERSISTENT       7 /* 0 (default): one wavefront per span of T_s nonzeros;
                                         1: only resident wavefronts are launched and each XCD's
                                         wavefronts take its spans round-robin                   */
+#define HBCSF_TUNE_STREAM_BYTES     8 /* factor matrices of fiber (middle) levels that are at least
+                                        this many bytes are gathered with streaming loads, so that
+                                        their rows, which are not reused while cached, do not evict
+                                        the leaf factor's popular rows from the L2; 0 = never;
+                                        default 2^30                                              */
 int hbcsf_tune(hbcsf_tensor *t, int key, uint64_t value);
 
 /* With HBCSF_TUNE_PROFILE on: milliseconds of the four kernels (define, COO, CSL, CSF; 0 for a

@@ -30,6 +30,7 @@ struct hbcsf_tensor {
   int steps = 8;             // records in flight per lane group
   uint32_t kernelMask = 15;  // bit0 define, bit1 COO, bit2 CSL, bit3 CSF
   bool persistent = false;   // resident wavefronts walk the spans round-robin
+  uint64_t streamBytes = 1ull << 30;  // fiber-level factors at least this large are gathered with streaming loads
   unsigned long long* trace = nullptr;  // caller's device buffer for wavefront traces
   uint64_t traceCapacity = 0;
   // profiling: a ring of event sets, one per hbcsf_mttkrp call
@@ -231,6 +232,10 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
         a.unitsPerWave = (uint32_t)upw;
         a.nSpans = (uint32_t)((a.nUnits + upw - 1) / upw);
         a.persistent = t->persistent ? 1u : 0u;
+        a.streamLevel = 0;
+        if (g == kCsf)
+          for (int l = 1; l < N - 1; ++l)
+            if (t->dims[f.levelMode[l]] * (uint64_t)rank * 4ull >= t->streamBytes) a.streamLevel |= 1u << l;
         blocks = (uint32_t)t->numCU;  // the launcher sizes the grid
       }
       bool wide = false;
@@ -318,6 +323,10 @@ int hbcsf_tune(hbcsf_tensor* t, int key, uint64_t value) {
   if (key == HBCSF_TUNE_TRACE_CAPACITY) {
     if (value > 0xffffffffull) return fail(HBCSF_EINVAL, "trace capacity too large");
     t->traceCapacity = value;
+    return HBCSF_OK;
+  }
+  if (key == HBCSF_TUNE_STREAM_BYTES) {
+    t->streamBytes = value ? value : ~0ull;  // 0 = never
     return HBCSF_OK;
   }
   if (key == HBCSF_TUNE_PERSISTENT) {

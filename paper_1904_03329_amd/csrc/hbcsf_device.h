@@ -23,6 +23,7 @@ struct GroupArgs {
   uint32_t nUnits;              // ceil(runs / lane groups per wavefront)
   uint32_t unitsPerWave;        // consecutive units in one span
   uint32_t nSpans;              // ceil(nUnits / unitsPerWave)
+  uint32_t streamLevel;         // bit l: the factor rows of fiber level l are gathered with streaming loads
   uint32_t persistent;          // 1: resident wavefronts take spans round-robin; 0: one wavefront per span
   // Optional wavefront trace (profiling only, nullptr = off): trace[0] counts records; record i
   // is the four words at trace[4 + 4 i]: {kernel kind, XCC_ID << 32 | HW_ID, start, end} with

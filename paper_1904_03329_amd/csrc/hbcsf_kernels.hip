@@ -50,6 +50,21 @@ __device__ __forceinline__ float4 row_load(const float* __restrict__ base, uint3
   }
 }
 
+// Streaming variant: the row is not expected to be used again while it could still be cached, so
+// it should not push reusable rows out of the L2.
+template <int G, bool WIDE>
+__device__ __forceinline__ float4 row_load_streaming(const float* __restrict__ base, uint32_t row, int c) {
+  const f32x4* p;
+  if (WIDE) {
+    p = reinterpret_cast<const f32x4*>(base + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c)));
+  } else {
+    const uint32_t off = row * (uint32_t)(16 * G) + (uint32_t)(16 * c);
+    p = reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(base) + off);
+  }
+  const f32x4 v = __builtin_nontemporal_load(p);
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
 template <int G>
 __device__ __forceinline__ void row_store(float* __restrict__ out, uint32_t row, int c, float4 a) {
   store_streaming(reinterpret_cast<float4*>(out + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c))), a);
@@ -468,8 +483,14 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
         // load issued before it has arrived too, and the leaf rows can be awaited one by one.
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
-          if (rr[t].z) br[t] = row_load<G, WIDE>(facDeep, rr[t].z - 1u, c);
-          if (N == 4 && rr[t].w) ar[t] = row_load<G, WIDE>(facTop, rr[t].w - 1u, c);
+          if (rr[t].z) {
+            br[t] = (a.streamLevel & (1u << (N - 2))) ? row_load_streaming<G, WIDE>(facDeep, rr[t].z - 1u, c)
+                                                       : row_load<G, WIDE>(facDeep, rr[t].z - 1u, c);
+          }
+          if (N == 4 && rr[t].w) {
+            ar[t] = (a.streamLevel & 2u) ? row_load_streaming<G, WIDE>(facTop, rr[t].w - 1u, c)
+                                         : row_load<G, WIDE>(facTop, rr[t].w - 1u, c);
+          }
         }
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) cr[t] = row_load<G, WIDE>(facLeaf, rr[t].x, c);

@@ -243,6 +243,27 @@ def test_duplicates_empty_and_errors(oracle):
     assert B.strerror(-2) == "index or size out of range"
 
 
+def test_tuning_keys_are_validated():
+    h = B.build_format((4, 4, 4), [np.array([1], np.uint32)] * 3, np.array([1.0], np.float32))
+    B.tune(h, B.TUNE_SLICE_THRESHOLD, 4096)
+    B.tune(h, B.TUNE_WAVES_PER_CU, 64)
+    B.tune(h, B.TUNE_STEPS, 4)
+    B.tune(h, B.TUNE_KERNEL_MASK, 8)
+    B.tune(h, B.TUNE_PERSISTENT, 1)
+    B.tune(h, B.TUNE_STREAM_BYTES, 0)
+    B.tune(h, B.TUNE_TRACE_CAPACITY, 10)
+    B.tune(h, B.TUNE_TRACE_BUFFER, 0)
+    for key, bad in ((B.TUNE_STEPS, 5), (B.TUNE_KERNEL_MASK, 16), (B.TUNE_WAVES_PER_CU, 5000),
+                     (B.TUNE_TRACE_BUFFER, 12), (99, 1)):
+        with pytest.raises(B.HbcsfError) as e:
+            B.tune(h, key, bad)
+        assert e.value.code == -1
+    with pytest.raises(B.HbcsfError) as e:       # no profiled call yet
+        B.kernel_ms(h, 0)
+    assert e.value.code == -4
+    B.free(h)
+
+
 def test_wide_coordinates_use_the_128_bit_sort_key(oracle):
     """Dimensions whose packed coordinate exceeds 64 bits (as FROSTT's larger tensors do)."""
     rng = np.random.default_rng(5)

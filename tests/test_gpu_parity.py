@@ -154,3 +154,51 @@ def test_repeated_calls_overwrite(oracle):
     with pytest.raises(B.HbcsfError):
         B.kernel_ms(t.handle, 2)
     t.close()
+
+
+def test_launch_variants_and_diagnostics(oracle):
+    """Persistent span walk, streaming middle-level loads, 4 gathers in flight, the kernel mask, the
+    wavefront trace and the row-gather probe."""
+    import torch
+    from paper_1904_03329_amd import HbcsfTensor
+    rng = np.random.default_rng(43)
+    dims = (6000, 500, 70)
+    inds, vals = _skewed(rng, dims, 150_000)
+    facs = _factors(rng, dims, 32)
+    want = [oracle.mttkrp(dims, inds, vals, facs, m) for m in range(3)]
+    t = HbcsfTensor(dims, inds, vals).to_device()
+    d = [torch.from_numpy(f).cuda() for f in facs]
+    for key, value in ((B.TUNE_PERSISTENT, 1), (B.TUNE_STREAM_BYTES, 1), (B.TUNE_STEPS, 4), (B.TUNE_WAVES_PER_CU, 7)):
+        B.tune(t.handle, key, value)
+        for m in range(3):
+            GU.assert_close(t.mttkrp(m, d).cpu().numpy(), want[m], f"tune {key}={value} mode {m}")
+    # the four kernels one by one give the same result as one call
+    out = torch.full((dims[0], 32), float("nan"), device="cuda")
+    for mask in (1, 2, 4, 8):
+        B.tune(t.handle, B.TUNE_KERNEL_MASK, mask)
+        t.mttkrp(0, d, out)
+    B.tune(t.handle, B.TUNE_KERNEL_MASK, 15)
+    GU.assert_close(out.cpu().numpy(), want[0], "kernel by kernel")
+    # trace: one record per wavefront of the CSL and B-CSF kernels, on at most 256 compute units
+    cap = 1 << 16
+    buf = torch.zeros(4 + 4 * cap, dtype=torch.int64, device="cuda")
+    B.tune(t.handle, B.TUNE_TRACE_CAPACITY, cap)
+    B.tune(t.handle, B.TUNE_TRACE_BUFFER, buf.data_ptr())
+    GU.assert_close(t.mttkrp(0, d).cpu().numpy(), want[0], "traced call")
+    n = int(buf[0].item())
+    rec = buf[4:4 + 4 * n].cpu().numpy().reshape(n, 4)
+    assert 0 < n <= cap and set(np.unique(rec[:, 0]).tolist()) <= {1, 2}
+    assert np.all(rec[:, 3] >= rec[:, 2])
+    cu = ((rec[:, 1] >> 32) << 8) | ((((rec[:, 1] & 0xFFFFFFFF) >> 8) & 0xFF))
+    assert np.unique(cu).size <= 256
+    B.tune(t.handle, B.TUNE_TRACE_BUFFER, 0)
+    t.close()
+    # the probe gathers what it says and rejects bad arguments
+    idx = torch.randint(0, 1000, (1 << 17,), device="cuda").to(torch.int32)
+    table = torch.ones((1000, 32), device="cuda")
+    sink = torch.zeros(4, device="cuda")
+    rows = B.probe_row_gather(idx.data_ptr(), idx.numel(), table.data_ptr(), 1000, sink.data_ptr())
+    torch.cuda.synchronize()
+    assert 0 < rows <= idx.numel()
+    with pytest.raises(B.HbcsfError):
+        B.probe_row_gather(idx.data_ptr(), 10, table.data_ptr(), 1000, sink.data_ptr())
