@@ -286,7 +286,7 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle  # test infrastructure: used here for the reported CPU baseline only
 
-        sample = min(t.nnz, 12_000_000)
+        sample = min(t.nnz, 30_000_000)
         si = [x[:sample] for x in t.inds]
         sv = t.vals[:sample]
         t0 = time.perf_counter()

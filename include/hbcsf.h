@@ -106,10 +106,12 @@ int hbcsf_upload(hbcsf_tensor *t, void *device_arena, uint64_t bytes, void *hip_
  *            16-byte aligned; factors[mode] is ignored (may be NULL).
  *   out      device [dims[mode]][rank], 16-byte aligned, OVERWRITTEN: every row is defined
  *            (rows of empty slices are zero), as Algorithm "COO-MTTKRP" returns Y from zero.
- * Launches the output-definition kernel, then the COO-group, CSL-group and B-CSF-group
- * kernels (Algorithm "HB-CSF-MTTKRP", execute step).  Slices that span several work units
+ * Launches the output-definition kernel, then the COO-group, CSL-group and B-CSF-group kernels
+ * (Algorithm "HB-CSF-MTTKRP", execute step); for small outputs the COO group's rows are written
+ * by the output-definition pass instead (HBCSF_TUNE_FUSE_COO).  Slices that span several work units
  * are merged with fp32 atomic adds (Section IV-A), so results can differ between runs in
- * the last bits.  NaN / Inf inputs propagate. */
+ * the last bits.  NaN / Inf inputs propagate.  Calls on one handle must not overlap in time when
+ * profiling (HBCSF_TUNE_PROFILE) or tracing is on; otherwise the handle is read-only here. */
 int hbcsf_mttkrp(const hbcsf_tensor *t, int mode, int rank, const float *const *factors,
                  float *out, void *hip_stream);
 
@@ -126,6 +128,8 @@ int hbcsf_get_stats(const hbcsf_tensor *t, int mode, hbcsf_stats *stats);
 #define HBCSF_ARR_RUNFIRST   3 /* uint32: slice / segment holding the first nonzero of each run,
                                   runs+1 entries                                                  */
 #define HBCSF_ARR_OWNED_BITS 4 /* uint32 bitmap over output rows: 1 = written by one plain store */
+#define HBCSF_ARR_COO_BITS   5 /* uint32 bitmap over output rows: 1 = row of a COO-group slice    */
+#define HBCSF_ARR_COO_PTR    6 /* uint32: COO-group nonzeros before each 32-row word, words+1     */
 int hbcsf_host_array(const hbcsf_tensor *t, int mode, int group, int level, int array_id,
                      const void **ptr, uint64_t *count);
 
@@ -156,6 +160,11 @@ int hbcsf_host_array(const hbcsf_tensor *t, int mode, int group, int level, int 
                                         their rows, which are not reused while cached, do not evict
                                         the leaf factor's popular rows from the L2; 0 = never;
                                         default 2^30                                              */
+#define HBCSF_TUNE_FUSE_COO         9 /* 1: the rows of COO-group slices are computed and written by
+                                        the output-definition pass (their kernel time is then
+                                        reported under "define" and the COO kernel is not
+                                        launched); 0: separate COO kernel; 2 (default): fused when
+                                        the output is at most 64 MiB, where it saves a launch     */
 int hbcsf_tune(hbcsf_tensor *t, int key, uint64_t value);
 
 /* With HBCSF_TUNE_PROFILE on: milliseconds of the four kernels (define, COO, CSL, CSF; 0 for a

@@ -30,6 +30,7 @@ struct hbcsf_tensor {
   int steps = 8;             // records in flight per lane group
   uint32_t kernelMask = 15;  // bit0 define, bit1 COO, bit2 CSL, bit3 CSF
   bool persistent = false;   // resident wavefronts walk the spans round-robin
+  int fuseCoo = 2;           // COO-group rows written by the output-definition pass: 0 never, 1 always, 2 small outputs
   uint64_t streamBytes = 1ull << 30;  // fiber-level factors at least this large are gathered with streaming loads
   unsigned long long* trace = nullptr;  // caller's device buffer for wavefront traces
   uint64_t traceCapacity = 0;
@@ -39,8 +40,9 @@ struct hbcsf_tensor {
     bool launched[4] = {false, false, false, false};
     bool valid = false;
   };
-  std::vector<EventSet> ring;
-  uint64_t calls = 0;  // profiled calls so far
+  // hbcsf_mttkrp takes a const handle; recording a profiled call is bookkeeping, not state of the tensor
+  mutable std::vector<EventSet> ring;
+  mutable uint64_t calls = 0;  // profiled calls so far
 };
 
 namespace {
@@ -135,9 +137,8 @@ int hbcsf_upload(hbcsf_tensor* t, void* device_arena, uint64_t bytes, void* hip_
   return HBCSF_OK;
 }
 
-int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const* factors, float* out,
+int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* factors, float* out,
                  void* hip_stream) {
-  hbcsf_tensor* t = const_cast<hbcsf_tensor*>(tc);
   if (!t || !factors || !out) return fail(HBCSF_EINVAL, "null argument");
   if (mode < 0 || mode >= t->order) return fail(HBCSF_EINVAL, "mode out of range");
   if (!(rank == 8 || rank == 16 || rank == 32 || rank == 64 || rank == 128))
@@ -168,14 +169,43 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
     if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
   }
 
-  // 1. define every output row that no plain store will write
+  auto group_args = [&](int g) {
+    const GroupFormat& gf = f.g[g];
+    GroupArgs a;
+    std::memset(&a, 0, sizeof(a));
+    for (int l = 0; l < N; ++l) {
+      a.ind[l] = gf.ind[l].present ? (const uint32_t*)(base + gf.ind[l].off) : nullptr;
+      a.ptr[l] = gf.ptr[l].present ? (const uint32_t*)(base + gf.ptr[l].off) : nullptr;
+      a.runFirst[l] = gf.runFirst[l].present ? (const uint32_t*)(base + gf.runFirst[l].off) : nullptr;
+      a.fac[l] = l == 0 ? nullptr : factors[f.levelMode[l]];
+    }
+    return a;
+  };
+  bool wide = false;  // some gathered factor matrix needs 64-bit row addressing
+  for (int l = 1; l < N; ++l) wide = wide || t->dims[f.levelMode[l]] * (uint64_t)rank * 4ull >= (1ull << 32);
+
+  // 1. define every output row that no plain store will write; the COO group's rows are written
+  //    in the same pass
+  // (measured: the fused pass saves a launch on small outputs but hides latency worse on large ones)
+  const bool wantFuse = t->fuseCoo == 1 || (t->fuseCoo == 2 && f.rows * (uint64_t)rank * 4ull <= (64ull << 20));
+  const bool fuseCoo = wantFuse && (t->kernelMask & 3u) == 3u && f.g[kCoo].nnz > 0;
   if (t->kernelMask & 1u) {
     // one wavefront per 32 rows, capped at 64 wavefronts per compute unit
     uint64_t blocks = ((f.rows + 31) / 32 + 3) / 4;
     const uint64_t cap = (uint64_t)t->numCU * 16;
     if (blocks > cap) blocks = cap;
     if (blocks == 0) blocks = 1;
-    e = launch_define(out, (const uint32_t*)(base + f.ownedBits.off), f.rows, G, (uint32_t)blocks, s);
+    if (fuseCoo) {
+      GroupArgs a = group_args(kCoo);
+      a.val = (const float*)(base + f.g[kCoo].val.off);
+      a.out = out;
+      a.nnz = (uint32_t)f.g[kCoo].nnz;
+      e = launch_define_coo(N, G, wide, a, (const uint32_t*)(base + f.ownedBits.off),
+                            (const uint32_t*)(base + f.cooBits.off), (const uint32_t*)(base + f.cooPtr.off),
+                            f.rows, (uint32_t)blocks, s);
+    } else {
+      e = launch_define(out, (const uint32_t*)(base + f.ownedBits.off), f.rows, G, (uint32_t)blocks, s);
+    }
     if (e != hipSuccess) return fail_hip(e, "launch of the output-definition kernel");
     if (es) es->launched[0] = true;
   } else if (es) {
@@ -187,15 +217,8 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
   for (int g = 0; g < 3; ++g) {
     const GroupFormat& gf = f.g[g];
     bool launched = false;
-    if (gf.nnz > 0 && (t->kernelMask & (2u << g))) {
-      GroupArgs a;
-      std::memset(&a, 0, sizeof(a));
-      for (int l = 0; l < N; ++l) {
-        a.ind[l] = gf.ind[l].present ? (const uint32_t*)(base + gf.ind[l].off) : nullptr;
-        a.ptr[l] = gf.ptr[l].present ? (const uint32_t*)(base + gf.ptr[l].off) : nullptr;
-        a.runFirst[l] = gf.runFirst[l].present ? (const uint32_t*)(base + gf.runFirst[l].off) : nullptr;
-        a.fac[l] = l == 0 ? nullptr : factors[f.levelMode[l]];
-      }
+    if (gf.nnz > 0 && (t->kernelMask & (2u << g)) && !(g == kCoo && fuseCoo)) {
+      GroupArgs a = group_args(g);
       a.val = (const float*)(base + gf.val.off);
       a.out = out;
       a.nnz = (uint32_t)gf.nnz;
@@ -238,9 +261,6 @@ int hbcsf_mttkrp(const hbcsf_tensor* tc, int mode, int rank, const float* const*
             if (t->dims[f.levelMode[l]] * (uint64_t)rank * 4ull >= t->streamBytes) a.streamLevel |= 1u << l;
         blocks = (uint32_t)t->numCU;  // the launcher sizes the grid
       }
-      bool wide = false;
-      for (int l = 1; l < N; ++l)
-        wide = wide || t->dims[f.levelMode[l]] * (uint64_t)rank * 4ull >= (1ull << 32);
       e = launch_group(g, N, G, t->steps, wide, a, blocks, threads, lds, s);
       if (e != hipSuccess) return fail_hip(e, "launch of a group kernel");
       launched = true;
@@ -272,6 +292,10 @@ int hbcsf_host_array(const hbcsf_tensor* t, int mode, int group, int level, int 
   const ArrayRef* r = nullptr;
   if (array_id == HBCSF_ARR_OWNED_BITS) {
     r = &f.ownedBits;
+  } else if (array_id == HBCSF_ARR_COO_BITS) {
+    r = &f.cooBits;
+  } else if (array_id == HBCSF_ARR_COO_PTR) {
+    r = &f.cooPtr;
   } else {
     if (group < 0 || group > 2 || level < 0 || level >= t->order) return fail(HBCSF_EINVAL, "group or level out of range");
     const GroupFormat& g = f.g[group];
@@ -327,6 +351,11 @@ int hbcsf_tune(hbcsf_tensor* t, int key, uint64_t value) {
   }
   if (key == HBCSF_TUNE_STREAM_BYTES) {
     t->streamBytes = value ? value : ~0ull;  // 0 = never
+    return HBCSF_OK;
+  }
+  if (key == HBCSF_TUNE_FUSE_COO) {
+    if (value > 2) return fail(HBCSF_EINVAL, "fuse mode must be 0, 1 or 2");
+    t->fuseCoo = (int)value;
     return HBCSF_OK;
   }
   if (key == HBCSF_TUNE_PERSISTENT) {

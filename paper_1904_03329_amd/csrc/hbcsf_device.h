@@ -39,7 +39,10 @@ struct GroupArgs {
 // units and the launcher sizes the grid (one wavefront per span, or persistent).
 #define HBCSF_DECLARE_LAUNCH(G, N)                                                                  \
   hipError_t launch_group_g##G##_n##N(int kind, int steps, bool wide, const GroupArgs& a,          \
-                                      uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s);
+                                      uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s); \
+  hipError_t launch_define_coo_g##G##_n##N(bool wide, const GroupArgs& a, const uint32_t* ownedBits,   \
+                                           const uint32_t* cooBits, const uint32_t* cooPtr, uint64_t rows, \
+                                           uint32_t blocks, hipStream_t s);
 HBCSF_DECLARE_LAUNCH(2, 3)
 HBCSF_DECLARE_LAUNCH(4, 3)
 HBCSF_DECLARE_LAUNCH(8, 3)
@@ -58,6 +61,26 @@ inline hipError_t launch_group(int kind, int order, int G, int steps, bool wide,
   case GV:                                                                                          \
     return order == 3 ? launch_group_g##GV##_n3(kind, steps, wide, a, blocks, threads, ldsBytes, s) \
                       : launch_group_g##GV##_n4(kind, steps, wide, a, blocks, threads, ldsBytes, s);
+  switch (G) {
+    HBCSF_CASE(2)
+    HBCSF_CASE(4)
+    HBCSF_CASE(8)
+    HBCSF_CASE(16)
+    HBCSF_CASE(32)
+    default:
+      return hipErrorInvalidValue;
+  }
+#undef HBCSF_CASE
+}
+
+// Output definition fused with the COO group (a: the COO group's arguments).
+inline hipError_t launch_define_coo(int order, int G, bool wide, const GroupArgs& a, const uint32_t* ownedBits,
+                                    const uint32_t* cooBits, const uint32_t* cooPtr, uint64_t rows,
+                                    uint32_t blocks, hipStream_t s) {
+#define HBCSF_CASE(GV)                                                                                     \
+  case GV:                                                                                                 \
+    return order == 3 ? launch_define_coo_g##GV##_n3(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s) \
+                      : launch_define_coo_g##GV##_n4(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s);
   switch (G) {
     HBCSF_CASE(2)
     HBCSF_CASE(4)

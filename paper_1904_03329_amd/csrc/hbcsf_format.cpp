@@ -291,6 +291,8 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   }
   const uint64_t ownedWords = (out->rows + 31) / 32;
   out->ownedBits = lay.add(ownedWords);
+  out->cooBits = lay.add(ownedWords);
+  out->cooPtr = lay.add(ownedWords + 1);
   out->blobBytes = lay.bytes;
   void* mem = nullptr;
   if (posix_memalign(&mem, kAlign, (size_t)lay.bytes) != 0 || !mem) {
@@ -301,6 +303,8 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   auto U32 = [&](const ArrayRef& r) { return (uint32_t*)(out->blob + r.off); };
   uint32_t* owned = U32(out->ownedBits);
   std::memset(owned, 0, ownedWords * 4);
+  uint32_t* cooBits = U32(out->cooBits);
+  std::memset(cooBits, 0, ownedWords * 4);
 
   GroupFormat& Go = out->g[kCoo];
   GroupFormat& Gl = out->g[kCsl];
@@ -334,6 +338,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
     if (g == kCoo) {
       for (int l = 0; l < N; ++l) cooInd[l][a] = idx(l, b);
       cooVal[a] = V[b];
+      __atomic_fetch_or(&cooBits[root >> 5], 1u << (root & 31), __ATOMIC_RELAXED);
     } else {
       own = (a / L) == ((a + n - 1) / L);
       uint32_t* run0 = g == kCsl ? cslRun : csfRun[0];
@@ -368,6 +373,16 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
       if (!own) ++sharedSlices;
     }
     if (own) __atomic_fetch_or(&owned[root >> 5], 1u << (root & 31), __ATOMIC_RELAXED);
+  }
+  {
+    // COO-group nonzeros are stored in row order, so a running count over the bitmap locates them
+    uint32_t* cooPtr = U32(out->cooPtr);
+    uint32_t run = 0;
+    for (uint64_t w = 0; w < ownedWords; ++w) {
+      cooPtr[w] = run;
+      run += (uint32_t)__builtin_popcount(cooBits[w]);
+    }
+    cooPtr[ownedWords] = run;
   }
   // sentinels and pads
   cslInd[0][Gl.n[0]] = 0;

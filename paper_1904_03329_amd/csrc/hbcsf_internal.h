@@ -46,6 +46,8 @@ struct ModeFormat {
   uint64_t rows = 0;               // dims[mode]
   GroupFormat g[3];
   ArrayRef ownedBits;
+  ArrayRef cooBits;                // bitmap over output rows: 1 = the row belongs to a COO-group slice
+  ArrayRef cooPtr;                 // COO-group nonzeros before each 32-row word (words + 1 entries)
   uint8_t* blob = nullptr;         // host copy of all arrays, kAlign-aligned
   uint64_t blobBytes = 0;
   uint64_t devOffset = 0;          // where the blob sits in the device arena

@@ -618,7 +618,7 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
 template <int G, int N, bool WIDE>
 __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
   constexpr int NG = 64 / G;
-  constexpr int kU = G < 4 ? G : 4;  // nonzeros per lane group in flight
+  constexpr int kU = G < 8 ? G : 8;  // nonzeros per lane group in flight
   const int lane = threadIdx.x & 63;
   const int g = lane / G, c = lane % G;
   const uint32_t waves = (gridDim.x * blockDim.x) >> 6;
@@ -662,6 +662,76 @@ __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
           float4 pr = mul4(x1[t], x2[t]);
           if (N == 4) pr = mul4(pr, x3[t]);
           row_store<G>(a.out, i0[t], c, scale4(__uint_as_float(v[t]), pr));
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Output definition fused with the COO group.  The rows of single-nonzero slices are scattered
+// thinly over the output (about one row in five on the hypersparse workloads), and writing them
+// in a pass of their own costs far more DRAM time per byte than writing them together with the
+// zero fill of their neighbours.  One wavefront takes one 32-row word at a time: rows of the
+// COO group get v * hadamard(factor rows), rows that nothing else stores get zeros, rows owned
+// by a CSL / CSF slice are left alone.  COO nonzeros are stored in row order, so the nonzero of
+// a row is cooPtr[word] + (number of COO rows before it in the word).
+// ---------------------------------------------------------------------------------------
+template <int G, int N, bool WIDE>
+__global__ __launch_bounds__(256) void define_coo_kernel(const GroupArgs a, const uint32_t* __restrict__ ownedBits,
+                                                         const uint32_t* __restrict__ cooBits,
+                                                         const uint32_t* __restrict__ cooPtr, uint64_t rows) {
+  constexpr int NG = 64 / G;
+  constexpr int RPG = 32 / NG;              // rows of a word per lane group (NG <= 32)
+  constexpr int CH = RPG < 4 ? RPG : 4;     // rows per lane group handled together
+  const int lane = threadIdx.x & 63;
+  const int g = lane / G, c = lane % G;
+  const uint32_t waves = (gridDim.x * blockDim.x) >> 6;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+  const uint64_t words = (rows + 31) >> 5;
+  const uint32_t* __restrict__ valb = reinterpret_cast<const uint32_t*>(a.val);
+  for (uint64_t wd = wave; wd < words; wd += waves) {
+    const uint32_t wo = ownedBits[wd];
+    const uint32_t wc = cooBits[wd];
+    const uint32_t zBase = cooPtr[wd];
+#pragma unroll
+    for (int qb = 0; qb < RPG; qb += CH) {
+      uint32_t i1[CH], i2[CH], i3[CH], v[CH];
+      bool isCoo[CH], fill[CH];
+#pragma unroll
+      for (int q = 0; q < CH; ++q) {
+        const uint32_t bit = (uint32_t)(g * RPG + qb + q);
+        const uint64_t row = (wd << 5) + bit;
+        isCoo[q] = ((wc >> bit) & 1u) != 0u;
+        fill[q] = row < rows && !isCoo[q] && ((wo >> bit) & 1u) == 0u;
+        i1[q] = i2[q] = i3[q] = v[q] = 0;
+        if (isCoo[q]) {
+          const uint32_t z = zBase + (uint32_t)__builtin_popcount(wc & ((1u << bit) - 1u));
+          i1[q] = a.ind[1][z];
+          i2[q] = a.ind[2][z];
+          if (N == 4) i3[q] = a.ind[3][z];
+          v[q] = valb[z];
+        }
+      }
+      float4 x1[CH], x2[CH], x3[CH];
+#pragma unroll
+      for (int q = 0; q < CH; ++q) {
+        if (isCoo[q]) {
+          x1[q] = row_load<G, WIDE>(a.fac[1], i1[q], c);
+          x2[q] = row_load<G, WIDE>(a.fac[2], i2[q], c);
+          if (N == 4) x3[q] = row_load<G, WIDE>(a.fac[3], i3[q], c);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < CH; ++q) {
+        const uint32_t bit = (uint32_t)(g * RPG + qb + q);
+        float4* dst = reinterpret_cast<float4*>(a.out + (((wd << 5) + bit) * (uint64_t)(4 * G) + (uint64_t)(4 * c)));
+        if (isCoo[q]) {
+          float4 pr = mul4(x1[q], x2[q]);
+          if (N == 4) pr = mul4(pr, x3[q]);
+          store_streaming(dst, scale4(__uint_as_float(v[q]), pr));
+        } else if (fill[q]) {
+          store_streaming(dst, f4zero());
         }
       }
     }
@@ -738,6 +808,19 @@ hipError_t launch_g(int kind, int steps, bool wide, const GroupArgs& a, dim3 gri
 #endif
 #define HBCSF_CAT2(a, b, c, d) a##b##c##d
 #define HBCSF_CAT(a, b, c, d) HBCSF_CAT2(a, b, c, d)
+
+hipError_t HBCSF_CAT(launch_define_coo_g, HBCSF_G, _n, HBCSF_N)(bool wide, const GroupArgs& a,
+                                                               const uint32_t* ownedBits, const uint32_t* cooBits,
+                                                               const uint32_t* cooPtr, uint64_t rows, uint32_t blocks,
+                                                               hipStream_t s) {
+  if (wide)
+    hipLaunchKernelGGL((define_coo_kernel<HBCSF_G, HBCSF_N, true>), dim3(blocks), dim3(256), 0, s, a, ownedBits,
+                       cooBits, cooPtr, rows);
+  else
+    hipLaunchKernelGGL((define_coo_kernel<HBCSF_G, HBCSF_N, false>), dim3(blocks), dim3(256), 0, s, a, ownedBits,
+                       cooBits, cooPtr, rows);
+  return hipGetLastError();
+}
 
 hipError_t HBCSF_CAT(launch_group_g, HBCSF_G, _n, HBCSF_N)(int kind, int steps, bool wide, const GroupArgs& a,
                                                           uint32_t blocks, uint32_t threads, size_t ldsBytes,

@@ -168,7 +168,8 @@ def test_launch_variants_and_diagnostics(oracle):
     want = [oracle.mttkrp(dims, inds, vals, facs, m) for m in range(3)]
     t = HbcsfTensor(dims, inds, vals).to_device()
     d = [torch.from_numpy(f).cuda() for f in facs]
-    for key, value in ((B.TUNE_PERSISTENT, 1), (B.TUNE_STREAM_BYTES, 1), (B.TUNE_STEPS, 4), (B.TUNE_WAVES_PER_CU, 7)):
+    for key, value in ((B.TUNE_PERSISTENT, 1), (B.TUNE_STREAM_BYTES, 1), (B.TUNE_STEPS, 4), (B.TUNE_WAVES_PER_CU, 7),
+                       (B.TUNE_FUSE_COO, 0), (B.TUNE_FUSE_COO, 1)):
         B.tune(t.handle, key, value)
         for m in range(3):
             GU.assert_close(t.mttkrp(m, d).cpu().numpy(), want[m], f"tune {key}={value} mode {m}")
