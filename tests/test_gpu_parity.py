@@ -203,3 +203,19 @@ def test_launch_variants_and_diagnostics(oracle):
     assert 0 < rows <= idx.numel()
     with pytest.raises(B.HbcsfError):
         B.probe_row_gather(idx.data_ptr(), 10, table.data_ptr(), 1000, sink.data_ptr())
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_small_tensors(oracle, seed):
+    """Small random tensors with duplicates, empty slices and every option drawn at random."""
+    rng = np.random.default_rng(1000 + seed)
+    order = int(rng.choice([3, 4]))
+    dims = tuple(int(x) for x in rng.integers(1, 60, size=order))
+    nnz = int(rng.integers(0, 6000))
+    inds = [rng.integers(0, d, size=nnz).astype(np.uint32) for d in dims]
+    vals = rng.uniform(-1, 1, size=nnz).astype(np.float32)
+    rank = int(rng.choice([8, 16, 32, 64]))
+    opts = dict(fiber_threshold=int(rng.choice([0, 8, 16, 32, 64])), group_mask=int(rng.integers(0, 5)),
+                mode_order_policy=int(rng.integers(0, 3)))
+    print("random", seed, dims, nnz, rank, opts, flush=True)
+    _check_all_modes(oracle, dims, inds, vals, _factors(rng, dims, rank), f"random {seed}", **opts)
