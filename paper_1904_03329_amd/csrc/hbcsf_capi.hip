@@ -190,8 +190,8 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
   const bool wantFuse = t->fuseCoo == 1 || (t->fuseCoo == 2 && f.rows * (uint64_t)rank * 4ull <= (64ull << 20));
   const bool fuseCoo = wantFuse && (t->kernelMask & 3u) == 3u && f.g[kCoo].nnz > 0;
   if (t->kernelMask & 1u) {
-    // one wavefront per 32 rows, capped at 64 wavefronts per compute unit
-    uint64_t blocks = ((f.rows + 31) / 32 + 3) / 4;
+    // one wavefront per 8 x 32 rows, capped at 64 wavefronts per compute unit
+    uint64_t blocks = ((f.rows + 255) / 256 + 3) / 4;
     const uint64_t cap = (uint64_t)t->numCU * 16;
     if (blocks > cap) blocks = cap;
     if (blocks == 0) blocks = 1;

@@ -401,13 +401,18 @@ __global__ __launch_bounds__(256) void define_rows_kernel(float4* __restrict__ o
   const uint64_t perWord = (uint64_t)32 << gshift;      // float4s covered by one bitmap word
   const uint64_t words = (nvec + perWord - 1) / perWord;
   const int reps = (int)(perWord >> 6);                  // stores per lane per word (G / 2)
-  for (uint64_t wd = wave; wd < words; wd += waves) {
-    const uint32_t w = ownedBits[wd];
-    const uint64_t base = wd * perWord;
-    for (int q = 0; q < reps; ++q) {
-      const uint32_t f = (uint32_t)q * 64u + lane;        // float4 within the word's 32 rows
-      const uint64_t t = base + f;
-      if (t < nvec && !((w >> (f >> gshift)) & 1u)) store_streaming(out + t, f4zero());
+  // a wavefront fills kChunk consecutive words (kChunk x 32 rows) before it strides on
+  constexpr uint64_t kChunk = 8;
+  for (uint64_t w0 = (uint64_t)wave * kChunk; w0 < words; w0 += (uint64_t)waves * kChunk) {
+    const uint64_t w1 = min(w0 + kChunk, words);
+    for (uint64_t wd = w0; wd < w1; ++wd) {
+      const uint32_t w = ownedBits[wd];
+      const uint64_t base = wd * perWord;
+      for (int q = 0; q < reps; ++q) {
+        const uint32_t f = (uint32_t)q * 64u + lane;        // float4 within the word's 32 rows
+        const uint64_t t = base + f;
+        if (t < nvec && !((w >> (f >> gshift)) & 1u)) store_streaming(out + t, f4zero());
+      }
     }
   }
 }
