@@ -196,6 +196,9 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
     if (blocks > cap) blocks = cap;
     if (blocks == 0) blocks = 1;
     if (fuseCoo) {
+      blocks = ((f.rows + 31) / 32 + 3) / 4;  // the fused pass takes one 32-row word per wavefront iteration
+      if (blocks > cap) blocks = cap;
+      if (blocks == 0) blocks = 1;
       GroupArgs a = group_args(kCoo);
       a.val = (const float*)(base + f.g[kCoo].val.off);
       a.out = out;
