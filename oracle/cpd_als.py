@@ -1,0 +1,61 @@
+"""TEST INFRASTRUCTURE ONLY: plain CPU oracle of one CPD-ALS iteration (Section II-B, Eq. 1-3, Algorithm
+"CPD-ALS").  Nothing in the product path may import this file; it shares no code with the GPU library.
+
+One iteration, in the algorithm's order and notation, for an order-N tensor with factor matrices A_1..A_N:
+
+    for n = 1..N:   A_n <- X_(n) (Khatri-Rao of the other factors) (Hadamard_{m != n} A_m^T A_m)^+
+    normalise the columns of every A_n and store the norms in lambda
+
+The first product is the mode-n MTTKRP (Section II-C, Eq. 4), evaluated here per nonzero in fp64 with numpy
+(Eq. 7); ^+ is the Moore-Penrose pseudo-inverse (numpy.linalg.pinv).  Everything is fp64.
+
+Readings (the paper leaves them open): "normalise columns ... and store in lambda" is done once at the end of
+the iteration, as the algorithm lists it; the norm is the 2-norm; lambda_r is the product over the modes of the
+r-th column norms, so that [[lambda; A_1..A_N]] is the same model as the unnormalised factors; a zero column is
+left as it is (norm taken as 1).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def mttkrp(dims, inds, vals, factors, mode):
+    """fp64 mode-`mode` MTTKRP from fp64 factor matrices: M[i_n] += v * prod_{m != n} A_m[i_m]."""
+    rank = factors[(mode + 1) % len(dims)].shape[1]
+    prod = np.repeat(np.asarray(vals, dtype=np.float64)[:, None], rank, axis=1)
+    for m in range(len(dims)):
+        if m != mode:
+            prod = prod * np.asarray(factors[m], dtype=np.float64)[np.asarray(inds[m], dtype=np.int64)]
+    out = np.zeros((dims[mode], rank))
+    np.add.at(out, np.asarray(inds[mode], dtype=np.int64), prod)
+    return out
+
+
+def als_iteration(dims, inds, vals, factors):
+    """One iteration of Algorithm "CPD-ALS".  factors: list of [dims[m], R] arrays (any float dtype).
+    Returns (new fp64 factors with unit-norm columns, lambda)."""
+    order = len(dims)
+    a = [np.array(f, dtype=np.float64) for f in factors]
+    rank = a[0].shape[1]
+    for n in range(order):
+        m_n = mttkrp(dims, inds, vals, a, n)
+        v = np.ones((rank, rank))
+        for m in range(order):
+            if m != n:
+                v = v * (a[m].T @ a[m])
+        a[n] = m_n @ np.linalg.pinv(v)
+    lam = np.ones(rank)
+    for n in range(order):
+        norms = np.sqrt((a[n] * a[n]).sum(axis=0))
+        norms = np.where(norms > 0, norms, 1.0)
+        a[n] = a[n] / norms
+        lam = lam * norms
+    return a, lam
+
+
+def model_values(inds, factors, lam):
+    """Values of the model [[lambda; A_1..A_N]] (Eq. 1) at the given coordinates."""
+    p = np.repeat(np.asarray(lam, dtype=np.float64)[None, :], len(inds[0]), axis=0)
+    for m, f in enumerate(factors):
+        p = p * np.asarray(f, dtype=np.float64)[np.asarray(inds[m], dtype=np.int64)]
+    return p.sum(axis=1)
