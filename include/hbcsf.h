@@ -172,6 +172,58 @@ int hbcsf_tune(hbcsf_tensor *t, int key, uint64_t value);
  * on this handle (0 = the last one).  Waits for that call's last event. */
 int hbcsf_kernel_ms(hbcsf_tensor *t, uint32_t calls_back, float ms[4]);
 
+/* ---------------------------------------------------------------------------------------------
+ * CPD-ALS iteration (Section II-B: Eq. 1 the model, Eq. 2-3 the mode update, Algorithm "CPD-ALS")
+ * built around hbcsf_mttkrp.  One iteration updates every factor in turn,
+ *     A_n <- MTTKRP_n(X; other factors) * pinv( Hadamard_{m != n} A_m^T A_m ),
+ * then leaves all factors with unit-2-norm columns and lambda_r = product over the modes of the
+ * r-th column norms (a zero column keeps norm 1).  The MTTKRP, the Gram matrix and the product
+ * with the R x R matrix run on the device in fp32 (Gram sums are accumulated in fp64); the
+ * R x R algebra (Hadamard products, pseudo-inverse, norms, fit) runs on the host in fp64.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct hbcsf_als hbcsf_als;
+
+#define HBCSF_ALS_KEEP_GRAMS 1 /* flag: the factors are exactly as this state's previous
+                                  hbcsf_als_iteration left them, so their Gram matrices need not
+                                  be recomputed (saves order-1 passes over the factors)           */
+
+/* Device workspace an ALS state needs for this tensor and rank: one [max dim][rank] fp32 matrix
+ * for the MTTKRP result plus two rank x rank matrices. */
+int hbcsf_als_workspace_bytes(const hbcsf_tensor *t, int rank, uint64_t *bytes);
+
+/* Creates an ALS state for an uploaded tensor.  workspace: device memory, 256-byte aligned, at
+ * least hbcsf_als_workspace_bytes; the caller owns it and keeps it and the tensor alive and
+ * untouched until hbcsf_als_free.  Allocates a few KB of pinned host memory.  rank as for
+ * hbcsf_mttkrp.  Errors: EINVAL, ESTATE (tensor not uploaded), ENOMEM (workspace too small),
+ * EHIP. */
+int hbcsf_als_create(const hbcsf_tensor *t, int rank, void *workspace, uint64_t workspace_bytes,
+                     hbcsf_als **out);
+
+/* One iteration.  factors: host array of `order` device pointers, factors[m] = [dims[m]][rank]
+ * fp32 row-major, read and overwritten in place (factors[0]'s content on entry is not used, as in
+ * the algorithm).  lambda: device [rank] fp32, written; may be null.  fit: host, may be null;
+ * receives 1 - ||X - model|| / ||X|| computed from the Gram matrices and the last MTTKRP (the
+ * nonzero coordinates are taken to be distinct).  flags: 0 or HBCSF_ALS_KEEP_GRAMS.
+ * Blocking: the host reads an R x R matrix back for every mode, so the call returns after the
+ * work on hip_stream has finished.  Two calls on one state must not overlap.  Errors: EINVAL,
+ * and whatever hbcsf_mttkrp reports. */
+int hbcsf_als_iteration(hbcsf_als *a, float *const *factors, float *lambda, int flags, double *fit,
+                        void *hip_stream);
+
+/* Device/host time of the last iteration, summed over the modes, in milliseconds: ms[0] MTTKRP,
+ * ms[1] Gram kernel with its read-back, ms[2] host R x R algebra, ms[3] product kernel with its
+ * R x R upload. */
+int hbcsf_als_phase_ms(const hbcsf_als *a, float ms[4]);
+
+/* Host only (no device call): the pseudo-inverse the mode update applies to the Hadamard product of
+ * Gram matrices (Eq. 3).  v, out: host [n][n] fp64, v symmetric, 1 <= n <= 128.  A safely positive
+ * definite v is inverted by Cholesky factorisation; otherwise eigenvalues below 1e-15 of the largest
+ * magnitude are treated as zero. */
+int hbcsf_sym_pinv(const double *v, int n, double *out);
+
+/* Releases the state (not the workspace, not the tensor). */
+void hbcsf_als_free(hbcsf_als *a);
+
 /* Diagnostic, not part of the MTTKRP path: launches a kernel that only gathers rows of 32 floats
  * (128 bytes, the R = 32 factor row) with the B-CSF kernel's lane mapping and discards them, so
  * that the row-gather rate the memory system sustains can be put beside the kernels' rates.

@@ -59,3 +59,19 @@ def model_values(inds, factors, lam):
     for m, f in enumerate(factors):
         p = p * np.asarray(f, dtype=np.float64)[np.asarray(inds[m], dtype=np.int64)]
     return p.sum(axis=1)
+
+
+def fit(dims, inds, vals, factors, lam):
+    """1 - ||X - model|| / ||X|| for a sparse X with distinct coordinates, without forming the model densely:
+    ||X - model||^2 = ||X||^2 - 2 <X, model> + ||model||^2, the inner product summed over the nonzeros and
+    ||model||^2 = sum_{r,s} lambda_r lambda_s prod_m (A_m^T A_m)[r, s]."""
+    vals = np.asarray(vals, dtype=np.float64)
+    lam = np.asarray(lam, dtype=np.float64)
+    inner = float((vals * model_values(inds, factors, lam)).sum())
+    g = np.outer(lam, lam)
+    for f in factors:
+        f = np.asarray(f, dtype=np.float64)
+        g = g * (f.T @ f)
+    x2 = float((vals * vals).sum())
+    res2 = max(x2 - 2.0 * inner + float(g.sum()), 0.0)
+    return 1.0 - np.sqrt(res2) / np.sqrt(x2)

@@ -8,7 +8,7 @@ from __future__ import annotations
 
 from . import binding
 
-__all__ = ["binding", "HbcsfTensor"]
+__all__ = ["binding", "HbcsfTensor", "CpdAls"]
 
 
 class HbcsfTensor:
@@ -66,6 +66,47 @@ class HbcsfTensor:
             binding.free(self.handle)
             self.handle = None
         self._arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class CpdAls:
+    """CPD-ALS iterations on a device-resident HbcsfTensor; PyTorch supplies the workspace and the stream."""
+
+    def __init__(self, tensor: HbcsfTensor, rank: int):
+        import torch
+
+        self.tensor = tensor
+        self.rank = int(rank)
+        n = binding.als_workspace_bytes(tensor.handle, self.rank)
+        self._ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+        self.handle = binding.als_create(tensor.handle, self.rank, self._ws.data_ptr(), n)
+        self.lam = torch.ones(self.rank, dtype=torch.float32, device="cuda")
+
+    def iteration(self, factors, keep_grams: bool = False) -> float:
+        """Updates the CUDA float32 factor matrices in place, stores lambda in self.lam, returns the fit."""
+        import torch
+
+        for m, f in enumerate(factors):
+            if (f.dtype != torch.float32 or not f.is_cuda or not f.is_contiguous()
+                    or tuple(f.shape) != (self.tensor.dims[m], self.rank)):
+                raise ValueError(f"factor {m} must be a contiguous float32 CUDA tensor [{self.tensor.dims[m]}, {self.rank}]")
+        return binding.als_iteration(self.handle, [f.data_ptr() for f in factors], self.lam.data_ptr(),
+                                     binding.ALS_KEEP_GRAMS if keep_grams else 0, True,
+                                     torch.cuda.current_stream().cuda_stream)
+
+    def phase_ms(self):
+        return binding.als_phase_ms(self.handle)
+
+    def close(self):
+        if self.handle is not None:
+            binding.als_free(self.handle)
+            self.handle = None
+        self._ws = None
 
     def __del__(self):
         try:

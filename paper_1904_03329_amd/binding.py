@@ -20,11 +20,13 @@ TUNE_SLICE_THRESHOLD, TUNE_PROFILE, TUNE_WAVES_PER_CU, TUNE_STEPS, TUNE_KERNEL_M
 TUNE_TRACE_BUFFER, TUNE_TRACE_CAPACITY, TUNE_PERSISTENT, TUNE_STREAM_BYTES, TUNE_FUSE_COO = 5, 6, 7, 8, 9
 GROUP_COO, GROUP_CSL, GROUP_CSF = 0, 1, 2
 OWNED_BIT = 0x80000000
+ALS_KEEP_GRAMS = 1
 
 EXPORTS = (
     "hbcsf_build_format", "hbcsf_device_bytes", "hbcsf_upload", "hbcsf_mttkrp", "hbcsf_get_stats",
     "hbcsf_host_array", "hbcsf_tune", "hbcsf_kernel_ms", "hbcsf_probe_row_gather", "hbcsf_free",
     "hbcsf_strerror", "hbcsf_last_error",
+    "hbcsf_als_workspace_bytes", "hbcsf_als_create", "hbcsf_als_iteration", "hbcsf_als_phase_ms", "hbcsf_als_free", "hbcsf_sym_pinv",
 )
 
 
@@ -87,6 +89,18 @@ def lib():
         L.hbcsf_strerror.argtypes = [i32]
         L.hbcsf_last_error.restype = ctypes.c_char_p
         L.hbcsf_last_error.argtypes = []
+        L.hbcsf_als_workspace_bytes.restype = i32
+        L.hbcsf_als_workspace_bytes.argtypes = [vp, i32, ctypes.POINTER(u64)]
+        L.hbcsf_als_create.restype = i32
+        L.hbcsf_als_create.argtypes = [vp, i32, vp, u64, ctypes.POINTER(vp)]
+        L.hbcsf_als_iteration.restype = i32
+        L.hbcsf_als_iteration.argtypes = [vp, vp, vp, i32, ctypes.POINTER(ctypes.c_double), vp]
+        L.hbcsf_als_phase_ms.restype = i32
+        L.hbcsf_als_phase_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4)]
+        L.hbcsf_sym_pinv.restype = i32
+        L.hbcsf_sym_pinv.argtypes = [vp, i32, vp]
+        L.hbcsf_als_free.restype = None
+        L.hbcsf_als_free.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -176,6 +190,46 @@ def probe_row_gather(idx_ptr: int, n: int, table_ptr: int, table_rows: int, sink
     _check(lib().hbcsf_probe_row_gather(ctypes.c_void_p(idx_ptr), n, ctypes.c_void_p(table_ptr), table_rows,
                                         ctypes.c_void_p(sink_ptr), ctypes.c_void_p(stream), ctypes.byref(rows)))
     return int(rows.value)
+
+
+def als_workspace_bytes(h, rank: int) -> int:
+    n = ctypes.c_uint64()
+    _check(lib().hbcsf_als_workspace_bytes(h, rank, ctypes.byref(n)))
+    return int(n.value)
+
+
+def als_create(h, rank: int, workspace_ptr: int, nbytes: int):
+    """hbcsf_als_create: workspace_ptr is a device address."""
+    a = ctypes.c_void_p()
+    _check(lib().hbcsf_als_create(h, rank, ctypes.c_void_p(workspace_ptr), nbytes, ctypes.byref(a)))
+    return a
+
+
+def als_iteration(a, factor_ptrs, lambda_ptr: int = 0, flags: int = 0, want_fit: bool = True, stream: int = 0):
+    """hbcsf_als_iteration: device addresses in, the fit (or None) out."""
+    arr = (ctypes.c_void_p * len(factor_ptrs))(*factor_ptrs)
+    fit = ctypes.c_double()
+    _check(lib().hbcsf_als_iteration(a, ctypes.cast(arr, ctypes.c_void_p), ctypes.c_void_p(lambda_ptr or None), flags,
+                                     ctypes.byref(fit) if want_fit else None, ctypes.c_void_p(stream)))
+    return float(fit.value) if want_fit else None
+
+
+def als_phase_ms(a):
+    ms = (ctypes.c_float * 4)()
+    _check(lib().hbcsf_als_phase_ms(a, ctypes.byref(ms)))
+    return [float(x) for x in ms]
+
+
+def sym_pinv(v: np.ndarray) -> np.ndarray:
+    """hbcsf_sym_pinv: host fp64 symmetric matrix in, its pseudo-inverse out."""
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    out = np.empty_like(v)
+    _check(lib().hbcsf_sym_pinv(v.ctypes.data, v.shape[0], out.ctypes.data))
+    return out
+
+
+def als_free(a):
+    lib().hbcsf_als_free(a)
 
 
 def free(h):

@@ -38,9 +38,10 @@ def build(verbose: bool = False) -> str:
             defs = [f"-DHBCSF_G={g}", f"-DHBCSF_N={n}"] + (["-DHBCSF_WITH_DEFINE"] if (g, n) == (8, 3) else [])
             jobs.append(["hipcc"] + HIP_FLAGS + inc + defs + ["-c", os.path.join(CSRC, "hbcsf_kernels.hip"), "-o", o])
             objs.append(o)
-    o = os.path.join(CSRC, "hbcsf_capi.o")
-    jobs.append(["hipcc"] + HIP_FLAGS + inc + ["-c", os.path.join(CSRC, "hbcsf_capi.hip"), "-o", o])
-    objs.append(o)
+    for name in ("hbcsf_capi", "hbcsf_als"):
+        o = os.path.join(CSRC, name + ".o")
+        jobs.append(["hipcc"] + HIP_FLAGS + inc + ["-c", os.path.join(CSRC, name + ".hip"), "-o", o])
+        objs.append(o)
     workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 4))))
     with ThreadPoolExecutor(workers) as pool:
         list(pool.map(run, jobs))

@@ -12,42 +12,17 @@
 #include "hbcsf.h"
 #include "hbcsf_device.h"
 #include "hbcsf_internal.h"
+#include "hbcsf_tensor.h"
 
 using namespace hbcsf;
-
-struct hbcsf_tensor {
-  int order = 0;
-  uint64_t dims[HBCSF_MAX_ORDER] = {0, 0, 0, 0};
-  uint64_t nnz = 0;
-  hbcsf_opts opts{};
-  std::unique_ptr<ModeFormat> modes[HBCSF_MAX_ORDER];
-  uint64_t arenaBytes = 0;
-  uint8_t* arena = nullptr;  // caller's device memory
-  bool uploaded = false;
-  int numCU = 256;
-  uint64_t sliceThreshold = 0;
-  uint64_t wavesPerCU = 0;   // launch sizing override, 0 = default
-  int steps = 8;             // records in flight per lane group
-  uint32_t kernelMask = 15;  // bit0 define, bit1 COO, bit2 CSL, bit3 CSF
-  bool persistent = false;   // resident wavefronts walk the spans round-robin
-  int fuseCoo = 2;           // COO-group rows written by the output-definition pass: 0 never, 1 always, 2 small outputs
-  uint64_t streamBytes = 1ull << 30;  // fiber-level factors at least this large are gathered with streaming loads
-  unsigned long long* trace = nullptr;  // caller's device buffer for wavefront traces
-  uint64_t traceCapacity = 0;
-  // profiling: a ring of event sets, one per hbcsf_mttkrp call
-  struct EventSet {
-    hipEvent_t ev[5];
-    bool launched[4] = {false, false, false, false};
-    bool valid = false;
-  };
-  // hbcsf_mttkrp takes a const handle; recording a profiled call is bookkeeping, not state of the tensor
-  mutable std::vector<EventSet> ring;
-  mutable uint64_t calls = 0;  // profiled calls so far
-};
 
 namespace {
 
 thread_local std::string g_err;
+
+}  // namespace
+
+namespace hbcsf {
 
 int fail(int code, const std::string& msg) {
   g_err = msg;
@@ -58,6 +33,10 @@ int fail_hip(hipError_t e, const char* what) {
   g_err = std::string(what) + ": " + hipGetErrorString(e);
   return HBCSF_EHIP;
 }
+
+}  // namespace hbcsf
+
+namespace {
 
 bool pow2_in(uint32_t v, uint32_t lo, uint32_t hi) { return v >= lo && v <= hi && (v & (v - 1)) == 0; }
 
@@ -92,6 +71,9 @@ int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint
   t->opts = o;
   t->sliceThreshold = o.slice_threshold;
   for (int m = 0; m < order; ++m) t->dims[m] = dims[m];
+  double sq = 0.0;
+  for (uint64_t z = 0; z < nnz; ++z) sq += (double)vals[z] * (double)vals[z];
+  t->normSq = sq;
   uint64_t off = 0;
   for (int m = 0; m < order; ++m) {
     t->modes[m].reset(new (std::nothrow) ModeFormat);

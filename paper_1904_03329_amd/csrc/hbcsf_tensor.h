@@ -1,0 +1,50 @@
+// The tensor handle behind the C ABI, shared by the translation units that implement its entry points.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "hbcsf.h"
+#include "hbcsf_internal.h"
+
+struct hbcsf_tensor {
+  int order = 0;
+  uint64_t dims[HBCSF_MAX_ORDER] = {0, 0, 0, 0};
+  uint64_t nnz = 0;
+  double normSq = 0.0;  // sum of the squared values (for the CPD fit)
+  hbcsf_opts opts{};
+  std::unique_ptr<hbcsf::ModeFormat> modes[HBCSF_MAX_ORDER];
+  uint64_t arenaBytes = 0;
+  uint8_t* arena = nullptr;  // caller's device memory
+  bool uploaded = false;
+  int numCU = 256;
+  uint64_t sliceThreshold = 0;
+  uint64_t wavesPerCU = 0;   // launch sizing override, 0 = default
+  int steps = 8;             // records in flight per lane group
+  uint32_t kernelMask = 15;  // bit0 define, bit1 COO, bit2 CSL, bit3 CSF
+  bool persistent = false;   // resident wavefronts walk the spans round-robin
+  int fuseCoo = 2;           // COO-group rows written by the output-definition pass: 0 never, 1 always, 2 small outputs
+  uint64_t streamBytes = 1ull << 30;  // fiber-level factors at least this large are gathered with streaming loads
+  unsigned long long* trace = nullptr;  // caller's device buffer for wavefront traces
+  uint64_t traceCapacity = 0;
+  // profiling: a ring of event sets, one per hbcsf_mttkrp call
+  struct EventSet {
+    hipEvent_t ev[5];
+    bool launched[4] = {false, false, false, false};
+    bool valid = false;
+  };
+  // hbcsf_mttkrp takes a const handle; recording a profiled call is bookkeeping, not state of the tensor
+  mutable std::vector<EventSet> ring;
+  mutable uint64_t calls = 0;  // profiled calls so far
+};
+
+namespace hbcsf {
+
+// Records the message hbcsf_last_error returns on this thread and passes the code through.
+int fail(int code, const std::string& msg);
+int fail_hip(hipError_t e, const char* what);
+
+}  // namespace hbcsf

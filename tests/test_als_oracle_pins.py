@@ -96,3 +96,16 @@ def test_its_mttkrp_agrees_with_the_c_oracle(oracle):
     for mode in range(4):
         np.testing.assert_allclose(cpd_als.mttkrp(dims, inds, vals, facs, mode),
                                    oracle.mttkrp(dims, inds, vals, facs, mode), rtol=1e-12, atol=1e-13)
+
+
+def test_fit_equals_the_dense_residual():
+    rng = np.random.default_rng(5)
+    dims = (6, 5, 4)
+    x = rng.normal(size=dims) * (rng.uniform(size=dims) < 0.4)
+    nz = np.nonzero(x)
+    inds = [i.astype(np.uint32) for i in nz]
+    vals = x[nz]
+    facs = [rng.uniform(0, 1, size=(d, 3)) for d in dims]
+    lam = rng.uniform(0.5, 2, size=3)
+    want = 1.0 - np.linalg.norm(_dense_model(facs, lam) - x) / np.linalg.norm(x)
+    np.testing.assert_allclose(cpd_als.fit(dims, inds, vals, facs, lam), want, rtol=1e-10)

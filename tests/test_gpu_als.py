@@ -1,0 +1,161 @@
+"""GPU parity of the CPD-ALS iteration (Section II-B, Algorithm "CPD-ALS") against the numpy fp64 oracle.
+
+Bar: the device computes the MTTKRP and the two dense passes in fp32, the oracle everything in fp64.  A
+relative error e in M or in a Gram matrix reaches the updated factor amplified by at most the condition
+number of the Hadamard product V of Gram matrices, so the bound used is
+    max |A_gpu - A_oracle| <= 1e-5 * max(cond(V), 10) * max |A_oracle|
+per factor (columns have unit norm), the same for lambda relative to its largest entry, and 1e-5 absolute
+for the fit.  The starting factors are uniform in (-1, 1), which keeps cond(V) near 1 in the first iteration.
+"""
+import numpy as np
+import pytest
+
+from oracle import cpd_als
+
+pytestmark = pytest.mark.gpu
+
+
+def _random_tensor(rng, dims, nnz):
+    total = int(np.prod([float(d) for d in dims]))
+    flat = rng.choice(total, size=min(nnz, total), replace=False)
+    inds = []
+    for d in reversed(dims):
+        inds.append((flat % d).astype(np.uint32))
+        flat = flat // d
+    inds = inds[::-1]
+    vals = rng.uniform(0.1, 1.0, size=len(inds[0])).astype(np.float32)
+    return inds, vals
+
+
+def _worst_cond(dims, inds, vals, facs):
+    """Largest condition number of the Hadamard products the oracle inverts during the iteration."""
+    a = [np.array(f, dtype=np.float64) for f in facs]
+    worst = 1.0
+    for n in range(len(dims)):
+        v = np.ones((a[0].shape[1],) * 2)
+        for m in range(len(dims)):
+            if m != n:
+                v = v * (a[m].T @ a[m])
+        worst = max(worst, np.linalg.cond(v))
+        a[n] = cpd_als.mttkrp(dims, inds, vals, a, n) @ np.linalg.pinv(v)
+    return worst
+
+
+def _run_gpu(dims, inds, vals, facs, rank, iterations=1, keep=False):
+    import torch
+    from paper_1904_03329_amd import CpdAls, HbcsfTensor
+
+    t = HbcsfTensor(dims, inds, vals).to_device()
+    als = CpdAls(t, rank)
+    dfacs = [torch.from_numpy(np.ascontiguousarray(f)).cuda() for f in facs]
+    fits = []
+    for it in range(iterations):
+        fits.append(als.iteration(dfacs, keep_grams=keep and it > 0))
+    torch.cuda.synchronize()
+    out = [f.cpu().numpy() for f in dfacs]
+    lam = als.lam.cpu().numpy()
+    phases = als.phase_ms()
+    als.close()
+    t.close()
+    return out, lam, fits, phases
+
+
+def _check(dims, inds, vals, facs, rank, iterations=1, keep=False):
+    got, lam, fits, _ = _run_gpu(dims, inds, vals, facs, rank, iterations, keep)
+    want = [np.array(f, dtype=np.float64) for f in facs]
+    cond = 1.0
+    for _ in range(iterations):
+        cond = max(cond, _worst_cond(dims, inds, vals, want))
+        want, want_lam = cpd_als.als_iteration(dims, inds, vals, want)
+    tol = 1e-5 * max(cond, 10.0)
+    for m, (g, w) in enumerate(zip(got, want)):
+        assert np.all(np.isfinite(g))
+        err = np.max(np.abs(g - w)) / np.max(np.abs(w))
+        assert err <= tol, f"factor {m}: {err:.2e} > {tol:.2e} (cond {cond:.1f})"
+    assert np.max(np.abs(lam - want_lam)) <= tol * np.max(np.abs(want_lam))
+    assert abs(fits[-1] - cpd_als.fit(dims, inds, vals, want, want_lam)) <= max(tol, 1e-5)
+    return fits
+
+
+@pytest.mark.parametrize("rank", [32, 8, 16, 64, 128])
+def test_one_iteration_third_order(rank):
+    rng = np.random.default_rng(100 + rank)
+    dims = (1000, 333, 77)          # several 32-row blocks, ragged tails, one dimension below a block pair
+    inds, vals = _random_tensor(rng, dims, 40000)
+    facs = [rng.uniform(-1, 1, size=(d, rank)).astype(np.float32) for d in dims]
+    _check(dims, inds, vals, facs, rank)
+
+
+@pytest.mark.parametrize("rank", [32, 16])
+def test_one_iteration_fourth_order(rank):
+    rng = np.random.default_rng(200 + rank)
+    dims = (130, 65, 31, 9)
+    inds, vals = _random_tensor(rng, dims, 30000)
+    facs = [rng.uniform(-1, 1, size=(d, rank)).astype(np.float32) for d in dims]
+    _check(dims, inds, vals, facs, rank)
+
+
+def test_three_iterations_reuse_gram_matrices():
+    rng = np.random.default_rng(300)
+    dims = (400, 300, 200)
+    inds, vals = _random_tensor(rng, dims, 60000)
+    facs = [rng.uniform(-1, 1, size=(d, 32)).astype(np.float32) for d in dims]
+    fits_keep = _check(dims, inds, vals, facs, 32, iterations=3, keep=True)
+    fits_fresh = _check(dims, inds, vals, facs, 32, iterations=3, keep=False)
+    np.testing.assert_allclose(fits_keep, fits_fresh, atol=1e-5)
+    assert fits_keep[2] >= fits_keep[1] - 1e-6 >= fits_keep[0] - 2e-6      # ALS never lowers the fit
+
+
+def test_recovers_an_exact_low_rank_tensor():
+    """All entries of a rank-8 model are stored, so the fit of the true factors is 1 and stays there."""
+    rng = np.random.default_rng(400)
+    dims = (40, 30, 20)
+    rank = 8
+    true = [rng.uniform(0.2, 1, size=(d, rank)) for d in dims]
+    grid = np.meshgrid(*[np.arange(d) for d in dims], indexing="ij")
+    inds = [g.ravel().astype(np.uint32) for g in grid]
+    vals = cpd_als.model_values(inds, true, np.ones(rank)).astype(np.float32)
+    got, lam, fits, _ = _run_gpu(dims, inds, vals, [f.astype(np.float32) for f in true], rank)
+    # the fit is 1 - sqrt(||X||^2 - 2<X, model> + ||model||^2) / ||X||: the three terms cancel, so fp32 rounding
+    # of the MTTKRP (relative 1e-6) limits its resolution near 1 to about sqrt(1e-6)
+    assert fits[0] > 1 - 3e-3
+    model = cpd_als.model_values(inds, got, lam)
+    assert np.max(np.abs(model - vals)) <= 1e-3 * np.max(np.abs(vals))
+
+
+def test_config1_shape(synth):
+    t, _, rank = synth.workload("cfg1")
+    rng = np.random.default_rng(500)
+    facs = [rng.uniform(-1, 1, size=(d, rank)).astype(np.float32) for d in t.dims]
+    _check(t.dims, t.inds, t.vals, facs, rank)
+
+
+def test_argument_errors():
+    import torch
+    from paper_1904_03329_amd import HbcsfTensor, binding as B
+
+    rng = np.random.default_rng(600)
+    dims = (50, 40, 30)
+    inds, vals = _random_tensor(rng, dims, 500)
+    t = HbcsfTensor(dims, inds, vals)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.HbcsfError) as e:
+        B.als_create(t.handle, 32, ws.data_ptr(), ws.numel())
+    assert e.value.code == -4                                  # not uploaded
+    t.to_device()
+    with pytest.raises(B.HbcsfError) as e:
+        B.als_create(t.handle, 24, ws.data_ptr(), ws.numel())
+    assert e.value.code == -1
+    with pytest.raises(B.HbcsfError) as e:
+        B.als_create(t.handle, 32, ws.data_ptr(), 1024)
+    assert e.value.code == -3
+    a = B.als_create(t.handle, 32, ws.data_ptr(), ws.numel())
+    f = [torch.zeros((d, 32), device="cuda") for d in dims]
+    with pytest.raises(B.HbcsfError) as e:
+        B.als_iteration(a, [f[0].data_ptr(), 0, f[2].data_ptr()])
+    assert e.value.code == -1
+    with pytest.raises(B.HbcsfError) as e:
+        B.als_iteration(a, [x.data_ptr() for x in f], flags=8)
+    assert e.value.code == -1
+    B.als_free(a)
+    t.close()
