@@ -140,6 +140,42 @@ def trace_cu_spread(torch, np, B, ht, dfacs, outs, order, log):
     return result
 
 
+def time_als(torch, ht, dfacs, rank, iterations, build_s, log):
+    """CPD-ALS iterations (Algorithm "CPD-ALS") from copies of the benchmark's factor matrices: wall time per
+    iteration with the factors' Gram matrices carried over (the steady state of a decomposition), and the
+    library's own split into MTTKRP / Gram / host / product time."""
+    from paper_1904_03329_amd import CpdAls
+
+    facs = [f.clone() for f in dfacs]
+    als = CpdAls(ht, rank)
+    fits, wall, phases = [], [], []
+    for it in range(iterations + 1):          # the first iteration also computes the initial Gram matrices
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fits.append(als.iteration(facs, keep_grams=it > 0))
+        wall.append(1e3 * (time.perf_counter() - t0))
+        phases.append(als.phase_ms())
+    als.close()
+    steady = wall[1:]
+    ph = [sum(p[k] for p in phases[1:]) / len(steady) for k in range(4)]
+    ms = sum(steady) / len(steady)
+    rows = sum(ht.dims)
+    dense_bytes = 3.0 * rows * rank * 4       # per iteration: Gram reads M, the product reads M and writes the factor
+    report = {
+        "iterations": iterations,
+        "ms_per_iteration": round(ms, 3),
+        "first_iteration_ms": round(wall[0], 3),
+        "phase_ms": {"mttkrp": round(ph[0], 3), "gram": round(ph[1], 3), "host": round(ph[2], 3),
+                     "product": round(ph[3], 3)},
+        "mttkrp_share": round(ph[0] / max(sum(ph), 1e-9), 3),
+        "dense_pass_gbs": round(dense_bytes / max((ph[1] + ph[3]) * 1e-3, 1e-12) / 1e9, 1),
+        "fit": [round(f, 6) for f in fits],
+        "iterations_to_equal_build_time": round(build_s * 1e3 / ms, 1),
+    }
+    log(f"[bench] als: {json.dumps(report)}")
+    return report
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,6 +189,9 @@ def main() -> int:
     ap.add_argument("--group-mask", type=int, default=0)
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--kernel-steps", type=int, default=0)
+    ap.add_argument("--als-iterations", type=int, default=3,
+                    help="after the timed MTTKRP steps, time this many CPD-ALS iterations built on the same "
+                         "library (reported under \"als\", not part of `value`); 0 skips them")
     ap.add_argument("--cu-spread", action="store_true",
                     help="after the timed steps, trace every wavefront of one more pass and report the "
                          "per-CU busy-time spread of the CSL and B-CSF kernels (profiling only)")
@@ -268,6 +307,10 @@ def main() -> int:
     if args.cu_spread:
         cu_spread = trace_cu_spread(torch, np, B, ht, dfacs, outs, order, log)
 
+    als_report = None
+    if args.als_iterations > 0:
+        als_report = time_als(torch, ht, dfacs, rank, args.als_iterations, build_s, log)
+
     achieved = csf_bytes / (csf_ms * 1e-3) / 1e9 if csf_ms > 0 else 0.0
     roofline = {
         "kernel": f"csf_group_kernel<{rank // 4},{order}>",
@@ -328,6 +371,7 @@ def main() -> int:
         "per_mode": per_mode,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "als": als_report,
     }
     if cu_spread is not None:
         line["cu_busy_spread"] = cu_spread
