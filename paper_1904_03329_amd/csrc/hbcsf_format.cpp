@@ -22,12 +22,6 @@
 namespace hbcsf {
 namespace {
 
-inline int bits_for(uint64_t dim) {
-  int b = 1;
-  while (b < 63 && (1ull << b) < dim) ++b;
-  return b;
-}
-
 // Stable parallel LSD radix sort of (key, payload) pairs on the low `totalBits` bits.
 // On return k / v point at the sorted data (either the first or the second buffer pair).
 template <typename Key>
@@ -73,19 +67,6 @@ void radix_sort_pairs(Key*& k, uint32_t*& v, Key*& k2, uint32_t*& v2, size_t n, 
   }
 }
 
-struct Layout {
-  uint64_t bytes = 0;
-  ArrayRef add(uint64_t count) {
-    ArrayRef r;
-    r.off = bytes;
-    r.count = count;
-    r.present = true;
-    bytes += ((count * 4 + kAlign - 1) / kAlign) * kAlign;
-    if (count == 0) bytes += kAlign;
-    return r;
-  }
-};
-
 template <typename Key>
 int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* const* inds,
                  const float* vals, const hbcsf_opts& opts, int mode, ModeFormat* out,
@@ -98,17 +79,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
 
   // Tree levels: root = the target mode; the other modes ordered by the policy.
   int lv[HBCSF_MAX_ORDER];
-  lv[0] = mode;
-  {
-    std::vector<int> rest;
-    for (int m = 0; m < N; ++m)
-      if (m != mode) rest.push_back(m);
-    if (opts.mode_order_policy == 0)
-      std::stable_sort(rest.begin(), rest.end(), [&](int a, int b) { return dims[a] < dims[b]; });
-    else if (opts.mode_order_policy == 1)
-      std::stable_sort(rest.begin(), rest.end(), [&](int a, int b) { return dims[a] > dims[b]; });
-    for (int l = 1; l < N; ++l) lv[l] = rest[l - 1];
-  }
+  level_order(N, dims, mode, opts.mode_order_policy, lv);
   int bits[HBCSF_MAX_ORDER], shift[HBCSF_MAX_ORDER];
   uint64_t mask[HBCSF_MAX_ORDER];
   int total = 0;
@@ -257,45 +228,10 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   }
 
   // ---- lay the arrays out in one blob ----
-  Layout lay;
-  for (int g = 0; g < 3; ++g) {
-    GroupFormat& G = out->g[g];
-    G.nnz = gM[g];
-    G.runs = (gM[g] + L - 1) / L;
-  }
-  {
-    GroupFormat& G = out->g[kCoo];
-    for (int l = 0; l < N; ++l) G.ind[l] = lay.add(G.nnz);
-    G.val = lay.add(G.nnz);
-  }
-  {
-    GroupFormat& G = out->g[kCsl];
-    G.n[0] = gS[kCsl];
-    G.ind[0] = lay.add(G.n[0] + 1);
-    G.ptr[0] = lay.add(G.n[0] + 1);
-    G.runFirst[0] = lay.add(G.runs + 1);
-    for (int l = 1; l < N; ++l) G.ind[l] = lay.add(G.nnz);
-    G.val = lay.add(G.nnz);
-  }
-  {
-    GroupFormat& G = out->g[kCsf];
-    G.n[0] = gS[kCsf];
-    for (int f = 0; f < NF; ++f) G.n[1 + f] = nSeg[f];
-    for (int l = 0; l < N - 1; ++l) {
-      G.ind[l] = lay.add(G.n[l] + 1);
-      G.ptr[l] = lay.add(G.n[l] + 1);
-      G.runFirst[l] = lay.add(G.runs + 1);
-    }
-    G.ind[N - 1] = lay.add(G.nnz);
-    G.val = lay.add(G.nnz);
-  }
+  layout_mode(out, N, gS, gM, nSeg);
   const uint64_t ownedWords = (out->rows + 31) / 32;
-  out->ownedBits = lay.add(ownedWords);
-  out->cooBits = lay.add(ownedWords);
-  out->cooPtr = lay.add(ownedWords + 1);
-  out->blobBytes = lay.bytes;
   void* mem = nullptr;
-  if (posix_memalign(&mem, kAlign, (size_t)lay.bytes) != 0 || !mem) {
+  if (posix_memalign(&mem, kAlign, (size_t)out->blobBytes) != 0 || !mem) {
     *err = "out of host memory for the format arrays";
     return HBCSF_ENOMEM;
   }
@@ -395,37 +331,8 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   }
 
   // ---- statistics ----
+  fill_count_stats(out, N, M, S, fibNat, fibNatCsf, nSeg, gS, gM, sharedSlices);
   hbcsf_stats& st = out->stats;
-  std::memset(&st, 0, sizeof(st));
-  st.nnz = M;
-  st.slices = S;
-  for (int f = 0; f < NF; ++f) {
-    st.fibers[f] = fibNat[f];
-    st.segments[f] = nSeg[f];
-  }
-  for (int g = 0; g < 3; ++g) {
-    st.group_nnz[g] = gM[g];
-    st.group_slices[g] = gS[g];
-    st.runs[g] = out->g[g].runs;
-  }
-  st.shared_slices = sharedSlices;
-  st.words_coo = (uint64_t)N * M;
-  st.words_csf = 2 * S + M;
-  st.words_hbcsf = (uint64_t)N * gM[kCoo] + 2 * gS[kCsl] + (uint64_t)(N - 1) * gM[kCsl] + 2 * gS[kCsf] + gM[kCsf];
-  for (int f = 0; f < NF; ++f) {
-    st.words_csf += 2 * fibNat[f];
-    st.words_hbcsf += 2 * fibNatCsf[f];
-  }
-  for (int g = 0; g < 3; ++g) {
-    const GroupFormat& G = out->g[g];
-    uint64_t words = G.val.count;
-    for (int l = 0; l < N; ++l) {
-      if (G.ind[l].present) words += G.ind[l].count;
-      if (G.ptr[l].present) words += G.ptr[l].count;
-      if (G.runFirst[l].present) words += G.runFirst[l].count;
-    }
-    st.stream_bytes[g] = G.nnz ? words * 4 : 0;
-  }
   {
     uint64_t cnt = 0;
 #pragma omp parallel for schedule(static) reduction(+ : cnt)
@@ -457,17 +364,8 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
         }
         st.distinct_rows[g][l] = d;
       }
-      st.distinct_rows[g][0] = gS[g];
     }
   }
-  {
-    uint64_t fl = (uint64_t)(N - 1) * gM[kCoo] + (uint64_t)N * gM[kCsl];
-    uint64_t csf = gM[kCsf];
-    for (int f = 0; f < NF; ++f) csf += nSeg[f];
-    st.flops_real = fl + 2 * csf;
-  }
-  for (int l = 0; l < N; ++l) st.level_mode[l] = (uint32_t)lv[l];
-  st.fiber_threshold = L;
   st.build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_begin).count();
   return HBCSF_OK;
 }

@@ -59,6 +59,126 @@ struct ModeFormat {
   ~ModeFormat() { std::free(blob); }
 };
 
+// Places every array of one mode in its blob, given the group sizes; both format builders (host and
+// device) call this, so the two produce the same byte layout.  gS / gM: slices and nonzeros per group;
+// nSeg: fiber segments of the CSF group per fiber level.  Sets out->blobBytes.
+inline void layout_mode(ModeFormat* out, int N, const uint64_t gS[3], const uint64_t gM[3],
+                        const uint64_t nSeg[2]) {
+  uint64_t bytes = 0;
+  auto add = [&bytes](uint64_t count) {
+    ArrayRef r;
+    r.off = bytes;
+    r.count = count;
+    r.present = true;
+    bytes += ((count * 4 + kAlign - 1) / kAlign) * kAlign;
+    if (count == 0) bytes += kAlign;
+    return r;
+  };
+  const uint32_t L = out->L;
+  for (int g = 0; g < 3; ++g) {
+    out->g[g].nnz = gM[g];
+    out->g[g].runs = (gM[g] + L - 1) / L;
+  }
+  {
+    GroupFormat& G = out->g[kCoo];
+    for (int l = 0; l < N; ++l) G.ind[l] = add(G.nnz);
+    G.val = add(G.nnz);
+  }
+  {
+    GroupFormat& G = out->g[kCsl];
+    G.n[0] = gS[kCsl];
+    G.ind[0] = add(G.n[0] + 1);
+    G.ptr[0] = add(G.n[0] + 1);
+    G.runFirst[0] = add(G.runs + 1);
+    for (int l = 1; l < N; ++l) G.ind[l] = add(G.nnz);
+    G.val = add(G.nnz);
+  }
+  {
+    GroupFormat& G = out->g[kCsf];
+    G.n[0] = gS[kCsf];
+    for (int f = 0; f < N - 2; ++f) G.n[1 + f] = nSeg[f];
+    for (int l = 0; l < N - 1; ++l) {
+      G.ind[l] = add(G.n[l] + 1);
+      G.ptr[l] = add(G.n[l] + 1);
+      G.runFirst[l] = add(G.runs + 1);
+    }
+    G.ind[N - 1] = add(G.nnz);
+    G.val = add(G.nnz);
+  }
+  const uint64_t ownedWords = (out->rows + 31) / 32;
+  out->ownedBits = add(ownedWords);
+  out->cooBits = add(ownedWords);
+  out->cooPtr = add(ownedWords + 1);
+  out->blobBytes = bytes;
+}
+
+// The statistics that follow from counts alone (call after layout_mode).
+inline void fill_count_stats(ModeFormat* out, int N, uint64_t M, uint64_t S, const uint64_t fibNat[2],
+                             const uint64_t fibNatCsf[2], const uint64_t nSeg[2], const uint64_t gS[3],
+                             const uint64_t gM[3], uint64_t sharedSlices) {
+  hbcsf_stats& st = out->stats;
+  st = hbcsf_stats{};
+  st.nnz = M;
+  st.slices = S;
+  for (int f = 0; f < N - 2; ++f) {
+    st.fibers[f] = fibNat[f];
+    st.segments[f] = nSeg[f];
+  }
+  for (int g = 0; g < 3; ++g) {
+    st.group_nnz[g] = gM[g];
+    st.group_slices[g] = gS[g];
+    st.runs[g] = out->g[g].runs;
+  }
+  st.shared_slices = sharedSlices;
+  st.words_coo = (uint64_t)N * M;
+  st.words_csf = 2 * S + M;
+  st.words_hbcsf = (uint64_t)N * gM[kCoo] + 2 * gS[kCsl] + (uint64_t)(N - 1) * gM[kCsl] + 2 * gS[kCsf] + gM[kCsf];
+  for (int f = 0; f < N - 2; ++f) {
+    st.words_csf += 2 * fibNat[f];
+    st.words_hbcsf += 2 * fibNatCsf[f];
+  }
+  for (int g = 0; g < 3; ++g) {
+    const GroupFormat& G = out->g[g];
+    uint64_t words = G.val.count;
+    for (int l = 0; l < N; ++l) {
+      if (G.ind[l].present) words += G.ind[l].count;
+      if (G.ptr[l].present) words += G.ptr[l].count;
+      if (G.runFirst[l].present) words += G.runFirst[l].count;
+    }
+    st.stream_bytes[g] = G.nnz ? words * 4 : 0;
+    st.distinct_rows[g][0] = gS[g];
+  }
+  uint64_t csf = gM[kCsf];
+  for (int f = 0; f < N - 2; ++f) csf += nSeg[f];
+  st.flops_real = (uint64_t)(N - 1) * gM[kCoo] + (uint64_t)N * gM[kCsl] + 2 * csf;
+  for (int l = 0; l < N; ++l) st.level_mode[l] = (uint32_t)out->levelMode[l];
+  st.fiber_threshold = out->L;
+}
+
+// Tree levels of a mode's representation: the root is the mode itself, the others follow the policy
+// (0: shortest mode first, 1: longest first, 2: natural order).
+inline void level_order(int N, const uint64_t* dims, int mode, uint32_t policy, int lv[HBCSF_MAX_ORDER]) {
+  lv[0] = mode;
+  int rest[HBCSF_MAX_ORDER], n = 0;
+  for (int m = 0; m < N; ++m)
+    if (m != mode) rest[n++] = m;
+  if (policy == 0 || policy == 1) {  // stable insertion sort
+    for (int i = 1; i < n; ++i)
+      for (int j = i; j > 0; --j) {
+        const bool swap = policy == 0 ? dims[rest[j]] < dims[rest[j - 1]] : dims[rest[j]] > dims[rest[j - 1]];
+        if (!swap) break;
+        const int t = rest[j]; rest[j] = rest[j - 1]; rest[j - 1] = t;
+      }
+  }
+  for (int l = 1; l < N; ++l) lv[l] = rest[l - 1];
+}
+
+inline int bits_for(uint64_t dim) {
+  int b = 1;
+  while (b < 63 && (1ull << b) < dim) ++b;
+  return b;
+}
+
 // Builds one mode's representation.  Returns HBCSF_OK or an error code and fills `err`.
 int build_mode(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* const* inds,
                const float* vals, const hbcsf_opts& opts, int mode, ModeFormat* out,
