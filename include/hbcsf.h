@@ -173,6 +173,41 @@ int hbcsf_tune(hbcsf_tensor *t, int key, uint64_t value);
 int hbcsf_kernel_ms(hbcsf_tensor *t, uint32_t calls_back, float ms[4]);
 
 /* ---------------------------------------------------------------------------------------------
+ * Format construction on the device (the pre-processing of Sections IV-V, whose cost Section VI-E
+ * weighs against the MTTKRP time): the same per-mode HB-CSF arrays as hbcsf_build_format, byte for
+ * byte, built from COO arrays that already are in device memory and written straight into the
+ * caller's device arena.  Tensors whose packed coordinate (sum over the modes of
+ * ceil(log2(dim))) exceeds 64 bits are refused with HBCSF_ERANGE; build those on the host.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Sizes to allocate before hbcsf_build_format_device: arena_bytes is an upper bound over every
+ * possible sparsity pattern of nnz nonzeros (the build reports what it used through
+ * hbcsf_device_bytes), workspace_bytes is scratch that can be released when the build returns.
+ * Needs a HIP device (the sort / scan scratch sizes are queried for it). */
+int hbcsf_device_build_bytes(int order, const uint64_t *dims, uint64_t nnz, const hbcsf_opts *opts,
+                             uint64_t *arena_bytes, uint64_t *workspace_bytes);
+
+/* As hbcsf_build_format, but inds[m] and vals are device pointers (read only), and the result is
+ * resident: the handle can be passed to hbcsf_mttkrp at once; hbcsf_upload must not be called on
+ * it.  device_arena / workspace: device memory, 256-byte aligned; the arena is kept by the caller
+ * for the handle's lifetime.  Blocking: the host waits for a few counts per mode.  Errors as
+ * hbcsf_build_format, plus ENOMEM when the arena or workspace is too small, and EHIP. */
+int hbcsf_build_format_device(int order, const uint64_t *dims, uint64_t nnz,
+                              const uint32_t *const *inds, const float *vals, const hbcsf_opts *opts,
+                              void *device_arena, uint64_t arena_bytes, void *workspace,
+                              uint64_t workspace_bytes, void *hip_stream, hbcsf_tensor **out);
+
+/* Moves a resident handle's arrays into another device arena of at least hbcsf_device_bytes
+ * (256-byte aligned, not overlapping the old one) and makes the handle use it, e.g. to release the
+ * upper-bound arena a device build was given.  Blocking.  The old arena is the caller's again. */
+int hbcsf_relocate(hbcsf_tensor *t, void *new_arena, uint64_t bytes, void *hip_stream);
+
+/* Copies the device-resident arrays of a handle built by hbcsf_build_format_device to host
+ * memory, after which hbcsf_host_array works on it (inspection and tests).  No effect on modes
+ * that already have a host copy. */
+int hbcsf_download(hbcsf_tensor *t, void *hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * CPD-ALS iteration (Section II-B: Eq. 1 the model, Eq. 2-3 the mode update, Algorithm "CPD-ALS")
  * built around hbcsf_mttkrp.  One iteration updates every factor in turn,
  *     A_n <- MTTKRP_n(X; other factors) * pinv( Hadamard_{m != n} A_m^T A_m ),

@@ -20,6 +20,39 @@ class HbcsfTensor:
         self.handle = binding.build_format(self.dims, inds, vals, **opts)
         self._arena = None
 
+    @classmethod
+    def from_device_coo(cls, dims, inds, vals, compact: bool = True, **opts):
+        """Builds the format on the GPU from CUDA tensors (int32 / uint32-valued index tensors of dtype
+        torch.int32, float32 values); the result is resident.  With `compact` the arrays are moved from the
+        upper-bound arena the build needs into one of exactly their size."""
+        import torch
+
+        self = cls.__new__(cls)
+        self.dims = tuple(int(d) for d in dims)
+        self.order = len(self.dims)
+        self.handle = None
+        self._arena = None
+        nnz = int(vals.shape[0])
+        for x in list(inds) + [vals]:
+            if not x.is_cuda or not x.is_contiguous() or x.shape[0] != nnz:
+                raise ValueError("index and value tensors must be contiguous CUDA tensors of one length")
+        if vals.dtype != torch.float32 or any(x.dtype != torch.int32 for x in inds):
+            raise ValueError("indices must be torch.int32 and values torch.float32")
+        stream = torch.cuda.current_stream().cuda_stream
+        arena_bytes, ws_bytes = binding.device_build_bytes(self.dims, nnz, **opts)
+        arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        self.handle = binding.build_format_device(self.dims, nnz, [x.data_ptr() for x in inds], vals.data_ptr(),
+                                                  arena.data_ptr(), arena_bytes, ws.data_ptr(), ws_bytes, stream, **opts)
+        del ws
+        if compact:
+            used = max(binding.device_bytes(self.handle), 256)
+            small = torch.empty(used, dtype=torch.uint8, device="cuda")
+            binding.relocate(self.handle, small.data_ptr(), used, stream)
+            arena = small
+        self._arena = arena
+        return self
+
     def stats(self, mode: int) -> dict:
         return binding.get_stats(self.handle, mode)
 

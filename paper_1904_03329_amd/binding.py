@@ -27,6 +27,7 @@ EXPORTS = (
     "hbcsf_host_array", "hbcsf_tune", "hbcsf_kernel_ms", "hbcsf_probe_row_gather", "hbcsf_free",
     "hbcsf_strerror", "hbcsf_last_error",
     "hbcsf_als_workspace_bytes", "hbcsf_als_create", "hbcsf_als_iteration", "hbcsf_als_phase_ms", "hbcsf_als_free", "hbcsf_sym_pinv",
+    "hbcsf_device_build_bytes", "hbcsf_build_format_device", "hbcsf_download", "hbcsf_relocate",
 )
 
 
@@ -97,6 +98,14 @@ def lib():
         L.hbcsf_als_iteration.argtypes = [vp, vp, vp, i32, ctypes.POINTER(ctypes.c_double), vp]
         L.hbcsf_als_phase_ms.restype = i32
         L.hbcsf_als_phase_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4)]
+        L.hbcsf_device_build_bytes.restype = i32
+        L.hbcsf_device_build_bytes.argtypes = [i32, vp, u64, vp, ctypes.POINTER(u64), ctypes.POINTER(u64)]
+        L.hbcsf_build_format_device.restype = i32
+        L.hbcsf_build_format_device.argtypes = [i32, vp, u64, vp, vp, vp, vp, u64, vp, u64, vp, ctypes.POINTER(vp)]
+        L.hbcsf_relocate.restype = i32
+        L.hbcsf_relocate.argtypes = [vp, vp, u64, vp]
+        L.hbcsf_download.restype = i32
+        L.hbcsf_download.argtypes = [vp, vp]
         L.hbcsf_sym_pinv.restype = i32
         L.hbcsf_sym_pinv.argtypes = [vp, i32, vp]
         L.hbcsf_als_free.restype = None
@@ -127,6 +136,45 @@ def build_format(dims, inds, vals, fiber_threshold=0, slice_threshold=0, mode_or
                                     vals.ctypes.data, ctypes.cast(ctypes.pointer(opts), ctypes.c_void_p),
                                     ctypes.byref(h)))
     return h
+
+
+def _opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask):
+    return hbcsf_opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask)
+
+
+def device_build_bytes(dims, nnz: int, fiber_threshold=0, slice_threshold=0, mode_order_policy=0, group_mask=0):
+    """hbcsf_device_build_bytes: (arena upper bound, workspace) in bytes."""
+    d = np.asarray(dims, dtype=np.uint64)
+    opts = _opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask)
+    a, w = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(lib().hbcsf_device_build_bytes(len(dims), d.ctypes.data, nnz,
+                                          ctypes.cast(ctypes.pointer(opts), ctypes.c_void_p), ctypes.byref(a),
+                                          ctypes.byref(w)))
+    return int(a.value), int(w.value)
+
+
+def build_format_device(dims, nnz: int, ind_ptrs, val_ptr: int, arena_ptr: int, arena_bytes: int, workspace_ptr: int,
+                        workspace_bytes: int, stream: int = 0, fiber_threshold=0, slice_threshold=0,
+                        mode_order_policy=0, group_mask=0):
+    """hbcsf_build_format_device: device addresses of the COO arrays in, resident handle out."""
+    d = np.asarray(dims, dtype=np.uint64)
+    opts = _opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask)
+    ptrs = (ctypes.c_void_p * len(dims))(*[(p if p else None) for p in ind_ptrs])
+    h = ctypes.c_void_p()
+    _check(lib().hbcsf_build_format_device(len(dims), d.ctypes.data, nnz, ctypes.cast(ptrs, ctypes.c_void_p),
+                                           ctypes.c_void_p(val_ptr or None),
+                                           ctypes.cast(ctypes.pointer(opts), ctypes.c_void_p),
+                                           ctypes.c_void_p(arena_ptr), arena_bytes, ctypes.c_void_p(workspace_ptr),
+                                           workspace_bytes, ctypes.c_void_p(stream), ctypes.byref(h)))
+    return h
+
+
+def relocate(h, arena_ptr: int, nbytes: int, stream: int = 0):
+    _check(lib().hbcsf_relocate(h, ctypes.c_void_p(arena_ptr), nbytes, ctypes.c_void_p(stream)))
+
+
+def download(h, stream: int = 0):
+    _check(lib().hbcsf_download(h, ctypes.c_void_p(stream)))
 
 
 def device_bytes(h) -> int:

@@ -38,7 +38,7 @@ def build(verbose: bool = False) -> str:
             defs = [f"-DHBCSF_G={g}", f"-DHBCSF_N={n}"] + (["-DHBCSF_WITH_DEFINE"] if (g, n) == (8, 3) else [])
             jobs.append(["hipcc"] + HIP_FLAGS + inc + defs + ["-c", os.path.join(CSRC, "hbcsf_kernels.hip"), "-o", o])
             objs.append(o)
-    for name in ("hbcsf_capi", "hbcsf_als"):
+    for name in ("hbcsf_capi", "hbcsf_als", "hbcsf_devbuild"):
         o = os.path.join(CSRC, name + ".o")
         jobs.append(["hipcc"] + HIP_FLAGS + inc + ["-c", os.path.join(CSRC, name + ".hip"), "-o", o])
         objs.append(o)

@@ -97,6 +97,8 @@ int hbcsf_device_bytes(const hbcsf_tensor* t, uint64_t* bytes) {
 
 int hbcsf_upload(hbcsf_tensor* t, void* device_arena, uint64_t bytes, void* hip_stream) {
   if (!t || !device_arena) return fail(HBCSF_EINVAL, "null argument");
+  for (int m = 0; m < t->order; ++m)
+    if (!t->modes[m]->blob) return fail(HBCSF_ESTATE, "the format was built on the device: it is already resident");
   if (bytes < t->arenaBytes) return fail(HBCSF_ENOMEM, "device arena is smaller than hbcsf_device_bytes");
   if (((uintptr_t)device_arena & (kAlign - 1)) != 0) return fail(HBCSF_EINVAL, "device arena must be 256-byte aligned");
   hipStream_t s = (hipStream_t)hip_stream;
@@ -290,6 +292,7 @@ int hbcsf_host_array(const hbcsf_tensor* t, int mode, int group, int level, int 
     else if (array_id == HBCSF_ARR_RUNFIRST) r = &g.runFirst[level];
   }
   if (!r || !r->present) return fail(HBCSF_EINVAL, "this group has no such array");
+  if (!f.blob) return fail(HBCSF_ESTATE, "the format was built on the device: call hbcsf_download first");
   *ptr = f.blob + r->off;
   *count = r->count;
   return HBCSF_OK;

@@ -1,0 +1,193 @@
+"""The device-side format builder against the host builder (array for array, bit for bit), against the
+CPU walks of tests/format_walk.py, and end to end against the MTTKRP oracle."""
+import numpy as np
+import pytest
+
+import format_walk as FW
+import gpu_util as GU
+from paper_1904_03329_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+
+
+def _device_tensor(dims, inds, vals, **opts):
+    import torch
+    from paper_1904_03329_amd import HbcsfTensor
+
+    di = [torch.from_numpy(np.ascontiguousarray(x, dtype=np.uint32).view(np.int32)).cuda() for x in inds]
+    dv = torch.from_numpy(np.ascontiguousarray(vals, dtype=np.float32)).cuda()
+    return HbcsfTensor.from_device_coo(dims, di, dv, **opts)
+
+
+def _arrays(h, order):
+    out = {}
+    for mode in range(order):
+        for aid in (B.ARR_OWNED_BITS, B.ARR_COO_BITS, B.ARR_COO_PTR):
+            out[(mode, aid)] = B.host_array(h, mode, 0, 0, aid)
+        for g in range(3):
+            for lvl in range(order):
+                for aid in (B.ARR_IND, B.ARR_PTR, B.ARR_RUNFIRST):
+                    try:
+                        out[(mode, g, lvl, aid)] = B.host_array(h, mode, g, lvl, aid)
+                    except B.HbcsfError:
+                        pass
+            out[(mode, g, "val")] = B.host_array(h, mode, g, 0, B.ARR_VAL).view(np.uint32)
+    return out
+
+
+def assert_same_format(dims, inds, vals, **opts):
+    """Builds on the host and on the device; every array and every statistic must agree."""
+    from paper_1904_03329_amd import HbcsfTensor
+
+    order = len(dims)
+    host = HbcsfTensor(dims, inds, vals, **opts)
+    dev = _device_tensor(dims, inds, vals, **opts)
+    assert B.device_bytes(dev.handle) == B.device_bytes(host.handle)
+    with pytest.raises(B.HbcsfError):
+        B.host_array(dev.handle, 0, 0, 0, B.ARR_VAL)          # no host copy yet
+    B.download(dev.handle)
+    for mode in range(order):
+        sh, sd = host.stats(mode), dev.stats(mode)
+        sh.pop("build_seconds"), sd.pop("build_seconds")
+        assert sh == sd, f"mode {mode}: statistics differ"
+    ah, ad = _arrays(host.handle, order), _arrays(dev.handle, order)
+    assert ah.keys() == ad.keys()
+    for k in ah:
+        assert np.array_equal(ah[k], ad[k]), f"array {k} differs"
+    host.close()
+    return dev
+
+
+def _random(rng, dims, nnz, distinct=True):
+    inds = [rng.integers(0, d, nnz).astype(np.uint32) for d in dims]
+    if distinct:
+        key = np.zeros(nnz, dtype=np.int64)
+        for i, d in zip(inds, dims):
+            key = key * d + i
+        _, keep = np.unique(key, return_index=True)
+        keep.sort()
+        inds = [i[keep] for i in inds]
+    vals = rng.uniform(-1, 1, len(inds[0])).astype(np.float32)
+    return inds, vals
+
+
+def _skewed(rng, dims, nnz, a=1.3):
+    inds = []
+    for d in dims:
+        p = 1.0 / np.arange(1, d + 1) ** a
+        inds.append(rng.permutation(d)[rng.choice(d, size=nnz, p=p / p.sum())].astype(np.uint32))
+    key = np.zeros(nnz, dtype=np.int64)
+    for i, d in zip(inds, dims):
+        key = key * d + i
+    _, keep = np.unique(key, return_index=True)
+    keep.sort()
+    return [i[keep] for i in inds], rng.uniform(-1, 1, keep.size).astype(np.float32)
+
+
+def test_cfg1_arrays_walks_and_mttkrp(oracle, synth):
+    import torch
+
+    t, facs, rank = synth.workload("cfg1")
+    dev = assert_same_format(t.dims, t.inds, t.vals)
+    for mode in range(t.order):
+        fmt = FW.read_mode(dev.handle, mode, t.order)
+        want = oracle.mttkrp(t.dims, t.inds, t.vals, facs, mode)
+        got = FW.walk_algorithms(fmt, facs, t.dims[mode], rank)
+        np.testing.assert_allclose(got, want, rtol=1e-9, atol=1e-9 * np.abs(want).max())
+    dfacs = [torch.from_numpy(f).cuda() for f in facs]
+    for mode in range(t.order):
+        out = dev.mttkrp(mode, dfacs)
+        torch.cuda.synchronize()
+        GU.assert_close(out.cpu().numpy(), oracle.mttkrp(t.dims, t.inds, t.vals, facs, mode), f"cfg1 mode {mode}")
+    dev.close()
+
+
+@pytest.mark.parametrize("opts", [dict(), dict(fiber_threshold=8), dict(fiber_threshold=16), dict(group_mask=4),
+                                  dict(group_mask=1), dict(group_mask=2), dict(mode_order_policy=1),
+                                  dict(mode_order_policy=2)])
+@pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000)])
+def test_same_arrays_as_the_host_builder(dims, nnz, opts):
+    rng = np.random.default_rng(len(dims) * 1000 + nnz)
+    inds, vals = _skewed(rng, dims, nnz)
+    assert_same_format(dims, inds, vals, **opts).close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_small_tensors(oracle, seed):
+    import torch
+
+    rng = np.random.default_rng(7000 + seed)
+    order = 3 + seed % 2
+    dims = tuple(int(rng.integers(1, 200)) for _ in range(order))
+    nnz = int(rng.integers(1, 3000))
+    inds, vals = _random(rng, dims, nnz)
+    rank = [8, 16, 32][seed % 3]
+    dev = assert_same_format(dims, inds, vals, fiber_threshold=[8, 64][seed % 2])
+    facs = [rng.uniform(0, 1, size=(d, rank)).astype(np.float32) for d in dims]
+    dfacs = [torch.from_numpy(f).cuda() for f in facs]
+    for mode in range(order):
+        out = dev.mttkrp(mode, dfacs)
+        torch.cuda.synchronize()
+        GU.assert_close(out.cpu().numpy(), oracle.mttkrp(dims, inds, vals, facs, mode), f"seed {seed} mode {mode}")
+    dev.close()
+
+
+def test_duplicates_keep_their_input_order():
+    """Equal coordinates are not merged; the sort is stable, so their values stay in input order."""
+    rng = np.random.default_rng(42)
+    dims = (30, 20, 10)
+    inds, vals = _random(rng, dims, 4000, distinct=False)
+    assert_same_format(dims, inds, vals).close()
+
+
+def test_degenerate_shapes():
+    one = (np.array([3], dtype=np.uint32), np.array([0], dtype=np.uint32), np.array([5], dtype=np.uint32))
+    assert_same_format((7, 1, 9), one, np.array([2.5], dtype=np.float32)).close()
+    # one heavy slice spanning many runs, one long fiber
+    n = 1000
+    inds = [np.zeros(n, dtype=np.uint32), np.zeros(n, dtype=np.uint32), np.arange(n, dtype=np.uint32)]
+    assert_same_format((2, 1, n), inds, np.ones(n, dtype=np.float32)).close()
+    # already sorted input, large sparse dimensions
+    inds = [np.arange(n, dtype=np.uint32) * 1000, np.arange(n, dtype=np.uint32) * 7, np.arange(n, dtype=np.uint32)]
+    assert_same_format((1_000_000, 7_000, n), inds, np.ones(n, dtype=np.float32)).close()
+
+
+def test_cfg2_full_size(synth):
+    t, _, _ = synth.workload("cfg2")
+    assert_same_format(t.dims, t.inds, t.vals).close()
+
+
+def test_errors():
+    import torch
+
+    dims = (50, 40, 30)
+    rng = np.random.default_rng(1)
+    inds, vals = _random(rng, dims, 500)
+    bad = [i.copy() for i in inds]
+    bad[1][7] = 40
+    with pytest.raises(B.HbcsfError) as e:
+        _device_tensor(dims, bad, vals)
+    assert e.value.code == -2
+    with pytest.raises(B.HbcsfError) as e:                      # 4 x 17 bits > 64
+        B.device_build_bytes((100_000,) * 4, 10)
+    assert e.value.code == -2
+    with pytest.raises(B.HbcsfError) as e:
+        B.device_build_bytes(dims, 10, fiber_threshold=5)
+    assert e.value.code == -1
+    arena_bytes, ws_bytes = B.device_build_bytes(dims, len(vals))
+    di = [torch.from_numpy(x.view(np.int32)).cuda() for x in inds]
+    dv = torch.from_numpy(vals).cuda()
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    ptrs = [x.data_ptr() for x in di]
+    with pytest.raises(B.HbcsfError) as e:                      # arena too small for the arrays
+        B.build_format_device(dims, len(vals), ptrs, dv.data_ptr(), arena.data_ptr(), 1024, ws.data_ptr(), ws_bytes)
+    assert e.value.code == -3
+    with pytest.raises(B.HbcsfError) as e:
+        B.build_format_device(dims, len(vals), ptrs, dv.data_ptr(), arena.data_ptr(), arena_bytes, ws.data_ptr(), 4096)
+    assert e.value.code == -3
+    h = B.build_format_device(dims, len(vals), ptrs, dv.data_ptr(), arena.data_ptr(), arena_bytes, ws.data_ptr(), ws_bytes)
+    with pytest.raises(B.HbcsfError) as e:                      # already resident
+        B.upload(h, arena.data_ptr(), arena_bytes)
+    assert e.value.code == -4
+    B.free(h)
