@@ -184,7 +184,13 @@ struct OutArrays {
   uint32_t* csfVal;
   uint32_t* owned;
   uint32_t* cooBits;
+  uint32_t* seen[3][HBCSF_MAX_ORDER];  // statistics: bitmap of the factor rows each group gathers, per level
 };
+
+__device__ __forceinline__ void mark_row(uint32_t* bitmap, uint32_t r) {
+  const uint32_t bit = 1u << (r & 31);
+  if (!(bitmap[r >> 5] & bit)) atomicOr(&bitmap[r >> 5], bit);
+}
 
 // every nonzero writes itself into its group's stream; segment starts write the fiber-level entries
 __global__ void fill_nonzeros_kernel(const uint64_t* K, const uint32_t* V, size_t M, Spec sp, Tables t,
@@ -200,6 +206,7 @@ __global__ void fill_nonzeros_kernel(const uint64_t* K, const uint32_t* V, size_
   const uint32_t v = V[p];
   if (g == kCoo) {
     for (int l = 0; l < sp.N; ++l) o.cooInd[l][pos] = idx[l];
+    for (int l = 1; l < sp.N; ++l) mark_row(o.seen[kCoo][l], idx[l]);
     o.cooVal[pos] = v;
     atomicOr(&o.cooBits[idx[0] >> 5], 1u << (idx[0] & 31));
     atomicOr(&o.owned[idx[0] >> 5], 1u << (idx[0] & 31));
@@ -209,11 +216,13 @@ __global__ void fill_nonzeros_kernel(const uint64_t* K, const uint32_t* V, size_
   const uint32_t ord = t.c6[s].s[g];
   if (g == kCsl) {
     for (int l = 1; l < sp.N; ++l) o.cslInd[l][pos] = idx[l];
+    for (int l = 1; l < sp.N; ++l) mark_row(o.seen[kCsl][l], idx[l]);
     o.cslVal[pos] = v;
     if (cut) o.cslRun[pos / sp.L] = ord;
     return;
   }
   o.csfInd[sp.N - 1][pos] = idx[sp.N - 1];
+  mark_row(o.seen[kCsf][sp.N - 1], idx[sp.N - 1]);
   o.csfVal[pos] = v;
   if (cut) o.csfRun[0][pos / sp.L] = ord;
   const uint64_t prev = p ? K[p - 1] : 0;
@@ -223,6 +232,7 @@ __global__ void fill_nonzeros_kernel(const uint64_t* K, const uint32_t* V, size_
       const uint32_t id = (l == 1 ? seg0 : seg1)[p];
       o.csfInd[l][id] = idx[l];
       o.csfPtr[l][id] = pos;
+      mark_row(o.seen[kCsf][l], idx[l]);
       if (cut) o.csfRun[l][pos / sp.L] = id;
     }
   }
@@ -275,13 +285,6 @@ __global__ void zero_words_kernel(uint32_t* p, size_t n) {
   if (i < n) p[i] = 0;
 }
 
-__global__ void mark_rows_kernel(const uint32_t* ind, size_t n, uint32_t* bitmap) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  const uint32_t r = ind[i], bit = 1u << (r & 31);
-  if (!(bitmap[r >> 5] & bit)) atomicOr(&bitmap[r >> 5], bit);
-}
-
 __global__ void count_bits_kernel(const uint32_t* bitmap, size_t words, unsigned long long* dst) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   wave_add(dst, i < words ? (unsigned long long)__popc(bitmap[i]) : 0ull);
@@ -299,7 +302,8 @@ struct Workspace {
   C6* c6;
   unsigned long long* cnt;  // 32 counters
   double* normSq;
-  uint32_t* bitmap;
+  uint32_t* bitmap;      // 3 groups x (order - 1) levels of row bitmaps (statistics)
+  size_t bitmapWords;    // words of one of them
   void* temp;
   size_t tempBytes;
   uint64_t total;
@@ -355,7 +359,8 @@ void carve(Workspace& w, uint8_t* base, size_t M, uint64_t maxDim, size_t tempBy
   w.c6 = (C6*)take((M + 2) * sizeof(C6));
   w.cnt = (unsigned long long*)take(kCounters * 8);
   w.normSq = (double*)take(8);
-  w.bitmap = (uint32_t*)take(((maxDim + 31) / 32 + 1) * 4);
+  w.bitmap = (uint32_t*)take(3 * (HBCSF_MAX_ORDER - 1) * ((maxDim + 31) / 32 + 1) * 4);
+  w.bitmapWords = (maxDim + 31) / 32 + 1;
   w.temp = take(tempBytes);
   w.tempBytes = tempBytes;
   w.total = off;
@@ -531,6 +536,12 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   const size_t ownedWords = (out->rows + 31) / 32;
   hipLaunchKernelGGL(zero_words_kernel, dim3(grid_for(ownedWords)), dim3(256), 0, st, o.owned, ownedWords);
   hipLaunchKernelGGL(zero_words_kernel, dim3(grid_for(ownedWords)), dim3(256), 0, st, o.cooBits, ownedWords);
+  for (int g = 0; g < 3; ++g)
+    for (int l = 1; l < N; ++l) o.seen[g][l] = w.bitmap + (size_t)(g * (HBCSF_MAX_ORDER - 1) + (l - 1)) * w.bitmapWords;
+  {
+    const size_t all = (size_t)3 * (HBCSF_MAX_ORDER - 1) * w.bitmapWords;
+    hipLaunchKernelGGL(zero_words_kernel, dim3(grid_for(all)), dim3(256), 0, st, w.bitmap, all);
+  }
   if (M > 0) {
     hipLaunchKernelGGL(fill_nonzeros_kernel, dim3(grid_for(M)), dim3(256), 0, st, K, V, M, sp, tb, seg[0], seg[1], o);
     hipLaunchKernelGGL(fill_slices_kernel, dim3(grid_for(S)), dim3(256), 0, st, K, S, sp, tb, o, w.cnt);
@@ -551,18 +562,13 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
 
   // ---- statistics that need a pass: rows owned by a plain store, distinct factor rows per group and level ----
   hipLaunchKernelGGL(count_bits_kernel, dim3(grid_for(ownedWords)), dim3(256), 0, st, o.owned, ownedWords, w.cnt + 4);
-  for (int g = 0; g < 3; ++g) {
-    const GroupFormat& G = out->g[g];
+  for (int g = 0; g < 3; ++g)
     for (int l = 1; l < N; ++l) {
-      const uint64_t n = (g == kCsf && l < N - 1) ? G.n[l] : G.nnz;
-      if (n == 0) continue;
+      if (out->g[g].nnz == 0) continue;
       const size_t words = (dims[lv[l]] + 31) / 32;
-      hipLaunchKernelGGL(zero_words_kernel, dim3(grid_for(words)), dim3(256), 0, st, w.bitmap, words);
-      hipLaunchKernelGGL(mark_rows_kernel, dim3(grid_for(n)), dim3(256), 0, st, U32(G.ind[l]), (size_t)n, w.bitmap);
-      hipLaunchKernelGGL(count_bits_kernel, dim3(grid_for(words)), dim3(256), 0, st, w.bitmap, words,
+      hipLaunchKernelGGL(count_bits_kernel, dim3(grid_for(words)), dim3(256), 0, st, o.seen[g][l], words,
                          w.cnt + 8 + g * HBCSF_MAX_ORDER + l);
     }
-  }
   HIP_TRY(hipGetLastError(), "format kernels");
   HIP_TRY(hipMemcpyAsync(hostCnt, w.cnt, kCounters * 8, hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
   HIP_TRY(hipStreamSynchronize(st), "hipStreamSynchronize");

@@ -2,7 +2,8 @@
 
 cfg2 is compared element by element.  cfg3-cfg5 are compared on sampled output rows that the oracle
 computes one by one (the heaviest rows, random non-empty rows and empty rows), plus the cross-mode
-invariant sum(M^(n) * A_n) = const, which holds at any size.
+invariant sum(M^(n) * A_n) = const, which holds at any size.  Each workload's format is then built again by
+the device-side builder and compared, array for array, with the host-built one.
 """
 import time
 
@@ -55,7 +56,44 @@ def _run_workload(oracle, synth, name, full):
         del out
     spread = (max(invariant) - min(invariant)) / max(scale)
     assert spread < 1e-5, f"{name}: cross-mode invariant differs by {spread:.2e}: {invariant}"
+    del dfacs
+    _device_build_matches(t, ht, name)
     ht.close()
+
+
+def _device_build_matches(t, host, name):
+    """The device-side builder must produce the host builder's arrays, which the checks above validated."""
+    import torch
+    from paper_1904_03329_amd import HbcsfTensor, binding as B
+
+    t0 = time.time()
+    di = [torch.from_numpy(x.view(np.int32)).cuda() for x in t.inds]
+    dv = torch.from_numpy(t.vals).cuda()
+    torch.cuda.synchronize()
+    t1 = time.time()
+    dev = HbcsfTensor.from_device_coo(t.dims, di, dv)
+    torch.cuda.synchronize()
+    print(f"{name}: device build {time.time() - t1:.2f}s (COO upload {t1 - t0:.2f}s)", flush=True)
+    del di, dv
+    assert B.device_bytes(dev.handle) == B.device_bytes(host.handle)
+    B.download(dev.handle)
+    for mode in range(t.order):
+        sh, sd = host.stats(mode), dev.stats(mode)
+        sh.pop("build_seconds"), sd.pop("build_seconds")
+        assert sh == sd, f"{name} mode {mode}: statistics differ"
+        for aid in (B.ARR_OWNED_BITS, B.ARR_COO_BITS, B.ARR_COO_PTR):
+            assert np.array_equal(B.host_array(host.handle, mode, 0, 0, aid), B.host_array(dev.handle, mode, 0, 0, aid))
+        for g in range(3):
+            assert np.array_equal(B.host_array(host.handle, mode, g, 0, B.ARR_VAL).view(np.uint32),
+                                  B.host_array(dev.handle, mode, g, 0, B.ARR_VAL).view(np.uint32)), (name, mode, g)
+            for lvl in range(t.order):
+                for aid in (B.ARR_IND, B.ARR_PTR, B.ARR_RUNFIRST):
+                    try:
+                        a = B.host_array(host.handle, mode, g, lvl, aid)
+                    except B.HbcsfError:
+                        continue
+                    assert np.array_equal(a, B.host_array(dev.handle, mode, g, lvl, aid)), (name, mode, g, lvl, aid)
+    dev.close()
 
 
 def test_cfg2_every_element(oracle, synth):
