@@ -149,9 +149,8 @@ __global__ void slice_start_kernel(const uint64_t* K, const uint32_t* sidp, size
 // Section V / VI-D: one nonzero -> COO; every fiber a single nonzero -> CSL; otherwise CSF
 __global__ void classify_kernel(const uint32_t* sStart, const uint32_t* F0, const uint32_t* F1, size_t S, Spec sp,
                                 uint8_t* grp, unsigned long long* cnt) {
-  const size_t s = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   unsigned long long c0 = 0, c1 = 0;
-  if (s < S) {
+  for (size_t s = (size_t)blockIdx.x * blockDim.x + threadIdx.x; s < S; s += (size_t)gridDim.x * blockDim.x) {
     const uint32_t b = sStart[s], e = sStart[s + 1];
     const uint32_t n = e - b;
     const uint32_t nf0 = F0[e - 1] - (b ? F0[b - 1] : 0u);
@@ -163,8 +162,8 @@ __global__ void classify_kernel(const uint32_t* sStart, const uint32_t* F0, cons
     else g = kCsf;
     grp[s] = g;
     if (g == kCsf) {
-      c0 = nf0;
-      c1 = nf1;
+      c0 += nf0;
+      c1 += nf1;
     }
   }
   wave_add(cnt + 2, c0);
@@ -241,9 +240,8 @@ __global__ void fill_nonzeros_kernel(const uint64_t* K, const uint32_t* V, size_
 // per-slice entries of the CSL and CSF groups; a slice inside one run owns its output row
 __global__ void fill_slices_kernel(const uint64_t* K, size_t S, Spec sp, Tables t, OutArrays o,
                                    unsigned long long* cnt) {
-  const size_t s = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   unsigned long long shared = 0;
-  if (s < S) {
+  for (size_t s = (size_t)blockIdx.x * blockDim.x + threadIdx.x; s < S; s += (size_t)gridDim.x * blockDim.x) {
     const int g = t.grp[s];
     if (g != kCoo) {
       const uint32_t b = t.sStart[s], n = t.sStart[s + 1] - b;
@@ -258,7 +256,7 @@ __global__ void fill_slices_kernel(const uint64_t* K, size_t S, Spec sp, Tables 
         o.csfPtr[0][ord] = a;
       }
       if (own) atomicOr(&o.owned[root >> 5], 1u << (root & 31));
-      else shared = 1;
+      else ++shared;
     }
   }
   wave_add(cnt + 1, shared);
@@ -286,10 +284,14 @@ __global__ void zero_words_kernel(uint32_t* p, size_t n) {
 }
 
 __global__ void count_bits_kernel(const uint32_t* bitmap, size_t words, unsigned long long* dst) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  wave_add(dst, i < words ? (unsigned long long)__popc(bitmap[i]) : 0ull);
+  unsigned long long c = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x)
+    c += (unsigned long long)__popc(bitmap[i]);
+  wave_add(dst, c);
 }
 
+// for kernels that loop over their items and end in a few same-address atomics per wavefront
+inline unsigned grid_capped(size_t n) { const size_t b = (n + 255) / 256; return (unsigned)(b < 1 ? 1 : (b > 2048 ? 2048 : b)); }
 inline unsigned grid_for(size_t n) { return (unsigned)((n + 255) / 256 > 0 ? (n + 255) / 256 : 1); }
 inline uint64_t up256(uint64_t v) { return (v + 255) / 256 * 256; }
 
@@ -484,7 +486,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
     fibNat[1] = tail[2];
 
     // ---- groups, and where every slice starts inside its group ----
-    hipLaunchKernelGGL(classify_kernel, dim3(grid_for(S)), dim3(256), 0, st, w.sStart, seg[0], seg[1], S, sp, w.grp,
+    hipLaunchKernelGGL(classify_kernel, dim3(grid_capped(S)), dim3(256), 0, st, w.sStart, seg[0], seg[1], S, sp, w.grp,
                        w.cnt);
     tb_ = w.tempBytes;
     HIP_TRY(rocprim::exclusive_scan(w.temp, tb_, rocprim::make_transform_iterator(cit, SliceIn{w.grp, w.sStart, S}),
@@ -544,7 +546,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   }
   if (M > 0) {
     hipLaunchKernelGGL(fill_nonzeros_kernel, dim3(grid_for(M)), dim3(256), 0, st, K, V, M, sp, tb, seg[0], seg[1], o);
-    hipLaunchKernelGGL(fill_slices_kernel, dim3(grid_for(S)), dim3(256), 0, st, K, S, sp, tb, o, w.cnt);
+    hipLaunchKernelGGL(fill_slices_kernel, dim3(grid_capped(S)), dim3(256), 0, st, K, S, sp, tb, o, w.cnt);
   }
   Sentinels z{};
   z.cslN0 = out->g[kCsl].n[0];
@@ -561,12 +563,12 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   }
 
   // ---- statistics that need a pass: rows owned by a plain store, distinct factor rows per group and level ----
-  hipLaunchKernelGGL(count_bits_kernel, dim3(grid_for(ownedWords)), dim3(256), 0, st, o.owned, ownedWords, w.cnt + 4);
+  hipLaunchKernelGGL(count_bits_kernel, dim3(grid_capped(ownedWords)), dim3(256), 0, st, o.owned, ownedWords, w.cnt + 4);
   for (int g = 0; g < 3; ++g)
     for (int l = 1; l < N; ++l) {
       if (out->g[g].nnz == 0) continue;
       const size_t words = (dims[lv[l]] + 31) / 32;
-      hipLaunchKernelGGL(count_bits_kernel, dim3(grid_for(words)), dim3(256), 0, st, o.seen[g][l], words,
+      hipLaunchKernelGGL(count_bits_kernel, dim3(grid_capped(words)), dim3(256), 0, st, o.seen[g][l], words,
                          w.cnt + 8 + g * HBCSF_MAX_ORDER + l);
     }
   HIP_TRY(hipGetLastError(), "format kernels");
