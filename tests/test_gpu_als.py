@@ -130,6 +130,15 @@ def test_config1_shape(synth):
     _check(t.dims, t.inds, t.vals, facs, rank)
 
 
+def test_config2_shape_at_one_tenth(synth):
+    """One iteration on the second workload's index laws at R = 32, scaled to 500 000 nonzeros so that the numpy
+    oracle finishes in seconds (10 000-row factors still span many wavefront chunks of the dense kernels)."""
+    t, _, rank = synth.workload("cfg2", scale=0.1)
+    rng = np.random.default_rng(700)
+    facs = [rng.uniform(-1, 1, size=(d, rank)).astype(np.float32) for d in t.dims]
+    _check(t.dims, t.inds, t.vals, facs, rank)
+
+
 def test_argument_errors():
     import torch
     from paper_1904_03329_amd import HbcsfTensor, binding as B
