@@ -24,6 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+FP32_VECTOR_PEAK_GFLOPS = 157300.0  # published plain vector fp32 peak (counts packed FMA on every lane)
 KERNELS = ("define", "coo", "csl", "csf")
 
 # HBM-side bytes per B-CSF-kernel launch (mean over the modes) measured with rocprofv3 --pmc
@@ -50,6 +51,15 @@ def algorithmic_bytes(st: dict, rank: int, order: int) -> dict:
     # take the zero fill out again so that the dense output is counted exactly once in the total
     out["total"] = sum(out[k] for k in KERNELS) - row * st["shared_slices"]
     return out
+
+
+def gather_bytes(st: dict, rank: int, order: int) -> int:
+    """Bytes through the cache hierarchy when every row gather is counted (not HBM bytes): format arrays +
+    one factor row per leaf-level gather and per fiber-segment gather + the output once."""
+    row = 4 * rank
+    coo, csl, csf = st["group_nnz"]
+    gathers = (order - 1) * (coo + csl) + csf + sum(st["segments"][: order - 2])
+    return sum(st["stream_bytes"]) + row * gathers + row * st["rows"]
 
 
 def calibrate(torch, log) -> int:
@@ -326,6 +336,14 @@ def main() -> int:
             "shared_slices": stats[m]["shared_slices"],
             "real_gflops": round(stats[m]["flops_real"] * rank / (tot_ms * 1e-3) / 1e9, 1),
         }
+        # the two roofs side by side: time the algorithmic bytes need at the HBM peak, time the multiply-adds really
+        # done need at the vector fp32 peak, and the larger of the two over the measured time
+        t_hbm = ab["total"] / (HBM_PEAK_GBS * 1e9) * 1e3
+        t_alu = stats[m]["flops_real"] * rank / (FP32_VECTOR_PEAK_GFLOPS * 1e9) * 1e3
+        gb = gather_bytes(stats[m], rank, order)
+        entry.update({"t_hbm_ms": round(t_hbm, 4), "t_alu_ms": round(t_alu, 4),
+                      "roof_frac": round(max(t_hbm, t_alu) / tot_ms, 4),
+                      "gather_model_bytes": gb, "gather_gbs": round(gb / (tot_ms * 1e-3) / 1e9, 1)})
         if order == 4:
             entry["gflops_4Rnnz"] = round(4.0 * rank * t.nnz / (tot_ms * 1e-3) / 1e9, 1)
         per_mode.append(entry)
