@@ -176,8 +176,8 @@ int hbcsf_kernel_ms(hbcsf_tensor *t, uint32_t calls_back, float ms[4]);
  * Format construction on the device (the pre-processing of Sections IV-V, whose cost Section VI-E
  * weighs against the MTTKRP time): the same per-mode HB-CSF arrays as hbcsf_build_format, byte for
  * byte, built from COO arrays that already are in device memory and written straight into the
- * caller's device arena.  Tensors whose packed coordinate (sum over the modes of
- * ceil(log2(dim))) exceeds 64 bits are refused with HBCSF_ERANGE; build those on the host.
+ * caller's device arena.  Packed coordinates (sum over the modes of ceil(log2(dim)) bits) above
+ * 64 bits are sorted in two stable 64-bit passes.
  * ------------------------------------------------------------------------------------------- */
 
 /* Sizes to allocate before hbcsf_build_format_device: arena_bytes is an upper bound over every

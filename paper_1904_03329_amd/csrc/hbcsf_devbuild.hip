@@ -28,6 +28,8 @@ using namespace hbcsf;
 
 namespace {
 
+typedef unsigned __int128 u128;
+
 struct Spec {
   int N, NF;
   int shift[HBCSF_MAX_ORDER];
@@ -62,16 +64,18 @@ __device__ __forceinline__ void locate(const Tables& t, size_t p, uint32_t& s, i
   pos = t.c6[s].m[g] + (uint32_t)(p - t.sStart[s]);
 }
 
+template <typename Key>
 struct FreshFlag {  // 1 where the index at some tree level (and everything above it) changes
-  const uint64_t* K;
+  const Key* K;
   int shift;
   __device__ uint32_t operator()(size_t p) const {
     return (p == 0 || (K[p] >> shift) != (K[p - 1] >> shift)) ? 1u : 0u;
   }
 };
 
+template <typename Key>
 struct SegFlag {  // 1 where a fiber segment of the CSF group starts
-  const uint64_t* K;
+  const Key* K;
   int shift;
   Tables t;
   uint32_t L;
@@ -121,25 +125,58 @@ struct IndPtrs {
   const uint32_t* p[HBCSF_MAX_ORDER];
 };
 
+struct Carried {  // what rides along while one 64-bit half of a wide key is being sorted
+  uint64_t other;  // the half that is not the sort key of this pass
+  uint32_t v, pad;
+};
+
+// Key = uint64_t: K / V receive the packed key and the value bits.  Key = u128: the key is sorted in two
+// stable 64-bit passes, so the low half goes to K (as uint64_t) and the high half rides in C.
+template <typename Key>
 __global__ void pack_kernel(IndPtrs inds, const float* vals, size_t M, Spec sp, uint64_t dim0, uint64_t dim1,
-                            uint64_t dim2, uint64_t dim3, uint64_t* K, uint32_t* V, unsigned long long* cnt) {
+                            uint64_t dim2, uint64_t dim3, uint64_t* K, uint32_t* V, Carried* C,
+                            unsigned long long* cnt) {
   const size_t z = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (z >= M) return;
   const uint64_t dims[HBCSF_MAX_ORDER] = {dim0, dim1, dim2, dim3};
-  uint64_t key = 0;
+  Key key = 0;
   bool bad = false;
   for (int l = 0; l < sp.N; ++l) {
     const uint32_t i = inds.p[l][z];
     bad = bad || (uint64_t)i >= dims[l];
-    key |= (uint64_t)i << sp.shift[l];
+    key |= (Key)i << sp.shift[l];
   }
-  K[z] = key;
-  V[z] = __float_as_uint(vals[z]);
+  if (sizeof(Key) == 8) {
+    K[z] = (uint64_t)key;
+    V[z] = __float_as_uint(vals[z]);
+  } else {
+    K[z] = (uint64_t)key;
+    C[z] = Carried{(uint64_t)((u128)key >> 64), __float_as_uint(vals[z]), 0u};
+  }
   if (bad) atomicOr(cnt, 1ull);
 }
 
+// between the two passes of a wide sort: the high half becomes the key, the low half rides along
+__global__ void swap_halves_kernel(const uint64_t* keyIn, const Carried* carIn, size_t M, uint64_t* keyOut,
+                                   Carried* carOut) {
+  const size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= M) return;
+  const Carried c = carIn[p];
+  keyOut[p] = c.other;
+  carOut[p] = Carried{keyIn[p], c.v, 0u};
+}
+
+__global__ void join_halves_kernel(const uint64_t* hi, const Carried* car, size_t M, u128* K, uint32_t* V) {
+  const size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= M) return;
+  const Carried c = car[p];
+  K[p] = ((u128)hi[p] << 64) | (u128)c.other;
+  V[p] = c.v;
+}
+
 // first nonzero of every slice, from the scanned slice numbers
-__global__ void slice_start_kernel(const uint64_t* K, const uint32_t* sidp, size_t M, int shift0, uint32_t* sStart) {
+template <typename Key>
+__global__ void slice_start_kernel(const Key* K, const uint32_t* sidp, size_t M, int shift0, uint32_t* sStart) {
   const size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= M) return;
   if (p == 0 || (K[p] >> shift0) != (K[p - 1] >> shift0)) sStart[sidp[p] - 1] = (uint32_t)p;
@@ -192,16 +229,17 @@ __device__ __forceinline__ void mark_row(uint32_t* bitmap, uint32_t r) {
 }
 
 // every nonzero writes itself into its group's stream; segment starts write the fiber-level entries
-__global__ void fill_nonzeros_kernel(const uint64_t* K, const uint32_t* V, size_t M, Spec sp, Tables t,
+template <typename Key>
+__global__ void fill_nonzeros_kernel(const Key* K, const uint32_t* V, size_t M, Spec sp, Tables t,
                                      const uint32_t* seg0, const uint32_t* seg1, OutArrays o) {
   const size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= M) return;
   uint32_t s, pos;
   int g;
   locate(t, p, s, g, pos);
-  const uint64_t key = K[p];
+  const Key key = K[p];
   uint32_t idx[HBCSF_MAX_ORDER];
-  for (int l = 0; l < sp.N; ++l) idx[l] = (uint32_t)((key >> sp.shift[l]) & sp.mask[l]);
+  for (int l = 0; l < sp.N; ++l) idx[l] = (uint32_t)((uint64_t)(key >> sp.shift[l]) & sp.mask[l]);
   const uint32_t v = V[p];
   if (g == kCoo) {
     for (int l = 0; l < sp.N; ++l) o.cooInd[l][pos] = idx[l];
@@ -224,7 +262,7 @@ __global__ void fill_nonzeros_kernel(const uint64_t* K, const uint32_t* V, size_
   mark_row(o.seen[kCsf][sp.N - 1], idx[sp.N - 1]);
   o.csfVal[pos] = v;
   if (cut) o.csfRun[0][pos / sp.L] = ord;
-  const uint64_t prev = p ? K[p - 1] : 0;
+  const Key prev = p ? K[p - 1] : (Key)0;
   for (int l = 1; l <= sp.NF; ++l) {
     const bool fresh = p == 0 || (key >> sp.shift[l]) != (prev >> sp.shift[l]);
     if (cut || fresh) {
@@ -238,7 +276,8 @@ __global__ void fill_nonzeros_kernel(const uint64_t* K, const uint32_t* V, size_
 }
 
 // per-slice entries of the CSL and CSF groups; a slice inside one run owns its output row
-__global__ void fill_slices_kernel(const uint64_t* K, size_t S, Spec sp, Tables t, OutArrays o,
+template <typename Key>
+__global__ void fill_slices_kernel(const Key* K, size_t S, Spec sp, Tables t, OutArrays o,
                                    unsigned long long* cnt) {
   unsigned long long shared = 0;
   for (size_t s = (size_t)blockIdx.x * blockDim.x + threadIdx.x; s < S; s += (size_t)gridDim.x * blockDim.x) {
@@ -246,7 +285,7 @@ __global__ void fill_slices_kernel(const uint64_t* K, size_t S, Spec sp, Tables 
     if (g != kCoo) {
       const uint32_t b = t.sStart[s], n = t.sStart[s + 1] - b;
       const uint32_t a = t.c6[s].m[g], ord = t.c6[s].s[g];
-      const uint32_t root = (uint32_t)((K[b] >> sp.shift[0]) & sp.mask[0]);
+      const uint32_t root = (uint32_t)((uint64_t)(K[b] >> sp.shift[0]) & sp.mask[0]);
       const bool own = (a / sp.L) == ((a + n - 1) / sp.L);
       if (g == kCsl) {
         o.cslInd[0][ord] = root | (own ? kOwnedBit : 0u);
@@ -297,8 +336,10 @@ inline uint64_t up256(uint64_t v) { return (v + 255) / 256 * 256; }
 
 // Workspace carve-up for M nonzeros; `temp` is the rocPRIM scratch, sized by temp_bytes().
 struct Workspace {
-  uint64_t* K[2];
-  uint32_t* V[2];
+  uint64_t* K[2];        // 64-bit sort keys (the packed key, or one half of a wide key), double buffered
+  uint32_t* V[2];        // values riding along a 64-bit key sort, double buffered
+  Carried* C[2];         // wide keys only: the other half + value, double buffered
+  u128* K128;            // wide keys only: the sorted keys put together again
   uint32_t* sStart;
   uint8_t* grp;
   C6* c6;
@@ -314,20 +355,27 @@ struct Workspace {
 constexpr int kCounters = 32;
 
 hipError_t temp_bytes(size_t M, size_t maxWords, int totalBits, size_t* out) {
+  const bool wide = totalBits > 64;
   // the largest scratch any rocPRIM call below asks for
   size_t need = 0, b = 0;
   hipError_t e;
   rocprim::double_buffer<uint64_t> kb((uint64_t*)nullptr, (uint64_t*)nullptr);
   rocprim::double_buffer<uint32_t> vb((uint32_t*)nullptr, (uint32_t*)nullptr);
-  e = rocprim::radix_sort_pairs(nullptr, b, kb, vb, M, 0u, (unsigned)totalBits);
+  e = rocprim::radix_sort_pairs(nullptr, b, kb, vb, M, 0u, (unsigned)(wide ? 64 : totalBits));
   if (e != hipSuccess) return e;
   need = b > need ? b : need;
+  if (wide) {
+    rocprim::double_buffer<Carried> cb((Carried*)nullptr, (Carried*)nullptr);
+    e = rocprim::radix_sort_pairs(nullptr, b, kb, cb, M, 0u, 64u);
+    if (e != hipSuccess) return e;
+    need = b > need ? b : need;
+  }
   auto cnt = rocprim::counting_iterator<size_t>(0);
-  e = rocprim::inclusive_scan(nullptr, b, rocprim::make_transform_iterator(cnt, FreshFlag{nullptr, 0}),
+  e = rocprim::inclusive_scan(nullptr, b, rocprim::make_transform_iterator(cnt, FreshFlag<u128>{nullptr, 0}),
                               (uint32_t*)nullptr, M + 1, rocprim::plus<uint32_t>());
   if (e != hipSuccess) return e;
   need = b > need ? b : need;
-  e = rocprim::exclusive_scan(nullptr, b, rocprim::make_transform_iterator(cnt, SegFlag{nullptr, 0, Tables{}, 1, 0}),
+  e = rocprim::exclusive_scan(nullptr, b, rocprim::make_transform_iterator(cnt, SegFlag<u128>{nullptr, 0, Tables{}, 1, 0}),
                               (uint32_t*)nullptr, 0u, M + 1, rocprim::plus<uint32_t>());
   if (e != hipSuccess) return e;
   need = b > need ? b : need;
@@ -347,7 +395,7 @@ hipError_t temp_bytes(size_t M, size_t maxWords, int totalBits, size_t* out) {
   return hipSuccess;
 }
 
-void carve(Workspace& w, uint8_t* base, size_t M, uint64_t maxDim, size_t tempBytes) {
+void carve(Workspace& w, uint8_t* base, size_t M, uint64_t maxDim, size_t tempBytes, bool wide) {
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) {
     uint8_t* p = base ? base + off : nullptr;
@@ -356,6 +404,8 @@ void carve(Workspace& w, uint8_t* base, size_t M, uint64_t maxDim, size_t tempBy
   };
   for (int i = 0; i < 2; ++i) w.K[i] = (uint64_t*)take((M + 1) * 8);
   for (int i = 0; i < 2; ++i) w.V[i] = (uint32_t*)take((M + 1) * 4);
+  for (int i = 0; i < 2; ++i) w.C[i] = wide ? (Carried*)take((M + 1) * sizeof(Carried)) : nullptr;
+  w.K128 = wide ? (u128*)take((M + 1) * 16) : nullptr;
   w.sStart = (uint32_t*)take((M + 2) * 4);
   w.grp = (uint8_t*)take(M + 1);
   w.c6 = (C6*)take((M + 2) * sizeof(C6));
@@ -386,8 +436,6 @@ int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* 
     if (dims[m] == 0 || dims[m] > 0x7ffffffeull) return fail(HBCSF_ERANGE, "each dimension must be in 1 .. 2^31-2");
     total += bits_for(dims[m]);
   }
-  if (total > 64)
-    return fail(HBCSF_ERANGE, "the packed coordinate needs more than 64 bits: build this tensor with hbcsf_build_format");
   *o = hbcsf_opts{};
   if (opts) *o = *opts;
   if (o->fiber_threshold == 0) o->fiber_threshold = 64;
@@ -405,6 +453,7 @@ int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* 
     if (e_ != hipSuccess) return fail_hip(e_, what); \
   } while (0)
 
+template <typename Key>
 int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* const* inds, const float* vals,
                       const hbcsf_opts& opts, int mode, int totalBits, Workspace& w, uint8_t* arena,
                       uint64_t arenaBytes, uint64_t* arenaUsed, ModeFormat* out, hipStream_t st) {
@@ -435,7 +484,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   unsigned long long hostCnt[kCounters];
   std::memset(hostCnt, 0, sizeof(hostCnt));
   HIP_TRY(hipMemsetAsync(w.cnt, 0, kCounters * 8, st), "hipMemsetAsync");
-  const uint64_t* K = w.K[0];
+  const Key* K = nullptr;
   const uint32_t* V = w.V[0];
   uint32_t* sidp = nullptr;
   uint32_t* seg[2] = {nullptr, nullptr};
@@ -450,28 +499,48 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
       ip.p[l] = inds[lv[l]];
       dl[l] = dims[lv[l]];
     }
-    hipLaunchKernelGGL(pack_kernel, dim3(grid_for(M)), dim3(256), 0, st, ip, vals, M, sp, dl[0], dl[1], dl[2], dl[3],
-                       w.K[0], w.V[0], w.cnt);
+    constexpr bool kWide = sizeof(Key) == 16;
+    hipLaunchKernelGGL(pack_kernel<Key>, dim3(grid_for(M)), dim3(256), 0, st, ip, vals, M, sp, dl[0], dl[1], dl[2],
+                       dl[3], w.K[0], w.V[0], w.C[0], w.cnt);
     rocprim::double_buffer<uint64_t> kb(w.K[0], w.K[1]);
-    rocprim::double_buffer<uint32_t> vb(w.V[0], w.V[1]);
     size_t tb_ = w.tempBytes;
-    HIP_TRY(rocprim::radix_sort_pairs(w.temp, tb_, kb, vb, M, 0u, (unsigned)totalBits, st), "radix sort");
-    K = kb.current();
-    V = vb.current();
-    // the buffers the sort no longer needs hold the per-nonzero scans from here on
-    sidp = (uint32_t*)kb.alternate();
-    seg[0] = sidp + (M + 1);
-    seg[1] = vb.alternate();
+    if (!kWide) {
+      rocprim::double_buffer<uint32_t> vb(w.V[0], w.V[1]);
+      HIP_TRY(rocprim::radix_sort_pairs(w.temp, tb_, kb, vb, M, 0u, (unsigned)totalBits, st), "radix sort");
+      K = (const Key*)kb.current();
+      V = vb.current();
+      // the buffers the sort no longer needs hold the per-nonzero scans from here on
+      sidp = (uint32_t*)kb.alternate();
+      seg[0] = sidp + (M + 1);
+      seg[1] = vb.alternate();
+    } else {
+      // two stable passes: by the low 64 bits with the high half riding along, then by the high bits
+      rocprim::double_buffer<Carried> cb(w.C[0], w.C[1]);
+      HIP_TRY(rocprim::radix_sort_pairs(w.temp, tb_, kb, cb, M, 0u, 64u, st), "radix sort");
+      hipLaunchKernelGGL(swap_halves_kernel, dim3(grid_for(M)), dim3(256), 0, st, kb.current(), cb.current(), M,
+                         kb.alternate(), cb.alternate());
+      rocprim::double_buffer<uint64_t> kb2(kb.alternate(), kb.current());
+      rocprim::double_buffer<Carried> cb2(cb.alternate(), cb.current());
+      tb_ = w.tempBytes;
+      HIP_TRY(rocprim::radix_sort_pairs(w.temp, tb_, kb2, cb2, M, 0u, (unsigned)(totalBits - 64), st), "radix sort");
+      hipLaunchKernelGGL(join_halves_kernel, dim3(grid_for(M)), dim3(256), 0, st, kb2.current(), cb2.current(), M,
+                         w.K128, w.V[1]);
+      K = (const Key*)w.K128;
+      V = w.V[1];
+      sidp = (uint32_t*)w.K[0];      // 8 (M + 1) bytes: slice numbers and the first fiber level's scan
+      seg[0] = sidp + (M + 1);
+      seg[1] = w.V[0];
+    }
 
     // ---- slices: scan of "root index changes" ----
     tb_ = w.tempBytes;
-    HIP_TRY(rocprim::inclusive_scan(w.temp, tb_, rocprim::make_transform_iterator(cit, FreshFlag{K, sp.shift[0]}),
+    HIP_TRY(rocprim::inclusive_scan(w.temp, tb_, rocprim::make_transform_iterator(cit, FreshFlag<Key>{K, sp.shift[0]}),
                                     sidp, M, rocprim::plus<uint32_t>(), st), "scan");
-    hipLaunchKernelGGL(slice_start_kernel, dim3(grid_for(M)), dim3(256), 0, st, K, sidp, M, sp.shift[0], w.sStart);
+    hipLaunchKernelGGL(slice_start_kernel<Key>, dim3(grid_for(M)), dim3(256), 0, st, K, sidp, M, sp.shift[0], w.sStart);
     // natural fibers per level (the deepest level decides CSL membership)
     for (int f = 0; f < sp.NF; ++f) {
       tb_ = w.tempBytes;
-      HIP_TRY(rocprim::inclusive_scan(w.temp, tb_, rocprim::make_transform_iterator(cit, FreshFlag{K, sp.shift[1 + f]}),
+      HIP_TRY(rocprim::inclusive_scan(w.temp, tb_, rocprim::make_transform_iterator(cit, FreshFlag<Key>{K, sp.shift[1 + f]}),
                                       seg[f], M, rocprim::plus<uint32_t>(), st), "scan");
     }
     uint32_t tail[3] = {0, 0, 0};
@@ -496,7 +565,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
     for (int f = 0; f < sp.NF; ++f) {
       tb_ = w.tempBytes;
       HIP_TRY(rocprim::exclusive_scan(w.temp, tb_,
-                                      rocprim::make_transform_iterator(cit, SegFlag{K, sp.shift[1 + f], tb, sp.L, M}),
+                                      rocprim::make_transform_iterator(cit, SegFlag<Key>{K, sp.shift[1 + f], tb, sp.L, M}),
                                       seg[f], 0u, M + 1, rocprim::plus<uint32_t>(), st), "scan");
     }
     C6 totals{};
@@ -545,8 +614,8 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
     hipLaunchKernelGGL(zero_words_kernel, dim3(grid_for(all)), dim3(256), 0, st, w.bitmap, all);
   }
   if (M > 0) {
-    hipLaunchKernelGGL(fill_nonzeros_kernel, dim3(grid_for(M)), dim3(256), 0, st, K, V, M, sp, tb, seg[0], seg[1], o);
-    hipLaunchKernelGGL(fill_slices_kernel, dim3(grid_capped(S)), dim3(256), 0, st, K, S, sp, tb, o, w.cnt);
+    hipLaunchKernelGGL(fill_nonzeros_kernel<Key>, dim3(grid_for(M)), dim3(256), 0, st, K, V, M, sp, tb, seg[0], seg[1], o);
+    hipLaunchKernelGGL(fill_slices_kernel<Key>, dim3(grid_capped(S)), dim3(256), 0, st, K, S, sp, tb, o, w.cnt);
   }
   Sentinels z{};
   z.cslN0 = out->g[kCsl].n[0];
@@ -599,7 +668,7 @@ int hbcsf_device_build_bytes(int order, const uint64_t* dims, uint64_t nnz, cons
   size_t tbytes = 0;
   HIP_TRY(temp_bytes((size_t)nnz, (size_t)((maxDim + 31) / 32), totalBits, &tbytes), "rocPRIM scratch query");
   Workspace w{};
-  carve(w, nullptr, (size_t)nnz, maxDim, tbytes);
+  carve(w, nullptr, (size_t)nnz, maxDim, tbytes, totalBits > 64);
   *workspace_bytes = w.total;
   *arena_bytes = arena_bound(order, dims, nnz, o.fiber_threshold);
   return HBCSF_OK;
@@ -626,7 +695,7 @@ int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, con
   size_t tbytes = 0;
   HIP_TRY(temp_bytes((size_t)nnz, (size_t)((maxDim + 31) / 32), totalBits, &tbytes), "rocPRIM scratch query");
   Workspace w{};
-  carve(w, (uint8_t*)workspace, (size_t)nnz, maxDim, tbytes);
+  carve(w, (uint8_t*)workspace, (size_t)nnz, maxDim, tbytes, totalBits > 64);
   if (workspace_bytes < w.total) return fail(HBCSF_ENOMEM, "workspace is smaller than hbcsf_device_build_bytes");
 
   std::unique_ptr<hbcsf_tensor> t(new (std::nothrow) hbcsf_tensor);
@@ -644,8 +713,11 @@ int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, con
   for (int m = 0; m < order; ++m) {
     t->modes[m].reset(new (std::nothrow) ModeFormat);
     if (!t->modes[m]) return fail(HBCSF_ENOMEM, "out of host memory");
-    const int rb = build_mode_device(order, dims, (size_t)nnz, inds, vals, o, m, totalBits, w, (uint8_t*)device_arena,
-                                     arena_bytes, &used, t->modes[m].get(), st);
+    const int rb = totalBits > 64
+                       ? build_mode_device<u128>(order, dims, (size_t)nnz, inds, vals, o, m, totalBits, w,
+                                                 (uint8_t*)device_arena, arena_bytes, &used, t->modes[m].get(), st)
+                       : build_mode_device<uint64_t>(order, dims, (size_t)nnz, inds, vals, o, m, totalBits, w,
+                                                     (uint8_t*)device_arena, arena_bytes, &used, t->modes[m].get(), st);
     if (rb != HBCSF_OK) return rb;
   }
   double sq = 0.0;

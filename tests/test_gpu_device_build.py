@@ -152,6 +152,29 @@ def test_degenerate_shapes():
     assert_same_format((1_000_000, 7_000, n), inds, np.ones(n, dtype=np.float32)).close()
 
 
+@pytest.mark.parametrize("dims", [(100_000, 90_000, 80_000, 70_000), (2_000_000_000, 1_500_000_000, 3_000)])
+def test_wide_coordinates_sort_in_two_passes(oracle, dims):
+    """Packed coordinates above 64 bits (68 and 74 here) take the 128-bit key path of both builders."""
+    import torch
+
+    rng = np.random.default_rng(len(dims))
+    nnz = 30_000
+    inds = [rng.integers(0, d, nnz).astype(np.uint32) for d in dims]
+    for x in inds:                                              # repeated indices so that slices and fibers exist
+        x[nnz // 2:] = x[rng.integers(0, 200, nnz - nnz // 2)]
+    vals = rng.uniform(-1, 1, nnz).astype(np.float32)
+    dev = assert_same_format(dims, inds, vals)
+    mode = len(dims) - 1                                        # the shortest mode: a dense check is affordable
+    rank = 8
+    facs = [None if d > 1_000_000 else rng.uniform(0, 1, size=(d, rank)).astype(np.float32) for d in dims]
+    if all(f is not None for f in facs):
+        dfacs = [torch.from_numpy(f).cuda() for f in facs]
+        out = dev.mttkrp(mode, dfacs)
+        torch.cuda.synchronize()
+        GU.assert_close(out.cpu().numpy(), oracle.mttkrp(dims, inds, vals, facs, mode), "wide keys")
+    dev.close()
+
+
 def test_cfg2_full_size(synth):
     t, _, _ = synth.workload("cfg2")
     assert_same_format(t.dims, t.inds, t.vals).close()
@@ -167,9 +190,6 @@ def test_errors():
     bad[1][7] = 40
     with pytest.raises(B.HbcsfError) as e:
         _device_tensor(dims, bad, vals)
-    assert e.value.code == -2
-    with pytest.raises(B.HbcsfError) as e:                      # 4 x 17 bits > 64
-        B.device_build_bytes((100_000,) * 4, 10)
     assert e.value.code == -2
     with pytest.raises(B.HbcsfError) as e:
         B.device_build_bytes(dims, 10, fiber_threshold=5)
