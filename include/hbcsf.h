@@ -245,6 +245,13 @@ int hbcsf_als_create(const hbcsf_tensor *t, int rank, void *workspace, uint64_t 
 int hbcsf_als_iteration(hbcsf_als *a, float *const *factors, float *lambda, int flags, double *fit,
                         void *hip_stream);
 
+/* The algorithm's outer loop: iterations until the fit changes by less than `tolerance` between two
+ * consecutive iterations, or `max_iterations` (>= 1) are done.  The first iteration computes the
+ * factors' Gram matrices, the later ones carry them over.  iterations_done, fit: host, may be null.
+ * Other arguments and errors as hbcsf_als_iteration. */
+int hbcsf_als_run(hbcsf_als *a, float *const *factors, float *lambda, int max_iterations,
+                  double tolerance, int *iterations_done, double *fit, void *hip_stream);
+
 /* Device/host time of the last iteration, summed over the modes, in milliseconds: ms[0] MTTKRP,
  * ms[1] Gram kernel with its read-back, ms[2] host R x R algebra, ms[3] product kernel with its
  * R x R upload. */

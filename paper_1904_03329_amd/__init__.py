@@ -132,6 +132,13 @@ class CpdAls:
                                      binding.ALS_KEEP_GRAMS if keep_grams else 0, True,
                                      torch.cuda.current_stream().cuda_stream)
 
+    def run(self, factors, max_iterations: int = 50, tolerance: float = 1e-5):
+        """Iterates until the fit changes by less than `tolerance`; returns (iterations done, fit)."""
+        import torch
+
+        return binding.als_run(self.handle, [f.data_ptr() for f in factors], self.lam.data_ptr(), max_iterations,
+                               tolerance, torch.cuda.current_stream().cuda_stream)
+
     def phase_ms(self):
         return binding.als_phase_ms(self.handle)
 

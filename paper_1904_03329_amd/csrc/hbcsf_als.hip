@@ -539,6 +539,26 @@ int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int 
   return HBCSF_OK;
 }
 
+int hbcsf_als_run(hbcsf_als* a, float* const* factors, float* lambda, int max_iterations, double tolerance,
+                  int* iterations_done, double* fit, void* hip_stream) {
+  if (!a || !factors) return fail(HBCSF_EINVAL, "null argument");
+  if (max_iterations < 1) return fail(HBCSF_EINVAL, "max_iterations must be at least 1");
+  double prev = 0.0, cur = 0.0;
+  int it = 0;
+  for (; it < max_iterations; ++it) {
+    const int rc = hbcsf_als_iteration(a, factors, lambda, it > 0 ? HBCSF_ALS_KEEP_GRAMS : 0, &cur, hip_stream);
+    if (rc != HBCSF_OK) return rc;
+    if (it > 0 && std::fabs(cur - prev) < tolerance) {
+      ++it;
+      break;
+    }
+    prev = cur;
+  }
+  if (iterations_done) *iterations_done = it;
+  if (fit) *fit = cur;
+  return HBCSF_OK;
+}
+
 int hbcsf_sym_pinv(const double* v, int n, double* out) {
   if (!v || !out) return fail(HBCSF_EINVAL, "null argument");
   if (n < 1 || n > 128) return fail(HBCSF_EINVAL, "n must be in 1 .. 128");

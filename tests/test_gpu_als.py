@@ -139,6 +139,32 @@ def test_config2_shape_at_one_tenth(synth):
     _check(t.dims, t.inds, t.vals, facs, rank)
 
 
+def test_run_until_the_fit_settles():
+    """The outer loop on a noisy low-rank tensor: stops by the tolerance, before the iteration cap, at the fit
+    the oracle reaches with the same number of iterations."""
+    import torch
+    from paper_1904_03329_amd import CpdAls, HbcsfTensor
+
+    rng = np.random.default_rng(800)
+    dims, rank = (60, 50, 40), 8
+    true = [rng.uniform(0, 1, size=(d, rank)) for d in dims]
+    grid = np.meshgrid(*[np.arange(d) for d in dims], indexing="ij")
+    inds = [g.ravel().astype(np.uint32) for g in grid]
+    vals = (cpd_als.model_values(inds, true, np.ones(rank)) + 0.05 * rng.normal(size=len(inds[0]))).astype(np.float32)
+    facs = [rng.uniform(0, 1, size=(d, rank)).astype(np.float32) for d in dims]
+    t = HbcsfTensor(dims, inds, vals).to_device()
+    als = CpdAls(t, rank)
+    dfacs = [torch.from_numpy(f).cuda() for f in facs]
+    done, fit = als.run(dfacs, max_iterations=200, tolerance=1e-4)
+    assert 2 <= done < 200 and fit > 0.8
+    want = [f.astype(np.float64) for f in facs]
+    for _ in range(done):
+        want, lam = cpd_als.als_iteration(dims, inds, vals, want)
+    assert abs(fit - cpd_als.fit(dims, inds, vals, want, lam)) < 2e-3
+    als.close()
+    t.close()
+
+
 def test_argument_errors():
     import torch
     from paper_1904_03329_amd import HbcsfTensor, binding as B
