@@ -219,3 +219,46 @@ def test_random_small_tensors(oracle, seed):
                 mode_order_policy=int(rng.integers(0, 3)))
     print("random", seed, dims, nnz, rank, opts, flush=True)
     _check_all_modes(oracle, dims, inds, vals, _factors(rng, dims, rank), f"random {seed}", **opts)
+
+
+def test_calls_replay_from_a_hip_graph(oracle):
+    """hbcsf_mttkrp only launches kernels on the caller's stream (the output is cleared by a fill kernel, not a
+    memset), so a step over all modes can be captured once and replayed; every replay, with eager work and
+    synchronisations in between, must reproduce the eager result."""
+    import torch
+    from paper_1904_03329_amd import HbcsfTensor
+
+    rng = np.random.default_rng(4242)
+    dims, rank = (4000, 500, 70), 32
+    inds, vals = _skewed(rng, dims, 150_000)
+    facs = _factors(rng, dims, rank)
+    t = HbcsfTensor(dims, inds, vals).to_device()
+    dfacs = [torch.from_numpy(f).cuda() for f in facs]
+    outs = [torch.empty((d, rank), dtype=torch.float32, device="cuda") for d in dims]
+    eager = []
+    for mode in range(3):                       # also warms up the launch-size queries
+        t.mttkrp(mode, dfacs, outs[mode])
+    torch.cuda.synchronize()
+    for mode in range(3):
+        GU.assert_close(outs[mode].cpu().numpy(), oracle.mttkrp(dims, inds, vals, facs, mode), f"eager mode {mode}")
+        eager.append(outs[mode].clone())
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for mode in range(3):
+                t.mttkrp(mode, dfacs, outs[mode])
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for o in outs:
+            o.fill_(float("nan"))               # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for mode in range(3):
+            got, want = outs[mode], eager[mode]
+            assert bool(torch.isfinite(got).all()), f"replay {replay} mode {mode}"
+            # atomics may merge in another order: same tolerance as against the oracle
+            assert float((got - want).abs().max()) <= GU.REL_TOL * float(want.abs().max())
+    t.close()
