@@ -111,8 +111,9 @@ int hbcsf_upload(hbcsf_tensor *t, void *device_arena, uint64_t bytes, void *hip_
  * by the output-definition pass instead (HBCSF_TUNE_FUSE_COO).  Slices that span several work units
  * are merged with fp32 atomic adds (Section IV-A), so results can differ between runs in
  * the last bits.  NaN / Inf inputs propagate.  Calls on one handle must not overlap in time when
- * profiling (HBCSF_TUNE_PROFILE) or tracing is on; otherwise the handle is read-only here. * With profiling off the call only launches kernels on hip_stream (no memset, no allocation, no host
- * wait), so it can be recorded into a HIP graph and replayed. */
+ * profiling (HBCSF_TUNE_PROFILE) or tracing is on; otherwise the handle is read-only here.
+ * With profiling off the call only launches kernels on hip_stream (no memset, no allocation, no
+ * host wait), so it can be recorded into a HIP graph and replayed. */
 int hbcsf_mttkrp(const hbcsf_tensor *t, int mode, int rank, const float *const *factors,
                  float *out, void *hip_stream);
 
