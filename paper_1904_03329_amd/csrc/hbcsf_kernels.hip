@@ -541,7 +541,8 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
 // The order-3, R = 32, 32-bit-offset instantiation needs 132 vector registers, four more than fit four
 // wavefronts per SIMD; held to 128 it spills three registers and gains a wavefront per SIMD, which pays on
 // the cache-resident workloads (measured -4.5 % on a 100 M-nonzero tensor whose factors fit the L2).  The
-// 64-bit-offset and order-4 instantiations spill more and lose, so they keep the plain kernel.
+// 64-bit-offset instantiation spills more and loses; order 4 (176 registers, held to 168 for a third wavefront
+// per SIMD) measured no gain; both keep the plain kernel.
 template <int G, int N, int LS, int kSteps>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void csf_group_kernel_occ4(const GroupArgs a) {
   csf_group_body<G, N, LS, kSteps, false>(a);
