@@ -43,7 +43,7 @@ typedef struct hbcsf_tensor hbcsf_tensor; /* opaque, owned by the library, freed
 typedef struct hbcsf_opts {
   uint32_t fiber_threshold;   /* T_f of fbr-split (Section IV-B, VI-B): no fiber segment holds more
                                  than T_f nonzeros.  Cuts fall on multiples of T_f in a group's
-                                 nonzero stream.  8, 16, 32 or 64.  Default 64.                     */
+                                 nonzero stream.  8, 16, 32 or 64.  Default 64 (order 3), 32 (order 4). */
   uint32_t slice_threshold;   /* T_s of slc-split (Section IV-A): nonzeros one wavefront works
                                  through before it merges its partial rows; a slice of n nonzeros
                                  is shared by at most ceil(n/T_s)+1 wavefronts.  0 = sized from
@@ -141,8 +141,8 @@ int hbcsf_host_array(const hbcsf_tensor *t, int mode, int group, int level, int 
                                         keep the last n calls' event sets; 0 = off              */
 #define HBCSF_TUNE_WAVES_PER_CU     2 /* wavefront spans launched per compute unit when T_s is
                                         automatic (default 128)                                 */
-#define HBCSF_TUNE_STEPS            3 /* gathers a lane group keeps in flight: 4 or 8 (default 8;
-                                        4 is only available at rank 32)                         */
+#define HBCSF_TUNE_STEPS            3 /* gathers a lane group keeps in flight: 4 or 8 (default 8 for
+                                        order 3, 4 for order 4; 4 is only available at rank 32)  */
 #define HBCSF_TUNE_KERNEL_MASK      4 /* which kernels hbcsf_mttkrp launches: bit0 define, bit1 COO,
                                         bit2 CSL, bit3 CSF (default 15).  For ablation and profiling
                                         only: with bits cleared the output is incomplete.        */

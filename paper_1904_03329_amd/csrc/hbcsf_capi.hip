@@ -60,7 +60,7 @@ int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint
   }
   hbcsf_opts o{};
   if (opts) o = *opts;
-  if (o.fiber_threshold == 0) o.fiber_threshold = 64;
+  if (o.fiber_threshold == 0) o.fiber_threshold = default_fiber_threshold(order);
   if (!pow2_in(o.fiber_threshold, 8, 64)) return fail(HBCSF_EINVAL, "fiber_threshold must be 8, 16, 32 or 64");
   if (o.mode_order_policy > 2) return fail(HBCSF_EINVAL, "mode_order_policy must be 0, 1 or 2");
   if (o.group_mask > 4) return fail(HBCSF_EINVAL, "group_mask must be 0..4");
@@ -70,6 +70,7 @@ int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint
   t->nnz = nnz;
   t->opts = o;
   t->sliceThreshold = o.slice_threshold;
+  t->steps = default_steps(order);
   for (int m = 0; m < order; ++m) t->dims[m] = dims[m];
   double sq = 0.0;
   for (uint64_t z = 0; z < nnz; ++z) sq += (double)vals[z] * (double)vals[z];

@@ -438,7 +438,7 @@ int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* 
   }
   *o = hbcsf_opts{};
   if (opts) *o = *opts;
-  if (o->fiber_threshold == 0) o->fiber_threshold = 64;
+  if (o->fiber_threshold == 0) o->fiber_threshold = default_fiber_threshold(order);
   const uint32_t ft = o->fiber_threshold;
   if (!(ft == 8 || ft == 16 || ft == 32 || ft == 64)) return fail(HBCSF_EINVAL, "fiber_threshold must be 8, 16, 32 or 64");
   if (o->mode_order_policy > 2) return fail(HBCSF_EINVAL, "mode_order_policy must be 0, 1 or 2");
@@ -704,6 +704,7 @@ int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, con
   t->nnz = nnz;
   t->opts = o;
   t->sliceThreshold = o.slice_threshold;
+  t->steps = default_steps(order);
   for (int m = 0; m < order; ++m) t->dims[m] = dims[m];
   int dev = 0, cu = 0;
   HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
