@@ -109,3 +109,27 @@ def test_fit_equals_the_dense_residual():
     lam = rng.uniform(0.5, 2, size=3)
     want = 1.0 - np.linalg.norm(_dense_model(facs, lam) - x) / np.linalg.norm(x)
     np.testing.assert_allclose(cpd_als.fit(dims, inds, vals, facs, lam), want, rtol=1e-10)
+
+
+def test_planted_mistakes_fail_the_least_squares_pin():
+    """The pin has teeth: plausible wrong updates (the updated mode's own Gram matrix in the Hadamard product, an
+    element-wise reciprocal instead of the pseudo-inverse, the MTTKRP of another mode) do not solve Eq. 2."""
+    rng = np.random.default_rng(6)
+    dims = (6, 5, 4)
+    x = rng.normal(size=dims)
+    inds, vals = _coo_of_dense(x)
+    facs = [rng.uniform(0.1, 1, size=(d, 3)) for d in dims]
+    n = 1
+    kr = _khatri_rao_all_but(facs, n)
+    xn = np.reshape(np.moveaxis(x, n, 0), (dims[n], -1), order="F")
+    want = np.linalg.lstsq(kr, xn.T, rcond=None)[0].T
+    m_n = cpd_als.mttkrp(dims, inds, vals, facs, n)
+    v = (facs[0].T @ facs[0]) * (facs[2].T @ facs[2])
+    np.testing.assert_allclose(m_n @ np.linalg.pinv(v), want, rtol=1e-9, atol=1e-10)       # the correct update
+    wrong = [
+        m_n @ np.linalg.pinv(v * (facs[1].T @ facs[1])),
+        m_n @ (1.0 / v),
+        m_n @ np.linalg.pinv((facs[0].T @ facs[0]) @ (facs[2].T @ facs[2])),               # matrix, not Hadamard, product
+    ]
+    for w in wrong:
+        assert np.max(np.abs(w - want)) > 1e-3 * np.max(np.abs(want))
