@@ -9,7 +9,8 @@ One iteration, in the algorithm's order and notation, for an order-N tensor with
 The first product is the mode-n MTTKRP (Section II-C, Eq. 4), evaluated here per nonzero in fp64 with numpy
 (Eq. 7); ^+ is the Moore-Penrose pseudo-inverse (numpy.linalg.pinv).  Everything is fp64.
 
-Readings (the paper leaves them open): "normalise columns ... and store in lambda" is done once at the end of
+Readings (the paper leaves them open): the "*" between the Gram matrices is the element-wise product (the normal
+equations of Eq. 2), whatever the prose under Eq. 3 calls it; "normalise columns ... and store in lambda" is done once at the end of
 the iteration, as the algorithm lists it; the norm is the 2-norm; lambda_r is the product over the modes of the
 r-th column norms, so that [[lambda; A_1..A_N]] is the same model as the unnormalised factors; a zero column is
 left as it is (norm taken as 1).
