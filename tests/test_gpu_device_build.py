@@ -140,6 +140,21 @@ def test_duplicates_keep_their_input_order():
     assert_same_format(dims, inds, vals).close()
 
 
+def test_empty_tensor():
+    import torch
+
+    dims = (9, 8, 7)
+    empty = [np.zeros(0, dtype=np.uint32) for _ in dims]
+    dev = assert_same_format(dims, empty, np.zeros(0, dtype=np.float32))
+    facs = [torch.ones((d, 8), device="cuda") for d in dims]
+    for mode in range(3):
+        out = torch.full((dims[mode], 8), float("nan"), device="cuda")
+        dev.mttkrp(mode, facs, out)
+        torch.cuda.synchronize()
+        assert float(out.abs().max()) == 0.0
+    dev.close()
+
+
 def test_degenerate_shapes():
     one = (np.array([3], dtype=np.uint32), np.array([0], dtype=np.uint32), np.array([5], dtype=np.uint32))
     assert_same_format((7, 1, 9), one, np.array([2.5], dtype=np.float32)).close()
