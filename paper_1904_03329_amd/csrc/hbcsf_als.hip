@@ -368,8 +368,16 @@ struct hbcsf_als {
   Mat gram[HBCSF_MAX_ORDER];  // Gram matrices of the factors as the last iteration left them
   bool gramsValid = false;
   hipEvent_t ev[HBCSF_MAX_ORDER][5];
-  bool evCreated = false;
+  int eventsCreated = 0;  // events are created in order; this many exist
   float phaseMs[4] = {0, 0, 0, 0};  // MTTKRP, Gram (with its read-back), host algebra, apply: last iteration
+
+  hbcsf_als() = default;
+  hbcsf_als(const hbcsf_als&) = delete;
+  hbcsf_als& operator=(const hbcsf_als&) = delete;
+  ~hbcsf_als() {
+    if (hostS) (void)hipHostFree(hostS);
+    for (int k = 0; k < eventsCreated; ++k) (void)hipEventDestroy(ev[k / 5][k % 5]);
+  }
 };
 
 extern "C" {
@@ -412,15 +420,11 @@ int hbcsf_als_create(const hbcsf_tensor* t, int rank, void* workspace, uint64_t 
   if (e != hipSuccess) return fail_hip(e, "hipHostMalloc");
   a->hostP = (float*)(a->hostS + rr);
   a->hostLambda = a->hostP + HBCSF_MAX_ORDER * rr;
-  for (int m = 0; m < HBCSF_MAX_ORDER; ++m)
-    for (int k = 0; k < 5; ++k) {
-      e = hipEventCreate(&a->ev[m][k]);
-      if (e != hipSuccess) {
-        (void)hipHostFree(a->hostS);
-        return fail_hip(e, "hipEventCreate");
-      }
-    }
-  a->evCreated = true;
+  for (int k = 0; k < HBCSF_MAX_ORDER * 5; ++k) {
+    e = hipEventCreate(&a->ev[k / 5][k % 5]);
+    if (e != hipSuccess) return fail_hip(e, "hipEventCreate");  // the destructor releases what exists
+    a->eventsCreated = k + 1;
+  }
   *out = a.release();
   return HBCSF_OK;
 }
@@ -574,13 +578,6 @@ int hbcsf_als_phase_ms(const hbcsf_als* a, float ms[4]) {
   return HBCSF_OK;
 }
 
-void hbcsf_als_free(hbcsf_als* a) {
-  if (!a) return;
-  if (a->hostS) (void)hipHostFree(a->hostS);
-  if (a->evCreated)
-    for (int m = 0; m < HBCSF_MAX_ORDER; ++m)
-      for (int k = 0; k < 5; ++k) (void)hipEventDestroy(a->ev[m][k]);
-  delete a;
-}
+void hbcsf_als_free(hbcsf_als* a) { delete a; }
 
 }  // extern "C"
