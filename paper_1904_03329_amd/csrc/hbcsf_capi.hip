@@ -312,10 +312,12 @@ int hbcsf_tune(hbcsf_tensor* t, int key, uint64_t value) {
     t->ring.clear();
     t->calls = 0;
     t->ring.resize((size_t)value);
+    size_t made = 0;  // events created so far, in ring order
     for (auto& es : t->ring)
-      for (int i = 0; i < 5; ++i) {
+      for (int i = 0; i < 5; ++i, ++made) {
         hipError_t e = hipEventCreate(&es.ev[i]);
         if (e != hipSuccess) {
+          for (size_t k = 0; k < made; ++k) (void)hipEventDestroy(t->ring[k / 5].ev[k % 5]);
           t->ring.clear();
           return fail_hip(e, "hipEventCreate");
         }
