@@ -31,7 +31,7 @@ KERNELS = ("define", "coo", "csl", "csf")
 # FETCH_SIZE and WRITE_SIZE in two runs of this script, FETCH_SIZE scaled by 2.0 and WRITE_SIZE by
 # 1.0 (what the counters read for a 1 GiB device copy, --calibrate); profiles/counters_cfg5.md
 # holds the readings.  A workload without an entry reports null.
-MEASURED_TRAFFIC = {"cfg5": 2.0 * 5790753.0 * 1024 + 1.0 * 241882.1 * 1024}
+MEASURED_TRAFFIC = {"cfg5": 2.0 * 5791241.5 * 1024 + 1.0 * 241882.1 * 1024}
 
 
 def algorithmic_bytes(st: dict, rank: int, order: int) -> dict:
