@@ -4,7 +4,7 @@
 One step = mode-n MTTKRP for every mode n of one synthetic tensor (output definition, COO-group,
 CSL-group and B-CSF-group kernels per mode), inputs resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--only-headline]
 
 GFLOP/s uses 3*R*nnz floating-point operations per mode (the COO operation count of Section
 III-A), R = 32.  The roofline entry is for the B-CSF-group kernel and prices its algorithmic
@@ -24,14 +24,65 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-FP32_VECTOR_PEAK_GFLOPS = 157300.0  # published plain vector fp32 peak (counts packed FMA on every lane)
+# The published fp32 vector peak (157.3 TFLOP/s) counts a packed two-wide FMA on every lane; this build turns packed
+# fp32 formation off, so the vector ALUs can retire one FMA per lane and cycle: half of the published figure
+# (256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz = 78.6 TFLOP/s).
+FP32_VECTOR_PEAK_GFLOPS = 157300.0 / 2
 KERNELS = ("define", "coo", "csl", "csf")
+OTHER_WORKLOADS = ("cfg3", "cfg4", "cfg2")   # measured after the headline workload, same process
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 
-# HBM-side bytes per B-CSF-kernel launch (mean over the modes) measured with rocprofv3 --pmc
-# FETCH_SIZE and WRITE_SIZE in two runs of this script, FETCH_SIZE scaled by 2.0 and WRITE_SIZE by
-# 1.0 (what the counters read for a 1 GiB device copy, --calibrate); profiles/counters_cfg5.md
-# holds the readings.  A workload without an entry reports null.
-MEASURED_TRAFFIC = {"cfg5": 2.0 * 5791241.5 * 1024 + 1.0 * 241882.1 * 1024}
+
+def measured_traffic(workload: str):
+    """HBM-side bytes per B-CSF-kernel launch (mean over the modes) from profiles/traffic.json, which
+    `bench.py --ingest-counters` writes from two rocprofv3 --pmc runs of this script (FETCH_SIZE, WRITE_SIZE, each
+    scaled by what the same counter reads for a plain copy of known size).  None when the file has no entry."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            entry = json.load(f)["workloads"].get(workload)
+    except (OSError, ValueError, KeyError):
+        return None
+    return None if entry is None else entry["csf_bytes_per_launch"]
+
+
+def ingest_counters(fetch_csv: str, write_csv: str, workload: str, commit: str, log) -> int:
+    """Reads the counter_collection CSVs of `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of
+    `bench.py --workload W --only-headline` and stores, per kernel of the library, the mean KiB per launch and the scaled
+    bytes in profiles/traffic.json under workload W (other workloads' entries are kept)."""
+    import collections
+    import csv
+
+    scale = {"FETCH_SIZE": 2.0, "WRITE_SIZE": 1.0}   # counter reading for a 1 GiB copy: 0.5 GiB read, 1 GiB written
+    per_kernel = collections.defaultdict(dict)
+    for path, counter in ((fetch_csv, "FETCH_SIZE"), (write_csv, "WRITE_SIZE")):
+        acc = collections.defaultdict(list)
+        with open(path) as f:
+            for r in csv.DictReader(f):
+                if r["Counter_Name"] == counter and "hbcsf::" in r["Kernel_Name"]:
+                    acc[r["Kernel_Name"].split("(")[0].replace("void ", "")].append(float(r["Counter_Value"]))
+        for k, v in acc.items():
+            per_kernel[k][counter] = {"kib_per_launch": round(sum(v) / len(v), 1), "launches": len(v)}
+    entry = {"commit": commit, "scale": scale, "kernels": per_kernel, "csf_bytes_per_launch": None,
+             "command": "rocprofv3 --pmc <FETCH_SIZE | WRITE_SIZE> --output-format csv -d <dir> -o t -- python3 bench.py "
+                        f"--workload {workload} --only-headline --no-cpu-baseline --als-iterations 0 --steps 3 --warmup 1"}
+    for k, c in per_kernel.items():
+        if "csf_group_kernel" in k and "FETCH_SIZE" in c and "WRITE_SIZE" in c:
+            entry["csf_kernel"] = k
+            entry["csf_bytes_per_launch"] = round(1024 * (scale["FETCH_SIZE"] * c["FETCH_SIZE"]["kib_per_launch"]
+                                                          + scale["WRITE_SIZE"] * c["WRITE_SIZE"]["kib_per_launch"]))
+    try:
+        with open(TRAFFIC_FILE) as f:
+            doc = json.load(f)
+    except (OSError, ValueError):
+        doc = {"what": "HBM-side traffic per kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch as "
+                       "reported, mean over all launches of the run), written by `python bench.py --ingest-counters`",
+               "workloads": {}}
+    doc["workloads"][workload] = entry
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(doc, f, indent=1, sort_keys=True)
+        f.write("\n")
+    log(f"[bench] {TRAFFIC_FILE}: {workload}: {json.dumps(entry)}")
+    return 0
 
 
 def algorithmic_bytes(st: dict, rank: int, order: int) -> dict:
@@ -217,53 +268,56 @@ def time_als(torch, ht, dfacs, rank, iterations, build_s, dev_build, log):
     return report
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5 (default: the largest, cfg5)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--fiber-threshold", type=int, default=0)
-    ap.add_argument("--slice-threshold", type=int, default=0)
-    ap.add_argument("--mode-order-policy", type=int, default=0)
-    ap.add_argument("--group-mask", type=int, default=0)
-    ap.add_argument("--waves-per-cu", type=int, default=0)
-    ap.add_argument("--kernel-steps", type=int, default=0)
-    ap.add_argument("--als-iterations", type=int, default=3,
-                    help="after the timed MTTKRP steps, time this many CPD-ALS iterations built on the same "
-                         "library (reported under \"als\", not part of `value`); 0 skips them")
-    ap.add_argument("--cu-spread", action="store_true",
-                    help="after the timed steps, trace every wavefront of one more pass and report the "
-                         "per-CU busy-time spread of the CSL and B-CSF kernels (profiling only)")
-    ap.add_argument("--calibrate", action="store_true",
-                    help="time a plain 1 GiB device copy, fill and read instead of the benchmark "
-                         "(also the known-size kernel that scales the rocprofv3 byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        return 2
+def cpu_baseline_of(np, t, facs, rank, order, log):
+    """The oracle as it stands, timed on the host: single thread (the parity reference) on a bounded sample, then
+    the same loop on every host core with atomic adds (oracle/mttkrp_oracle_omp.c).  A reported baseline only."""
+    import oracle  # test infrastructure: used here for the reported CPU baseline only
 
+    sample = min(t.nnz, 30_000_000)
+    si = [x[:sample] for x in t.inds]
+    sv = t.vals[:sample]
+    t0 = time.perf_counter()
+    for m in range(order):
+        oracle.mttkrp(t.dims, si, sv, facs, m)
+    cpu_s = time.perf_counter() - t0
+    base = {
+        "value": round(3.0 * rank * sample * order / cpu_s / 1e9, 3),
+        "unit": "GFLOP/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"first {sample} of {t.nnz} nonzeros (generator order), all {order} modes, {cpu_s:.1f}s",
+    }
+    t0 = time.perf_counter()
+    threads = 1
+    for m in range(order):
+        _, threads = oracle.mttkrp_all_cores(t.dims, si, sv, facs, m)
+    omp_s = time.perf_counter() - t0
+    base["all_cores"] = {
+        "value": round(3.0 * rank * sample * order / omp_s / 1e9, 3),
+        "unit": "GFLOP/s",
+        "cores": threads,
+        "kind": "oracle loop split over the host cores with atomic fp64 adds",
+        "sample": f"the same {sample} nonzeros, all {order} modes, {omp_s:.1f}s",
+    }
+    log(f"[bench] cpu baseline: {base}")
+    return base
+
+
+def measure(name: str, args, headline: bool, log) -> dict:
+    """Generates one workload, builds and uploads its format and times `args.steps` steps (one step = MTTKRP on
+    every mode).  The headline workload also gets the device-side build, the CPD-ALS iterations, the per-CU
+    trace (on request) and the CPU baseline; the others are timed only."""
     import numpy as np
     import torch
 
     import synthgen
     from paper_1904_03329_amd import HbcsfTensor, binding as B
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    torch.cuda.set_device(0)
-    log = lambda *a: print(*a, file=sys.stderr, flush=True)
-    if args.calibrate:
-        return calibrate(torch, log)
-
-    w = synthgen.WORKLOADS[args.workload]
+    w = synthgen.WORKLOADS[name]
     t0 = time.time()
-    t, facs, rank = synthgen.workload(args.workload)
+    t, facs, rank = synthgen.workload(name)
     gen_s = time.time() - t0
-    log(f"[bench] {args.workload}: dims={t.dims} nnz={t.nnz} draws={t.draws} R={rank} generated in {gen_s:.1f}s")
+    log(f"[bench] {name}: dims={t.dims} nnz={t.nnz} draws={t.draws} R={rank} generated in {gen_s:.1f}s")
     t0 = time.time()
     ht = HbcsfTensor(t.dims, t.inds, t.vals, fiber_threshold=args.fiber_threshold,
                      slice_threshold=args.slice_threshold, mode_order_policy=args.mode_order_policy,
@@ -279,10 +333,9 @@ def main() -> int:
         st["rows"] = t.dims[m]
         stats.append(st)
     log(f"[bench] format built in {build_s:.1f}s, uploaded {B.device_bytes(ht.handle) / 1e9:.2f} GB in {upload_s:.1f}s")
-    dev_build = time_device_build(torch, np, B, HbcsfTensor, t, ht, args, log)
+    dev_build = time_device_build(torch, np, B, HbcsfTensor, t, ht, args, log) if headline else None
     dfacs = [torch.from_numpy(f).cuda() for f in facs]
     outs = [torch.empty((t.dims[m], rank), dtype=torch.float32, device="cuda") for m in range(order)]
-    stream = torch.cuda.current_stream()
 
     def step():
         for m in range(order):
@@ -337,7 +390,7 @@ def main() -> int:
             "real_gflops": round(stats[m]["flops_real"] * rank / (tot_ms * 1e-3) / 1e9, 1),
         }
         # the two roofs side by side: time the algorithmic bytes need at the HBM peak, time the multiply-adds really
-        # done need at the vector fp32 peak, and the larger of the two over the measured time
+        # done need at the vector fp32 peak without packed FMA, and the larger of the two over the measured time
         t_hbm = ab["total"] / (HBM_PEAK_GBS * 1e9) * 1e3
         t_alu = stats[m]["flops_real"] * rank / (FP32_VECTOR_PEAK_GFLOPS * 1e9) * 1e3
         gb = gather_bytes(stats[m], rank, order)
@@ -351,15 +404,7 @@ def main() -> int:
             csf_bytes += ab["csf"]
             csf_ms += float(kmean[m][3])
             csf_launches += 1
-        log(f"[bench] mode {m}: {json.dumps(entry)}")
-
-    cu_spread = None
-    if args.cu_spread:
-        cu_spread = trace_cu_spread(torch, np, B, ht, dfacs, outs, order, log)
-
-    als_report = None
-    if args.als_iterations > 0:
-        als_report = time_als(torch, ht, dfacs, rank, args.als_iterations, build_s, dev_build, log)
+        log(f"[bench] {name} mode {m}: {json.dumps(entry)}")
 
     achieved = csf_bytes / (csf_ms * 1e-3) / 1e9 if csf_ms > 0 else 0.0
     roofline = {
@@ -369,65 +414,138 @@ def main() -> int:
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": MEASURED_TRAFFIC.get(args.workload),
+        "traffic": measured_traffic(name),
         "bytes_per_launch": round(csf_bytes / max(csf_launches, 1)),
         "ms_per_launch": round(csf_ms / max(csf_launches, 1), 4),
         "launches_per_step": csf_launches,
     }
+    res = {
+        "workload": f"{name}: order {order}, dims {'x'.join(str(d) for d in t.dims)}, nnz {t.nnz}, "
+                    f"Zipf alphas {list(w.alpha)}, R={rank}",
+        "value": round(value, 1),
+        "ms_per_step": round(ms_per_step, 4),
+        "hbm_gbs_model_all_modes": round(sum(p["model_bytes"] for p in per_mode) / (ms_per_step * 1e-3) / 1e9, 1),
+        "roof_frac_all_modes": round(sum(max(p["t_hbm_ms"], p["t_alu_ms"]) for p in per_mode) / ms_per_step, 4),
+        "fiber_threshold": stats[0]["fiber_threshold"],
+        "order": order,
+        "build_seconds": round(build_s, 2),
+        "upload_seconds": round(upload_s, 2),
+        "generate_seconds": round(gen_s, 2),
+        "device_build": dev_build,
+        "per_mode": per_mode,
+        "roofline": roofline,
+    }
+    if order == 4:
+        res["value_4Rnnz"] = round(value * 4.0 / 3.0, 1)
+    if headline:
+        if args.cu_spread:
+            res["cu_busy_spread"] = trace_cu_spread(torch, np, B, ht, dfacs, outs, order, log)
+        res["als"] = (time_als(torch, ht, dfacs, rank, args.als_iterations, build_s, dev_build, log)
+                      if args.als_iterations > 0 else None)
+    del outs, dfacs
+    ht.close()
+    torch.cuda.empty_cache()
+    if headline:
+        res["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline_of(np, t, facs, rank, order, log)
+    return res
 
-    cpu_baseline = None
-    if not args.no_cpu_baseline:
-        import oracle  # test infrastructure: used here for the reported CPU baseline only
 
-        sample = min(t.nnz, 30_000_000)
-        si = [x[:sample] for x in t.inds]
-        sv = t.vals[:sample]
-        t0 = time.perf_counter()
-        for m in range(order):
-            oracle.mttkrp(t.dims, si, sv, facs, m)
-        cpu_s = time.perf_counter() - t0
-        cpu_baseline = {
-            "value": round(3.0 * rank * sample * order / cpu_s / 1e9, 3),
-            "unit": "GFLOP/s",
-            "cores": 1,
-            "kind": "oracle",
-            "sample": f"first {sample} of {t.nnz} nonzeros (generator order), all {order} modes, {cpu_s:.1f}s",
-        }
-        log(f"[bench] cpu baseline: {cpu_baseline}")
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5: the headline workload (default: the largest, cfg5)")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="do not measure the other workloads (cfg3, cfg4, cfg2) after the headline one")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fiber-threshold", type=int, default=0)
+    ap.add_argument("--slice-threshold", type=int, default=0)
+    ap.add_argument("--mode-order-policy", type=int, default=0)
+    ap.add_argument("--group-mask", type=int, default=0)
+    ap.add_argument("--waves-per-cu", type=int, default=0)
+    ap.add_argument("--kernel-steps", type=int, default=0)
+    ap.add_argument("--als-iterations", type=int, default=3,
+                    help="after the timed MTTKRP steps, time this many CPD-ALS iterations built on the same "
+                         "library (reported under \"als\", not part of `value`); 0 skips them")
+    ap.add_argument("--cu-spread", action="store_true",
+                    help="after the timed steps, trace every wavefront of one more pass and report the "
+                         "per-CU busy-time spread of the CSL and B-CSF kernels (profiling only)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="time a plain 1 GiB device copy, fill and read instead of the benchmark "
+                         "(also the known-size kernel that scales the rocprofv3 byte counters)")
+    ap.add_argument("--ingest-counters", nargs=3, metavar=("FETCH_CSV", "WRITE_CSV", "COMMIT"),
+                    help="no GPU work: read the counter_collection CSVs of two rocprofv3 --pmc runs of this script "
+                         "(FETCH_SIZE, WRITE_SIZE) for --workload and record them in profiles/traffic.json")
+    args = ap.parse_args()
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    if args.ingest_counters:
+        return ingest_counters(args.ingest_counters[0], args.ingest_counters[1], args.workload,
+                               args.ingest_counters[2], log)
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
 
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    if args.calibrate:
+        return calibrate(torch, log)
+
+    head = measure(args.workload, args, True, log)
+    others = {}
+    if not args.only_headline:
+        for name in OTHER_WORKLOADS:
+            if name == args.workload:
+                continue
+            r = measure(name, args, False, log)
+            # the compact form: per-mode detail stays in the log
+            others[name] = {k: r[k] for k in ("workload", "value", "ms_per_step", "hbm_gbs_model_all_modes",
+                                              "roof_frac_all_modes", "fiber_threshold", "roofline")}
+            if "value_4Rnnz" in r:
+                others[name]["value_4Rnnz"] = r["value_4Rnnz"]
+            others[name]["mode_ms"] = [p["ms"] for p in r["per_mode"]]
+            others[name]["mode_hbm_frac"] = [p["hbm_frac"] for p in r["per_mode"]]
+            others[name]["mode_gather_gbs"] = [p["gather_gbs"] for p in r["per_mode"]]
+
+    order = head["order"]
     line = {
         "metric": "sparse MTTKRP GFLOP/s (3*R*nnz per mode, all modes) at rank R=32",
-        "value": round(value, 1),
+        "value": head["value"],
         "unit": "GFLOP/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"{args.workload}: order {order}, dims {'x'.join(str(d) for d in t.dims)}, nnz {t.nnz}, "
-                        f"Zipf alphas {list(w.alpha)}, R={rank}",
-            "fiber_threshold": stats[0]["fiber_threshold"],
+            "workload": head["workload"],
+            "fiber_threshold": head["fiber_threshold"],
             "step": f"MTTKRP on all {order} modes",
-            "hbm_gbs_model_all_modes": round(sum(p["model_bytes"] for p in per_mode) / (ms_per_step * 1e-3) / 1e9, 1),
-            "build_seconds": round(build_s, 2),
-            "device_build": dev_build,
-            "upload_seconds": round(upload_s, 2),
-            "generate_seconds": round(gen_s, 2),
+            "hbm_gbs_model_all_modes": head["hbm_gbs_model_all_modes"],
+            "roof_frac_all_modes": head["roof_frac_all_modes"],
+            "build_seconds": head["build_seconds"],
+            "device_build": head["device_build"],
+            "upload_seconds": head["upload_seconds"],
+            "generate_seconds": head["generate_seconds"],
         },
-        "per_mode": per_mode,
-        "roofline": roofline,
-        "cpu_baseline": cpu_baseline,
-        "als": als_report,
+        "per_mode": head["per_mode"],
+        "roofline": head["roofline"],
+        "cpu_baseline": head["cpu_baseline"],
+        "als": head["als"],
+        "other_workloads": others,
     }
-    if cu_spread is not None:
-        line["cu_busy_spread"] = cu_spread
+    if "cu_busy_spread" in head:
+        line["cu_busy_spread"] = head["cu_busy_spread"]
     print(json.dumps(line), flush=True)
-    ht.close()
     return 0
 
 

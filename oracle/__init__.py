@@ -16,14 +16,18 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "liboracle_mttkrp.so")
+_SO_OMP = os.path.join(_HERE, "liboracle_mttkrp_omp.so")
 _lib = None
+_lib_omp = None
 
 
 def build(force: bool = True) -> str:
-    """Compile the oracle with gcc: -O2, no fast-math, single thread."""
-    src = os.path.join(_HERE, "mttkrp_oracle.c")
-    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(src):
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-shared", "-fPIC", "-o", _SO, src])
+    """Compile the oracle with gcc: -O2, no fast-math, single thread; and, as a library of its own, the same
+    loop on all cores (mttkrp_oracle_omp.c, -fopenmp), which only the benchmark's CPU baseline uses."""
+    for so, name, extra in ((_SO, "mttkrp_oracle.c", []), (_SO_OMP, "mttkrp_oracle_omp.c", ["-fopenmp"])):
+        src = os.path.join(_HERE, name)
+        if force or not os.path.exists(so) or os.path.getmtime(so) < os.path.getmtime(src):
+            subprocess.check_call(["gcc", "-O2", "-std=c99", "-shared", "-fPIC"] + extra + ["-o", so, src])
     return _SO
 
 
@@ -97,3 +101,27 @@ def mttkrp_rows(dims, inds, vals, factors, mode, rows) -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"oracle_mttkrp_rows failed with code {rc}")
     return out
+
+
+def mttkrp_all_cores(dims, inds, vals, factors, mode):
+    """The oracle's loop split over all host cores with atomic fp64 adds (for the benchmark's reported CPU
+    baseline; not the parity reference).  Returns (fp64 [dims[mode], R], threads used)."""
+    global _lib_omp
+    if _lib_omp is None:
+        if not os.path.exists(_SO_OMP):
+            build(force=False)
+        lib = ctypes.CDLL(_SO_OMP)
+        lib.oracle_mttkrp_omp.restype = ctypes.c_int
+        lib.oracle_mttkrp_omp.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
+                                          ctypes.c_void_p, ctypes.POINTER(ctypes.c_int)]
+        _lib_omp = lib
+    order, d, nnz, iptr, vals, rank, fptr, keep = _marshal(dims, inds, vals, factors, mode)
+    out = np.empty((int(dims[mode]), rank), dtype=np.float64)
+    team = ctypes.c_int(0)
+    rc = _lib_omp.oracle_mttkrp_omp(order, d.ctypes.data, nnz, ctypes.cast(iptr, ctypes.c_void_p),
+                                    vals.ctypes.data, rank, ctypes.cast(fptr, ctypes.c_void_p), mode,
+                                    out.ctypes.data, ctypes.byref(team))
+    if rc != 0:
+        raise RuntimeError(f"oracle_mttkrp_omp failed with code {rc}")
+    return out, team.value

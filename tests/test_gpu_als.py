@@ -139,6 +139,22 @@ def test_config2_shape_at_one_tenth(synth):
     _check(t.dims, t.inds, t.vals, facs, rank)
 
 
+def test_factor_matrix_above_4GiB(synth):
+    """A 34 M-row factor matrix at R = 32 is 4.35 GB: the Gram and product kernels then index beyond 2^32 bytes,
+    and the MTTKRPs of the other modes gather from it with 64-bit offsets.  One iteration against the oracle."""
+    with open("/proc/meminfo") as f:
+        avail = [int(l.split()[1]) for l in f if l.startswith("MemAvailable:")][0] / (1 << 20)
+    if avail < 64:
+        pytest.skip(f"the fp64 numpy oracle holds several 8.7 GB matrices: needs about 64 GiB of host memory, "
+                    f"{avail:.0f} GiB available")
+    dims, rank = (34_000_000, 300, 40), 32
+    t = synth.tensor(dims, 2_000_000, (1.05, 1.1, 0.0), seed=900)
+    vals = (0.1 + 0.45 * (t.vals + 1.0)).astype(np.float32)      # positive, as in the other cases
+    facs = [synth.uniform((d, rank), 900 + m, -1.0, 1.0) for m, d in enumerate(dims)]
+    print("als wide", dims, t.nnz, flush=True)
+    _check(dims, t.inds, vals, facs, rank)
+
+
 def test_run_until_the_fit_settles():
     """The outer loop on a noisy low-rank tensor: stops by the tolerance, before the iteration cap, at the fit
     the oracle reaches with the same number of iterations."""

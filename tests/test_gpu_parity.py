@@ -71,6 +71,41 @@ def test_hypersparse_groups(oracle, synth):
     assert stats[0]["group_nnz"][0] > 0 and stats[0]["group_nnz"][1] > 0 and stats[0]["group_nnz"][2] > 0
 
 
+@pytest.mark.parametrize("dims,nnz,alpha", [((34_000_000, 34_000_000, 100), 1_500_000, (1.05, 1.05, 0.0)),
+                                            ((34_000_000, 3000, 60, 20), 1_000_000, (1.05, 1.1, 1.0, 0.8))])
+def test_factor_matrices_above_4GiB(oracle, synth, dims, nnz, alpha):
+    """Factor matrices of 34 M rows x 32 floats exceed 4 GiB, so every kernel runs in its 64-bit-offset
+    instantiation (orders 3 and 4).  Every non-empty output row is compared with the oracle and every other
+    row must be exactly zero."""
+    import torch
+    from paper_1904_03329_amd import HbcsfTensor
+
+    with open("/proc/meminfo") as f:
+        avail = [int(l.split()[1]) for l in f if l.startswith("MemAvailable:")][0] / (1 << 20)
+    if avail < 24:
+        pytest.skip(f"needs about 24 GiB of host memory for the factor matrices, {avail:.0f} GiB available")
+    t = synth.tensor(dims, nnz, alpha, seed=4242)
+    facs = synth.factors(t.dims, 32, seed=4242)
+    print("wide", t.dims, t.nnz, flush=True)
+    ht = HbcsfTensor(t.dims, t.inds, t.vals).to_device()
+    dfacs = [torch.from_numpy(f).cuda() for f in facs]
+    for mode in range(t.order):
+        st = ht.stats(mode)
+        out = torch.full((t.dims[mode], 32), float("nan"), dtype=torch.float32, device="cuda")
+        ht.mttkrp(mode, dfacs, out)
+        torch.cuda.synchronize()
+        rows = np.unique(t.inds[mode])
+        want = oracle.mttkrp_rows(t.dims, t.inds, t.vals, facs, mode, rows)
+        drows = torch.from_numpy(rows.astype(np.int64)).cuda()
+        rel = GU.assert_close(out[drows].cpu().numpy(), want, f"wide order {t.order} mode {mode}")
+        out[drows] = 0.0
+        assert int(torch.count_nonzero(out)) == 0 and bool(torch.isfinite(out).all()), "an empty slice's row is not zero"
+        print(f"wide order {t.order} mode {mode}: {rows.size} non-empty rows, groups {st['group_nnz']}, "
+              f"max|diff|/max|M| = {rel:.2e}", flush=True)
+        del out
+    ht.close()
+
+
 def test_degenerate_shapes(oracle):
     rng = np.random.default_rng(31)
     # one heavy slice only (every partial row merged with atomics), ragged tail

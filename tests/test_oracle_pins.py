@@ -233,3 +233,22 @@ def test_workload_cfg1(oracle, synth):
     for n in range(3):
         want = _unfold(x, n) @ _khatri_rao_all_but(facs, n)
         np.testing.assert_allclose(oracle.mttkrp(t.dims, t.inds, t.vals, facs, n), want, rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("dims", [(60, 40, 30), (30, 12, 9, 7)])
+def test_all_cores_variant_equals_the_oracle(oracle, dims):
+    """The all-cores timing variant (atomic fp64 adds) is the same sum in another order: equal to the
+    single-thread oracle within fp64 rounding, and against the dense definition (Eq. 4) directly."""
+    rng = np.random.default_rng(41 + len(dims))
+    inds, vals = _random_coo(rng, dims, 5000)
+    facs = _factors(rng, dims, 8)
+    x = _dense(dims, inds, vals)
+    for n in range(len(dims)):
+        got, threads = oracle.mttkrp_all_cores(dims, inds, vals, facs, n)
+        assert threads >= 1
+        np.testing.assert_allclose(got, oracle.mttkrp(dims, inds, vals, facs, n), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(got, _unfold(x, n) @ _khatri_rao_all_but(facs, n), rtol=1e-11, atol=1e-12)
+    bad = [a.copy() for a in inds]
+    bad[0][3] = dims[0]
+    with pytest.raises(RuntimeError):
+        oracle.mttkrp_all_cores(dims, bad, vals, facs, 1)
