@@ -15,7 +15,9 @@
  *
  * Every function returns 0 on success or a negative HBCSF_E* code; the text of
  * the last failure on the calling thread is kept for hbcsf_last_error().  No
- * C++ exception crosses this boundary.  "host" / "device" on a pointer says
+ * C++ exception crosses this boundary: every entry point that returns a code
+ * catches whatever its body throws (a failed host allocation becomes
+ * HBCSF_ENOMEM).  "host" / "device" on a pointer says
  * which memory it must point to.  The library never frees caller memory.
  */
 #ifndef HBCSF_H_
@@ -110,8 +112,10 @@ int hbcsf_upload(hbcsf_tensor *t, void *device_arena, uint64_t bytes, void *hip_
  * (Algorithm "HB-CSF-MTTKRP", execute step); for small outputs the COO group's rows are written
  * by the output-definition pass instead (HBCSF_TUNE_FUSE_COO).  Slices that span several work units
  * are merged with fp32 atomic adds (Section IV-A), so results can differ between runs in
- * the last bits.  NaN / Inf inputs propagate.  Calls on one handle must not overlap in time when
- * profiling (HBCSF_TUNE_PROFILE) or tracing is on; otherwise the handle is read-only here.
+ * the last bits.  NaN / Inf inputs propagate.  The handle is const because the representation is
+ * only read; with profiling on (HBCSF_TUNE_PROFILE) the call also records HIP events into the
+ * handle's event ring, which is bookkeeping outside the const promise, so calls on one handle
+ * must not overlap in time while profiling or tracing is on.
  * With profiling off the call only launches kernels on hip_stream (no memset, no allocation, no
  * host wait), so it can be recorded into a HIP graph and replayed. */
 int hbcsf_mttkrp(const hbcsf_tensor *t, int mode, int rank, const float *const *factors,

@@ -10,8 +10,8 @@ The first product is the mode-n MTTKRP (Section II-C, Eq. 4), evaluated here per
 (Eq. 7); ^+ is the Moore-Penrose pseudo-inverse (numpy.linalg.pinv).  Everything is fp64.
 
 Readings (the paper leaves them open): the "*" between the Gram matrices is the element-wise product (the normal
-equations of Eq. 2), whatever the prose under Eq. 3 calls it; "normalise columns ... and store in lambda" is done once at the end of
-the iteration, as the algorithm lists it; the norm is the 2-norm; lambda_r is the product over the modes of the
+equations of Eq. 2), whatever the prose under Eq. 3 calls it; the column normalisation step of Algorithm "CPD-ALS" is applied once, at
+the end of the iteration, where the algorithm lists it; the norm is the 2-norm; lambda_r is the product over the modes of the
 r-th column norms, so that [[lambda; A_1..A_N]] is the same model as the unnormalised factors; a zero column is
 left as it is (norm taken as 1).
 """

@@ -382,7 +382,7 @@ struct hbcsf_als {
 
 extern "C" {
 
-int hbcsf_als_workspace_bytes(const hbcsf_tensor* t, int rank, uint64_t* bytes) {
+int hbcsf_als_workspace_bytes(const hbcsf_tensor* t, int rank, uint64_t* bytes) try {
   if (!t || !bytes) return fail(HBCSF_EINVAL, "null argument");
   if (!rank_ok(rank)) return fail(HBCSF_EINVAL, "rank must be 8, 16, 32, 64 or 128");
   uint64_t maxDim = 0;
@@ -390,10 +390,10 @@ int hbcsf_als_workspace_bytes(const hbcsf_tensor* t, int rank, uint64_t* bytes) 
   *bytes = round256(maxDim * (uint64_t)rank * 4) + round256((uint64_t)rank * rank * 8) +
            round256((uint64_t)rank * rank * 4);
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
 int hbcsf_als_create(const hbcsf_tensor* t, int rank, void* workspace, uint64_t workspace_bytes,
-                     hbcsf_als** out) {
+                     hbcsf_als** out) try {
   if (!out) return fail(HBCSF_EINVAL, "out is null");
   *out = nullptr;
   if (!t || !workspace) return fail(HBCSF_EINVAL, "null argument");
@@ -427,10 +427,10 @@ int hbcsf_als_create(const hbcsf_tensor* t, int rank, void* workspace, uint64_t 
   }
   *out = a.release();
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
 int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int flags, double* fit,
-                        void* hip_stream) {
+                        void* hip_stream) try {
   if (!a || !factors) return fail(HBCSF_EINVAL, "null argument");
   const hbcsf_tensor* t = a->t;
   const int order = t->order, R = a->rank;
@@ -541,10 +541,10 @@ int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int 
       if (hipEventElapsedTime(&ms, a->ev[n][k], a->ev[n][k + 1]) == hipSuccess) a->phaseMs[k] += ms;
     }
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
 int hbcsf_als_run(hbcsf_als* a, float* const* factors, float* lambda, int max_iterations, double tolerance,
-                  int* iterations_done, double* fit, void* hip_stream) {
+                  int* iterations_done, double* fit, void* hip_stream) try {
   if (!a || !factors) return fail(HBCSF_EINVAL, "null argument");
   if (max_iterations < 1) return fail(HBCSF_EINVAL, "max_iterations must be at least 1");
   double prev = 0.0, cur = 0.0;
@@ -561,22 +561,22 @@ int hbcsf_als_run(hbcsf_als* a, float* const* factors, float* lambda, int max_it
   if (iterations_done) *iterations_done = it;
   if (fit) *fit = cur;
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
-int hbcsf_sym_pinv(const double* v, int n, double* out) {
+int hbcsf_sym_pinv(const double* v, int n, double* out) try {
   if (!v || !out) return fail(HBCSF_EINVAL, "null argument");
   if (n < 1 || n > 128) return fail(HBCSF_EINVAL, "n must be in 1 .. 128");
   const Mat in(v, v + (size_t)n * n);
   const Mat r = pinv_of_gram_product(in, n);
   std::memcpy(out, r.data(), (size_t)n * n * sizeof(double));
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
-int hbcsf_als_phase_ms(const hbcsf_als* a, float ms[4]) {
+int hbcsf_als_phase_ms(const hbcsf_als* a, float ms[4]) try {
   if (!a || !ms) return fail(HBCSF_EINVAL, "null argument");
   for (int k = 0; k < 4; ++k) ms[k] = a->phaseMs[k];
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
 void hbcsf_als_free(hbcsf_als* a) { delete a; }
 

@@ -34,6 +34,25 @@ int fail_hip(hipError_t e, const char* what) {
   return HBCSF_EHIP;
 }
 
+int fail_exception() noexcept {
+  int code = HBCSF_EINVAL;
+  try {
+    try {
+      throw;
+    } catch (const std::bad_alloc&) {
+      code = HBCSF_ENOMEM;
+      g_err = "out of host memory";
+    } catch (const std::exception& e) {
+      g_err = std::string("unexpected C++ exception: ") + e.what();
+    } catch (...) {
+      g_err = "unexpected C++ exception";
+    }
+  } catch (...) {
+    g_err.clear();  // even the message could not be stored
+  }
+  return code;
+}
+
 }  // namespace hbcsf
 
 namespace {
@@ -47,7 +66,7 @@ uint32_t round_up8(uint64_t v) { return (uint32_t)((v + 7) / 8 * 8); }
 extern "C" {
 
 int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* const* inds,
-                       const float* vals, const hbcsf_opts* opts, hbcsf_tensor** out) {
+                       const float* vals, const hbcsf_opts* opts, hbcsf_tensor** out) try {
   if (!out) return fail(HBCSF_EINVAL, "out is null");
   *out = nullptr;
   if (order != 3 && order != 4) return fail(HBCSF_EINVAL, "order must be 3 or 4");
@@ -88,15 +107,15 @@ int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint
   t->arenaBytes = off;
   *out = t.release();
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
-int hbcsf_device_bytes(const hbcsf_tensor* t, uint64_t* bytes) {
+int hbcsf_device_bytes(const hbcsf_tensor* t, uint64_t* bytes) try {
   if (!t || !bytes) return fail(HBCSF_EINVAL, "null argument");
   *bytes = t->arenaBytes;
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
-int hbcsf_upload(hbcsf_tensor* t, void* device_arena, uint64_t bytes, void* hip_stream) {
+int hbcsf_upload(hbcsf_tensor* t, void* device_arena, uint64_t bytes, void* hip_stream) try {
   if (!t || !device_arena) return fail(HBCSF_EINVAL, "null argument");
   for (int m = 0; m < t->order; ++m)
     if (!t->modes[m]->blob) return fail(HBCSF_ESTATE, "the format was built on the device: it is already resident");
@@ -120,10 +139,10 @@ int hbcsf_upload(hbcsf_tensor* t, void* device_arena, uint64_t bytes, void* hip_
   t->arena = (uint8_t*)device_arena;
   t->uploaded = true;
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
 int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* factors, float* out,
-                 void* hip_stream) {
+                 void* hip_stream) try {
   if (!t || !factors || !out) return fail(HBCSF_EINVAL, "null argument");
   if (mode < 0 || mode >= t->order) return fail(HBCSF_EINVAL, "mode out of range");
   if (!(rank == 8 || rank == 16 || rank == 32 || rank == 64 || rank == 128))
@@ -263,17 +282,17 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
     ++t->calls;
   }
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
-int hbcsf_get_stats(const hbcsf_tensor* t, int mode, hbcsf_stats* stats) {
+int hbcsf_get_stats(const hbcsf_tensor* t, int mode, hbcsf_stats* stats) try {
   if (!t || !stats) return fail(HBCSF_EINVAL, "null argument");
   if (mode < 0 || mode >= t->order) return fail(HBCSF_EINVAL, "mode out of range");
   *stats = t->modes[mode]->stats;
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
 int hbcsf_host_array(const hbcsf_tensor* t, int mode, int group, int level, int array_id,
-                     const void** ptr, uint64_t* count) {
+                     const void** ptr, uint64_t* count) try {
   if (!t || !ptr || !count) return fail(HBCSF_EINVAL, "null argument");
   if (mode < 0 || mode >= t->order) return fail(HBCSF_EINVAL, "mode out of range");
   const ModeFormat& f = *t->modes[mode];
@@ -297,9 +316,9 @@ int hbcsf_host_array(const hbcsf_tensor* t, int mode, int group, int level, int 
   *ptr = f.blob + r->off;
   *count = r->count;
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
-int hbcsf_tune(hbcsf_tensor* t, int key, uint64_t value) {
+int hbcsf_tune(hbcsf_tensor* t, int key, uint64_t value) try {
   if (!t) return fail(HBCSF_EINVAL, "null argument");
   if (key == HBCSF_TUNE_SLICE_THRESHOLD) {
     t->sliceThreshold = value;
@@ -364,9 +383,9 @@ int hbcsf_tune(hbcsf_tensor* t, int key, uint64_t value) {
     return HBCSF_OK;
   }
   return fail(HBCSF_EINVAL, "unknown tuning key");
-}
+} HBCSF_CATCH_ALL
 
-int hbcsf_kernel_ms(hbcsf_tensor* t, uint32_t calls_back, float ms[4]) {
+int hbcsf_kernel_ms(hbcsf_tensor* t, uint32_t calls_back, float ms[4]) try {
   if (!t || !ms) return fail(HBCSF_EINVAL, "null argument");
   if (t->ring.empty() || calls_back >= t->ring.size() || calls_back >= t->calls)
     return fail(HBCSF_ESTATE, "no profiled hbcsf_mttkrp call that far back");
@@ -381,10 +400,10 @@ int hbcsf_kernel_ms(hbcsf_tensor* t, uint32_t calls_back, float ms[4]) {
     if (e != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
   }
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
 int hbcsf_probe_row_gather(const uint32_t* idx, uint64_t n, const float* table, uint64_t table_rows,
-                           float* sink, void* hip_stream, uint64_t* rows_gathered) {
+                           float* sink, void* hip_stream, uint64_t* rows_gathered) try {
   if (!idx || !table || !sink || !rows_gathered) return fail(HBCSF_EINVAL, "null argument");
   if (table_rows == 0 || n < 64 * 1024) return fail(HBCSF_EINVAL, "need a table and at least 65536 indices");
   int dev = 0, cu = 0;
@@ -404,7 +423,7 @@ int hbcsf_probe_row_gather(const uint32_t* idx, uint64_t n, const float* table, 
   if (e != hipSuccess) return fail_hip(e, "launch of the gather probe");
   *rows_gathered = waves * perWave;
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
 void hbcsf_free(hbcsf_tensor* t) {
   if (!t) return;

@@ -657,7 +657,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
 extern "C" {
 
 int hbcsf_device_build_bytes(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* opts,
-                             uint64_t* arena_bytes, uint64_t* workspace_bytes) {
+                             uint64_t* arena_bytes, uint64_t* workspace_bytes) try {
   hbcsf_opts o;
   int totalBits = 0;
   const int rc = check_args(order, dims, nnz, opts, &o, &totalBits);
@@ -672,11 +672,11 @@ int hbcsf_device_build_bytes(int order, const uint64_t* dims, uint64_t nnz, cons
   *workspace_bytes = w.total;
   *arena_bytes = arena_bound(order, dims, nnz, o.fiber_threshold);
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
 int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* const* inds,
                               const float* vals, const hbcsf_opts* opts, void* device_arena, uint64_t arena_bytes,
-                              void* workspace, uint64_t workspace_bytes, void* hip_stream, hbcsf_tensor** out) {
+                              void* workspace, uint64_t workspace_bytes, void* hip_stream, hbcsf_tensor** out) try {
   if (!out) return fail(HBCSF_EINVAL, "out is null");
   *out = nullptr;
   hbcsf_opts o;
@@ -736,9 +736,9 @@ int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, con
   t->uploaded = true;
   *out = t.release();
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
-int hbcsf_relocate(hbcsf_tensor* t, void* new_arena, uint64_t bytes, void* hip_stream) {
+int hbcsf_relocate(hbcsf_tensor* t, void* new_arena, uint64_t bytes, void* hip_stream) try {
   if (!t || !new_arena) return fail(HBCSF_EINVAL, "null argument");
   if (!t->uploaded || !t->arena) return fail(HBCSF_ESTATE, "the tensor has no device copy");
   if (bytes < t->arenaBytes) return fail(HBCSF_ENOMEM, "the new arena is smaller than hbcsf_device_bytes");
@@ -748,9 +748,9 @@ int hbcsf_relocate(hbcsf_tensor* t, void* new_arena, uint64_t bytes, void* hip_s
   HIP_TRY(hipStreamSynchronize(st), "hipStreamSynchronize");
   t->arena = (uint8_t*)new_arena;
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
-int hbcsf_download(hbcsf_tensor* t, void* hip_stream) {
+int hbcsf_download(hbcsf_tensor* t, void* hip_stream) try {
   if (!t) return fail(HBCSF_EINVAL, "null argument");
   if (!t->uploaded || !t->arena) return fail(HBCSF_ESTATE, "the tensor has no device copy");
   hipStream_t st = (hipStream_t)hip_stream;
@@ -764,6 +764,6 @@ int hbcsf_download(hbcsf_tensor* t, void* hip_stream) {
   }
   HIP_TRY(hipStreamSynchronize(st), "hipStreamSynchronize");
   return HBCSF_OK;
-}
+} HBCSF_CATCH_ALL
 
 }  // extern "C"

@@ -39,13 +39,16 @@ void radix_sort_pairs(Key*& k, uint32_t*& v, Key*& k2, uint32_t*& v2, size_t n, 
     const uint32_t* srcv = v;
     Key* dst = k2;
     uint32_t* dstv = v2;
-#pragma omp parallel num_threads(nt)
+    // The data is cut into nt chunks and the loops run over chunk numbers, so the result does not depend on how
+    // many threads the runtime really grants.
+#pragma omp parallel
     {
-      const int t = omp_get_thread_num();
-      const size_t lo = n * (size_t)t / nt, hi = n * (size_t)(t + 1) / nt;
-      size_t* h = &hist[(size_t)t * buckets];
-      for (size_t i = lo; i < hi; ++i) ++h[(size_t)(src[i] >> shift) & (buckets - 1)];
-#pragma omp barrier
+#pragma omp for schedule(static, 1)
+      for (int c = 0; c < nt; ++c) {
+        const size_t lo = n * (size_t)c / nt, hi = n * (size_t)(c + 1) / nt;
+        size_t* h = &hist[(size_t)c * buckets];
+        for (size_t i = lo; i < hi; ++i) ++h[(size_t)(src[i] >> shift) & (buckets - 1)];
+      }
 #pragma omp single
       {
         size_t run = 0;
@@ -56,10 +59,15 @@ void radix_sort_pairs(Key*& k, uint32_t*& v, Key*& k2, uint32_t*& v2, size_t n, 
             run += c;
           }
       }
-      for (size_t i = lo; i < hi; ++i) {
-        const size_t at = h[(size_t)(src[i] >> shift) & (buckets - 1)]++;
-        dst[at] = src[i];
-        dstv[at] = srcv[i];
+#pragma omp for schedule(static, 1)
+      for (int c = 0; c < nt; ++c) {
+        const size_t lo = n * (size_t)c / nt, hi = n * (size_t)(c + 1) / nt;
+        size_t* h = &hist[(size_t)c * buckets];
+        for (size_t i = lo; i < hi; ++i) {
+          const size_t at = h[(size_t)(src[i] >> shift) & (buckets - 1)]++;
+          dst[at] = src[i];
+          dstv[at] = srcv[i];
+        }
       }
     }
     std::swap(k, k2);
@@ -139,9 +147,8 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   // ---- slices ----
   const int nt = omp_get_max_threads();
   std::vector<uint64_t> tcount(nt + 1, 0);
-#pragma omp parallel num_threads(nt)
-  {
-    const int t = omp_get_thread_num();
+#pragma omp parallel for schedule(static, 1)
+  for (int t = 0; t < nt; ++t) {  // chunk numbers, not thread numbers: any team size gives the same result
     const size_t lo = M * (size_t)t / nt, hi = M * (size_t)(t + 1) / nt;
     uint64_t c = 0;
     for (size_t p = lo; p < hi; ++p) c += fresh(0, p);
@@ -150,9 +157,8 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   for (int t = 0; t < nt; ++t) tcount[t + 1] += tcount[t];
   const uint64_t S = tcount[nt];
   std::vector<uint32_t> sStart(S + 1);
-#pragma omp parallel num_threads(nt)
-  {
-    const int t = omp_get_thread_num();
+#pragma omp parallel for schedule(static, 1)
+  for (int t = 0; t < nt; ++t) {
     const size_t lo = M * (size_t)t / nt, hi = M * (size_t)(t + 1) / nt;
     uint64_t at = tcount[t];
     for (size_t p = lo; p < hi; ++p)

@@ -769,20 +769,18 @@ template <int G, int N, int LS, int S, bool WIDE>
 hipError_t launch_one(int kind, const GroupArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
   auto csf = (G == 8 && N == 3 && S == 8 && !WIDE) ? csf_group_kernel_occ4<G, N, LS, S> : csf_group_kernel<G, N, LS, S, WIDE>;
   auto csl = csl_group_kernel<G, N, LS, S, WIDE>;
-  static int perCu[2] = {0, 0};  // resident blocks per CU, asked once per kernel
   const int which = kind == kCsfKernel ? 1 : 0;
-  if (perCu[which] == 0) {
-    int n = 0;
-    const hipError_t e = which ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, csf, (int)block.x, lds)
-                               : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, csl, (int)block.x, lds);
-    if (e != hipSuccess) return e;
-    perCu[which] = n > 0 ? n : 1;
-  }
   const uint32_t wpb = block.x >> 6;
   const uint64_t need = ((uint64_t)a.nSpans + wpb - 1) / wpb;
   uint64_t blocks = need;
   if (a.persistent) {
-    blocks = (uint64_t)grid.x * (uint64_t)perCu[which];
+    // resident blocks per CU of this kernel on the current device (asked per launch: the persistent launch is a
+    // tuning variant, and a cached answer would be wrong for another device of the process)
+    int n = 0;
+    const hipError_t e = which ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, csf, (int)block.x, lds)
+                               : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, csl, (int)block.x, lds);
+    if (e != hipSuccess) return e;
+    blocks = (uint64_t)grid.x * (uint64_t)(n > 0 ? n : 1);
     if (blocks > need) blocks = need;
   }
   blocks = (blocks + 7) / 8 * 8;

@@ -46,5 +46,12 @@ namespace hbcsf {
 // Records the message hbcsf_last_error returns on this thread and passes the code through.
 int fail(int code, const std::string& msg);
 int fail_hip(hipError_t e, const char* what);
+// For the handler of an entry point's function-try-block: turns the exception in flight into an error code
+// (std::bad_alloc -> HBCSF_ENOMEM, anything else -> HBCSF_EINVAL with its text) and never throws itself.
+int fail_exception() noexcept;
 
 }  // namespace hbcsf
+
+// Every entry point that returns an error code is a function-try-block closed by this handler, so that no C++
+// exception (a failed allocation in a container, above all) crosses the C boundary.
+#define HBCSF_CATCH_ALL catch (...) { return hbcsf::fail_exception(); }

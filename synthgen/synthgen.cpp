@@ -134,13 +134,15 @@ void radix_sort_u64(std::vector<uint64_t>& a) {
   uint64_t* dst = b.data();
   for (int shift = 0; shift < 64; shift += kBits) {
     std::fill(hist.begin(), hist.end(), 0);
-#pragma omp parallel num_threads(nt)
+    // chunk numbers, not thread numbers, index the histograms: any team size gives the same result
+#pragma omp parallel
     {
-      const int t = omp_get_thread_num();
-      const size_t lo = n * t / nt, hi = n * (t + 1) / nt;
-      size_t* h = &hist[(size_t)t * kBuckets];
-      for (size_t i = lo; i < hi; ++i) ++h[(src[i] >> shift) & (kBuckets - 1)];
-#pragma omp barrier
+#pragma omp for schedule(static, 1)
+      for (int c = 0; c < nt; ++c) {
+        const size_t lo = n * c / nt, hi = n * (c + 1) / nt;
+        size_t* h = &hist[(size_t)c * kBuckets];
+        for (size_t i = lo; i < hi; ++i) ++h[(src[i] >> shift) & (kBuckets - 1)];
+      }
 #pragma omp single
       {
         size_t run = 0;
@@ -151,7 +153,12 @@ void radix_sort_u64(std::vector<uint64_t>& a) {
             run += c;
           }
       }
-      for (size_t i = lo; i < hi; ++i) dst[h[(src[i] >> shift) & (kBuckets - 1)]++] = src[i];
+#pragma omp for schedule(static, 1)
+      for (int c = 0; c < nt; ++c) {
+        const size_t lo = n * c / nt, hi = n * (c + 1) / nt;
+        size_t* h = &hist[(size_t)c * kBuckets];
+        for (size_t i = lo; i < hi; ++i) dst[h[(src[i] >> shift) & (kBuckets - 1)]++] = src[i];
+      }
     }
     std::swap(src, dst);
   }
