@@ -228,8 +228,26 @@ typedef struct hbcsf_als hbcsf_als;
                                   hbcsf_als_iteration left them, so their Gram matrices need not
                                   be recomputed (saves order-1 passes over the factors)           */
 
+/* Gram matrix of a tall factor matrix, S = A^T A: the rank x rank matrices whose Hadamard product
+ * the mode update of Eq. 3 inverts.  Asynchronous on hip_stream.
+ *   a          device [rows][rank] fp32 row-major, 16-byte aligned (rows may be 0: S is all zeros).
+ *   rank       8, 16, 32, 64 or 128.
+ *   workspace  device, 256-byte aligned: scratch for per-workgroup partial sums (one rank x rank fp64
+ *              slot per workgroup).  hbcsf_gram_workspace_bytes gives the size that lets every launch
+ *              use its full grid; a smaller buffer (at least rank*rank*8 bytes) is legal and only
+ *              lowers the number of workgroups.  Contents on entry are irrelevant; two calls that
+ *              overlap in time must not share a workspace.
+ *   s          device [rank][rank] fp64, 8-byte aligned, overwritten.
+ * Products are formed in fp32 (matrix instructions at rank 32) and summed in fp64; the partial sums
+ * are added in a fixed order, so equal inputs give equal bits.  Errors: EINVAL, ENOMEM (workspace
+ * smaller than one slot), EHIP. */
+int hbcsf_gram_workspace_bytes(int rank, uint64_t *bytes);
+int hbcsf_gram(const float *a, uint64_t rows, int rank, void *workspace, uint64_t workspace_bytes,
+               double *s, void *hip_stream);
+
 /* Device workspace an ALS state needs for this tensor and rank: one [max dim][rank] fp32 matrix
- * for the MTTKRP result plus two rank x rank matrices. */
+ * for the MTTKRP result, two rank x rank matrices and the Gram computation's scratch
+ * (hbcsf_gram_workspace_bytes). */
 int hbcsf_als_workspace_bytes(const hbcsf_tensor *t, int rank, uint64_t *bytes);
 
 /* Creates an ALS state for an uploaded tensor.  workspace: device memory, 256-byte aligned, at

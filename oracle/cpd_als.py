@@ -32,6 +32,12 @@ def mttkrp(dims, inds, vals, factors, mode):
     return out
 
 
+def gram(a):
+    """fp64 Gram matrix A^T A of a factor matrix: the R x R matrices whose Hadamard product Eq. 3 inverts."""
+    a = np.asarray(a, dtype=np.float64)
+    return a.T @ a
+
+
 def als_iteration(dims, inds, vals, factors):
     """One iteration of Algorithm "CPD-ALS".  factors: list of [dims[m], R] arrays (any float dtype).
     Returns (new fp64 factors with unit-norm columns, lambda)."""

@@ -30,17 +30,21 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kGramFlush = 8;  // 16-row steps between two flushes of the fp32 partial sums into fp64
+constexpr int kGramFlush = 4;  // 32-row steps between two flushes of the fp32 partial sums into fp64
 
 // ---------------------------------------------------------------------------------------------------
-// R = 32: S += A^T A with the 32x32x2 fp32 matrix instruction.  One instruction consumes two rows of A:
-// lane (h = lane / 32, c = lane % 32) supplies A[row 2u + h][c] as both operands, since the left operand
-// is the transpose of the right one.  A wavefront walks a contiguous chunk of rows, eight coalesced
-// 256-byte loads in flight; partial sums leave fp32 every 128 rows.
+// Gram matrix S = A^T A of a tall matrix in two steps, without atomics and therefore with the same bits on
+// every run: each block writes the partial sums of its rows (all R x R entries, zeros included) to its own
+// slot of a scratch buffer, and a second kernel adds the slots in block order.
+//
+// R = 32: the 32x32x2 fp32 matrix instruction.  One instruction consumes two rows of A: lane
+// (h = lane / 32, c = lane % 32) supplies A[row 2u + h][c] as both operands, since the left operand is the
+// transpose of the right one.  A wavefront walks a contiguous chunk of rows, sixteen coalesced 256-byte
+// loads in flight; partial sums leave fp32 every 128 rows.
 // Accumulator register v of a lane holds entry (8 (v / 4) + 4 h + v % 4, c).
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void gram32_kernel(const float* __restrict__ a, uint64_t rows,
-                                                     uint64_t rowsPerWave, double* __restrict__ s) {
+__global__ __launch_bounds__(256) void gram32_partial_kernel(const float* __restrict__ a, uint64_t rows,
+                                                             uint64_t rowsPerWave, double* __restrict__ partial) {
   __shared__ double red[4][1024];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -55,15 +59,15 @@ __global__ __launch_bounds__(256) void gram32_kernel(const float* __restrict__ a
     f32x16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    for (int it = 0; it < kGramFlush && r0 < r1; ++it, r0 += 16) {
-      float x[8];
+    for (int it = 0; it < kGramFlush && r0 < r1; ++it, r0 += 32) {
+      float x[16];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < 16; ++u) {
         const uint64_t r = r0 + 2 * u + h;
         x[u] = (r < r1) ? __builtin_nontemporal_load(a + r * 32 + c) : 0.f;
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[u], x[u], acc, 0, 0, 0);
+      for (int u = 0; u < 16; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[u], x[u], acc, 0, 0, 0);
     }
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc64[v] += (double)acc[v];
@@ -71,9 +75,27 @@ __global__ __launch_bounds__(256) void gram32_kernel(const float* __restrict__ a
 #pragma unroll
   for (int v = 0; v < 16; ++v) red[wave][(8 * (v / 4) + 4 * h + (v % 4)) * 32 + c] = acc64[v];
   __syncthreads();
-  for (int e = threadIdx.x; e < 1024; e += 256) {
-    const double t = red[0][e] + red[1][e] + red[2][e] + red[3][e];
-    if (t != 0.0) atomicAdd(s + e, t);
+  double* mine = partial + (size_t)blockIdx.x * 1024;
+  for (int e = threadIdx.x; e < 1024; e += 256) mine[e] = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+}
+
+// s[e] = sum over the blocks' slots, in block order.  64 entries x 16 interleaved block subsets per workgroup;
+// the 16 subset sums are added in a fixed order.
+__global__ __launch_bounds__(1024) void gram_reduce_kernel(const double* __restrict__ partial, uint32_t nSlots,
+                                                           uint32_t rr, double* __restrict__ s) {
+  __shared__ double part[16][64];
+  const int el = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const uint32_t e = blockIdx.x * 64u + (uint32_t)el;
+  double t = 0.0;
+  if (e < rr)
+    for (uint32_t b = (uint32_t)q; b < nSlots; b += 16) t += partial[(size_t)b * rr + e];
+  part[q][el] = t;
+  __syncthreads();
+  if (q == 0 && e < rr) {
+    double sum = 0.0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) sum += part[k][el];
+    s[e] = sum;
   }
 }
 
@@ -125,8 +147,8 @@ __global__ __launch_bounds__(256) void apply32_kernel(const float* __restrict__ 
 // Other ranks: plain vector-ALU kernels (correct for any R in the supported list, not tuned).
 // ---------------------------------------------------------------------------------------------------
 template <int R>
-__global__ __launch_bounds__(256) void gram_generic_kernel(const float* __restrict__ a, uint64_t rows,
-                                                           uint64_t rowsPerBlock, double* __restrict__ s) {
+__global__ __launch_bounds__(256) void gram_generic_partial_kernel(const float* __restrict__ a, uint64_t rows,
+                                                                   uint64_t rowsPerBlock, double* __restrict__ partial) {
   constexpr int kTile = 32;                                   // rows staged per step
   constexpr int kPer = (R * R + 255) / 256;                   // entries of S per thread
   __shared__ float tile[kTile][R + 1];
@@ -157,7 +179,7 @@ __global__ __launch_bounds__(256) void gram_generic_kernel(const float* __restri
 #pragma unroll
   for (int e = 0; e < kPer; ++e) {
     const int id = threadIdx.x + 256 * e;
-    if (id < R * R && acc[e] != 0.0) atomicAdd(s + id, acc[e]);
+    if (id < R * R) partial[(size_t)blockIdx.x * (R * R) + id] = acc[e];
   }
 }
 
@@ -176,34 +198,47 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const float* __restr
   }
 }
 
-__global__ void fill_zero_kernel(double* p, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0.0;
+// Scratch of the Gram computation: one R x R fp64 slot per block.  At most kGramSlotsMax blocks, fewer when the
+// scratch buffer is smaller; any number of blocks >= 1 gives the same sum up to fp64 rounding.
+constexpr uint32_t kGramSlotsMax = 1024;
+constexpr uint64_t kGramWorkspaceCap = 32ull << 20;   // hbcsf_gram_workspace_bytes never asks for more
+
+uint32_t gram_slots_for(int rank, uint64_t scratchBytes) {
+  const uint64_t fit = scratchBytes / ((uint64_t)rank * rank * 8);
+  return (uint32_t)(fit < kGramSlotsMax ? fit : kGramSlotsMax);
 }
 
-void launch_gram(const float* a, uint64_t rows, int rank, double* s, int numCU, hipStream_t st) {
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((rank * rank + 255) / 256), dim3(256), 0, st, s, rank * rank);
-  if (rows == 0) return;
-  if (rank == 32) {
+// s (device, [R][R] fp64) = a^T a; scratch holds `slots` R x R fp64 partial sums (slots >= 1).  Nothing has to be
+// cleared between calls: every launched block writes its whole slot, and only the launched blocks' slots are read.
+void launch_gram(const float* a, uint64_t rows, int rank, double* scratch, uint32_t slots, double* s, int numCU,
+                 hipStream_t st) {
+  const uint32_t rr = (uint32_t)(rank * rank);
+  uint32_t used = 0;
+  if (rows > 0 && rank == 32) {
     // enough wavefronts to cover the memory latency, long enough chunks to amortise the final reduction
-    uint64_t waves = (uint64_t)numCU * 32;
+    uint64_t waves = (uint64_t)numCU * 16;
+    if (waves > (uint64_t)slots * 4) waves = (uint64_t)slots * 4;
     uint64_t per = (rows + waves - 1) / waves;
-    per = (per + 15) / 16 * 16;
+    per = (per + 31) / 32 * 32;
     if (per < 256) per = 256;
     const uint64_t nWaves = (rows + per - 1) / per;
-    hipLaunchKernelGGL(gram32_kernel, dim3((unsigned)((nWaves + 3) / 4)), dim3(256), 0, st, a, rows, per, s);
-    return;
+    used = (uint32_t)((nWaves + 3) / 4);
+    hipLaunchKernelGGL(gram32_partial_kernel, dim3(used), dim3(256), 0, st, a, rows, per, scratch);
+  } else if (rows > 0) {
+    uint64_t blocks = (uint64_t)numCU * 8;
+    if (blocks > slots) blocks = slots;
+    uint64_t per = (rows + blocks - 1) / blocks;
+    per = (per + 31) / 32 * 32;
+    used = (uint32_t)((rows + per - 1) / per);
+    switch (rank) {
+      case 8: hipLaunchKernelGGL(gram_generic_partial_kernel<8>, dim3(used), dim3(256), 0, st, a, rows, per, scratch); break;
+      case 16: hipLaunchKernelGGL(gram_generic_partial_kernel<16>, dim3(used), dim3(256), 0, st, a, rows, per, scratch); break;
+      case 64: hipLaunchKernelGGL(gram_generic_partial_kernel<64>, dim3(used), dim3(256), 0, st, a, rows, per, scratch); break;
+      default: hipLaunchKernelGGL(gram_generic_partial_kernel<128>, dim3(used), dim3(256), 0, st, a, rows, per, scratch); break;
+    }
   }
-  uint64_t blocks = (uint64_t)numCU * 8;
-  uint64_t per = (rows + blocks - 1) / blocks;
-  per = (per + 31) / 32 * 32;
-  const unsigned grid = (unsigned)((rows + per - 1) / per);
-  switch (rank) {
-    case 8: hipLaunchKernelGGL(gram_generic_kernel<8>, dim3(grid), dim3(256), 0, st, a, rows, per, s); break;
-    case 16: hipLaunchKernelGGL(gram_generic_kernel<16>, dim3(grid), dim3(256), 0, st, a, rows, per, s); break;
-    case 64: hipLaunchKernelGGL(gram_generic_kernel<64>, dim3(grid), dim3(256), 0, st, a, rows, per, s); break;
-    default: hipLaunchKernelGGL(gram_generic_kernel<128>, dim3(grid), dim3(256), 0, st, a, rows, per, s); break;
-  }
+  // with no rows no slot is read and the result is all zeros
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3((rr + 63) / 64), dim3(1024), 0, st, scratch, used, rr, s);
 }
 
 void launch_apply(const float* m, uint64_t rows, int rank, const float* p, float* out, int numCU,
@@ -360,7 +395,9 @@ struct hbcsf_als {
   const hbcsf_tensor* t = nullptr;
   int rank = 0;
   float* m = nullptr;    // workspace: MTTKRP output of the mode being updated [max dim][R]
-  double* s = nullptr;   // workspace: Gram accumulators [R][R]
+  double* s = nullptr;   // workspace: Gram matrix [R][R]
+  double* gramScratch = nullptr;  // workspace: per-block partial sums of the Gram kernel
+  uint32_t gramSlots = 0;
   float* p = nullptr;    // workspace: right-hand R x R matrix of the update [R][R]
   double* hostS = nullptr;  // pinned staging
   float* hostP = nullptr;   // pinned staging
@@ -380,15 +417,63 @@ struct hbcsf_als {
   }
 };
 
+namespace {
+
+int gram_check(const float* a, int rank, const double* s) {
+  if (!a || !s) return fail(HBCSF_EINVAL, "null argument");
+  if (!rank_ok(rank)) return fail(HBCSF_EINVAL, "rank must be 8, 16, 32, 64 or 128");
+  if (((uintptr_t)a & 15) != 0) return fail(HBCSF_EINVAL, "the matrix must be 16-byte aligned");
+  if (((uintptr_t)s & 7) != 0) return fail(HBCSF_EINVAL, "the result must be 8-byte aligned");
+  return HBCSF_OK;
+}
+
+int current_cu_count(int* cu) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  e = hipDeviceGetAttribute(cu, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return fail_hip(e, "hipDeviceGetAttribute");
+  if (*cu <= 0) *cu = 256;
+  return HBCSF_OK;
+}
+
+}  // namespace
+
 extern "C" {
+
+int hbcsf_gram_workspace_bytes(int rank, uint64_t* bytes) try {
+  if (!bytes) return fail(HBCSF_EINVAL, "null argument");
+  if (!rank_ok(rank)) return fail(HBCSF_EINVAL, "rank must be 8, 16, 32, 64 or 128");
+  *bytes = (uint64_t)gram_slots_for(rank, kGramWorkspaceCap) * (uint64_t)rank * rank * 8;
+  return HBCSF_OK;
+} HBCSF_CATCH_ALL
+
+int hbcsf_gram(const float* a, uint64_t rows, int rank, void* workspace, uint64_t workspace_bytes, double* s,
+               void* hip_stream) try {
+  const int rc = gram_check(a, rank, s);
+  if (rc != HBCSF_OK) return rc;
+  if (!workspace) return fail(HBCSF_EINVAL, "null argument");
+  if (((uintptr_t)workspace & 255) != 0) return fail(HBCSF_EINVAL, "workspace must be 256-byte aligned");
+  const uint32_t slots = gram_slots_for(rank, workspace_bytes);
+  if (slots == 0) return fail(HBCSF_ENOMEM, "workspace holds less than one rank x rank fp64 matrix");
+  int cu = 0;
+  const int rd = current_cu_count(&cu);
+  if (rd != HBCSF_OK) return rd;
+  launch_gram(a, rows, rank, (double*)workspace, slots, s, cu, (hipStream_t)hip_stream);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail_hip(e, "Gram kernel launch");
+  return HBCSF_OK;
+} HBCSF_CATCH_ALL
 
 int hbcsf_als_workspace_bytes(const hbcsf_tensor* t, int rank, uint64_t* bytes) try {
   if (!t || !bytes) return fail(HBCSF_EINVAL, "null argument");
   if (!rank_ok(rank)) return fail(HBCSF_EINVAL, "rank must be 8, 16, 32, 64 or 128");
   uint64_t maxDim = 0;
   for (int m = 0; m < t->order; ++m) maxDim = t->dims[m] > maxDim ? t->dims[m] : maxDim;
+  uint64_t gramBytes = 0;
+  (void)hbcsf_gram_workspace_bytes(rank, &gramBytes);
   *bytes = round256(maxDim * (uint64_t)rank * 4) + round256((uint64_t)rank * rank * 8) +
-           round256((uint64_t)rank * rank * 4);
+           round256((uint64_t)rank * rank * 4) + round256(gramBytes);
   return HBCSF_OK;
 } HBCSF_CATCH_ALL
 
@@ -415,6 +500,11 @@ int hbcsf_als_create(const hbcsf_tensor* t, int rank, void* workspace, uint64_t 
   a->s = (double*)w;
   w += round256((uint64_t)rank * rank * 8);
   a->p = (float*)w;
+  w += round256((uint64_t)rank * rank * 4);
+  a->gramScratch = (double*)w;
+  uint64_t gramBytes = 0;
+  (void)hbcsf_gram_workspace_bytes(rank, &gramBytes);
+  a->gramSlots = gram_slots_for(rank, gramBytes);
   const size_t rr = (size_t)rank * rank;
   hipError_t e = hipHostMalloc((void**)&a->hostS, rr * 8 + HBCSF_MAX_ORDER * rr * 4 + (size_t)rank * 4, hipHostMallocDefault);
   if (e != hipSuccess) return fail_hip(e, "hipHostMalloc");
@@ -442,7 +532,7 @@ int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int 
   hipError_t e;
 
   auto gram_to_host = [&](const float* src, uint64_t rows, Mat& dst) -> int {
-    launch_gram(src, rows, R, a->s, t->numCU, st);
+    launch_gram(src, rows, R, a->gramScratch, a->gramSlots, a->s, t->numCU, st);
     e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e, "Gram kernel launch");
     e = hipMemcpyAsync(a->hostS, a->s, rr * 8, hipMemcpyDeviceToHost, st);

@@ -133,3 +133,19 @@ def test_planted_mistakes_fail_the_least_squares_pin():
     ]
     for w in wrong:
         assert np.max(np.abs(w - want)) > 1e-3 * np.max(np.abs(want))
+
+
+def test_gram_is_the_sum_of_row_outer_products():
+    """The Gram matrix of Eq. 3 written out entry by entry: S[r][s] = sum_i A[i][r] A[i][s]."""
+    rng = np.random.default_rng(77)
+    a = rng.uniform(-1, 1, size=(37, 5)).astype(np.float32)
+    want = np.zeros((5, 5))
+    for i in range(37):
+        for r in range(5):
+            for s in range(5):
+                want[r, s] += float(a[i, r]) * float(a[i, s])
+    got = cpd_als.gram(a)
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(np.diag(got), (a.astype(np.float64) ** 2).sum(axis=0), rtol=1e-13)
+    assert np.array_equal(got, got.T)
+    assert np.array_equal(cpd_als.gram(np.zeros((0, 4), np.float32)), np.zeros((4, 4)))
