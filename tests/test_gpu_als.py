@@ -189,7 +189,7 @@ def test_argument_errors():
     dims = (50, 40, 30)
     inds, vals = _random_tensor(rng, dims, 500)
     t = HbcsfTensor(dims, inds, vals)
-    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.als_workspace_bytes(t.handle, 32), dtype=torch.uint8, device="cuda")
     with pytest.raises(B.HbcsfError) as e:
         B.als_create(t.handle, 32, ws.data_ptr(), ws.numel())
     assert e.value.code == -4                                  # not uploaded
