@@ -245,6 +245,18 @@ int hbcsf_gram_workspace_bytes(int rank, uint64_t *bytes);
 int hbcsf_gram(const float *a, uint64_t rows, int rank, void *workspace, uint64_t workspace_bytes,
                double *s, void *hip_stream);
 
+/* hbcsf_gram for callers that cannot allocate device memory (code recorded under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same computation with the partial-sum
+ * slots taken from an 8 MiB array the library itself holds in device memory (one copy per device, kept
+ * until the process ends) instead of a workspace argument.  The call allocates nothing on the host or the
+ * device and only launches kernels on hip_stream; the first call on a device also looks up the array's
+ * address there.  a, rows, rank, s, errors: as hbcsf_gram; a rank whose single rank x rank fp64 slot
+ * exceeds the array is rejected with HBCSF_EINVAL (none of the supported ranks does: at most 128 KB),
+ * and at ranks 64 and 128 fewer workgroups run than with hbcsf_gram's full workspace (256 and 64).
+ * All calls on one device share the array: calls that overlap in time on one device race, whatever
+ * their streams; calls one after the other need no clearing in between. */
+int hbcsf_gram_noalloc(const float *a, uint64_t rows, int rank, double *s, void *hip_stream);
+
 /* Device workspace an ALS state needs for this tensor and rank: one [max dim][rank] fp32 matrix
  * for the MTTKRP result, two rank x rank matrices and the Gram computation's scratch
  * (hbcsf_gram_workspace_bytes). */

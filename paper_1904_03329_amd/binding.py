@@ -27,7 +27,7 @@ EXPORTS = (
     "hbcsf_host_array", "hbcsf_tune", "hbcsf_kernel_ms", "hbcsf_probe_row_gather", "hbcsf_free",
     "hbcsf_strerror", "hbcsf_last_error",
     "hbcsf_als_workspace_bytes", "hbcsf_als_create", "hbcsf_als_iteration", "hbcsf_als_run", "hbcsf_als_phase_ms", "hbcsf_als_free", "hbcsf_sym_pinv",
-    "hbcsf_gram_workspace_bytes", "hbcsf_gram",
+    "hbcsf_gram_workspace_bytes", "hbcsf_gram", "hbcsf_gram_noalloc",
     "hbcsf_device_build_bytes", "hbcsf_build_format_device", "hbcsf_download", "hbcsf_relocate",
 )
 
@@ -113,6 +113,8 @@ def lib():
         L.hbcsf_gram_workspace_bytes.argtypes = [i32, ctypes.POINTER(u64)]
         L.hbcsf_gram.restype = i32
         L.hbcsf_gram.argtypes = [vp, u64, i32, vp, u64, vp, vp]
+        L.hbcsf_gram_noalloc.restype = i32
+        L.hbcsf_gram_noalloc.argtypes = [vp, u64, i32, vp, vp]
         L.hbcsf_sym_pinv.restype = i32
         L.hbcsf_sym_pinv.argtypes = [vp, i32, vp]
         L.hbcsf_als_free.restype = None
@@ -294,6 +296,12 @@ def gram(a_ptr: int, rows: int, rank: int, workspace_ptr: int, workspace_bytes: 
     """hbcsf_gram: device addresses in; s_ptr receives the [rank][rank] fp64 Gram matrix."""
     _check(lib().hbcsf_gram(ctypes.c_void_p(a_ptr), rows, rank, ctypes.c_void_p(workspace_ptr), workspace_bytes,
                             ctypes.c_void_p(s_ptr), ctypes.c_void_p(stream or None)))
+
+
+def gram_noalloc(a_ptr: int, rows: int, rank: int, s_ptr: int, stream: int = 0):
+    """hbcsf_gram_noalloc: as gram, with the library's own scratch."""
+    _check(lib().hbcsf_gram_noalloc(ctypes.c_void_p(a_ptr), rows, rank, ctypes.c_void_p(s_ptr),
+                                    ctypes.c_void_p(stream or None)))
 
 
 def sym_pinv(v: np.ndarray) -> np.ndarray:

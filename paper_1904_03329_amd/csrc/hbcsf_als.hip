@@ -17,6 +17,7 @@
 #include <cmath>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -417,7 +418,25 @@ struct hbcsf_als {
   }
 };
 
+// ---------------------------------------------------------------------------------------------------
+// Scratch owned by the library, for hbcsf_gram_noalloc: callers that may not allocate device memory (code
+// under graph capture, serving loops, harnesses that forbid it) get the Gram computation's partial-sum
+// slots from this array instead of a workspace argument.  Every device the library runs on holds its own
+// copy, at its own address, until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address that call returns is what kernels and copies are given.
+// ---------------------------------------------------------------------------------------------------
+constexpr uint64_t kStaticScratchBytes = 8ull << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+struct DeviceScratch {
+  void* ptr = nullptr;  // device address of `scratch` on this device
+  int numCU = 0;
+};
+DeviceScratch g_scratch[kMaxDevices];
+std::mutex g_scratchMutex;
 
 int gram_check(const float* a, int rank, const double* s) {
   if (!a || !s) return fail(HBCSF_EINVAL, "null argument");
@@ -461,6 +480,37 @@ int hbcsf_gram(const float* a, uint64_t rows, int rank, void* workspace, uint64_
   if (rd != HBCSF_OK) return rd;
   launch_gram(a, rows, rank, (double*)workspace, slots, s, cu, (hipStream_t)hip_stream);
   const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail_hip(e, "Gram kernel launch");
+  return HBCSF_OK;
+} HBCSF_CATCH_ALL
+
+int hbcsf_gram_noalloc(const float* a, uint64_t rows, int rank, double* s, void* hip_stream) try {
+  const int rc = gram_check(a, rank, s);
+  if (rc != HBCSF_OK) return rc;
+  if ((uint64_t)rank * rank * 8 > kStaticScratchBytes)
+    return fail(HBCSF_EINVAL, "rank is beyond what the library's own scratch holds (one rank x rank fp64 slot)");
+  int dev = 0, cu = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(HBCSF_EINVAL, "device ordinal beyond the library's per-device table");
+  DeviceScratch& d = g_scratch[dev];
+  {
+    // once per device, with that device current: the array's address on this device (each device has its own copy)
+    std::lock_guard<std::mutex> lock(g_scratchMutex);
+    if (!d.ptr) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return fail_hip(e, "hipGetSymbolAddress");
+      if (!p || ((uintptr_t)p & 255) != 0) return fail(HBCSF_EHIP, "the scratch array has no usable device address");
+      e = hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+      if (e != hipSuccess) return fail_hip(e, "hipDeviceGetAttribute");
+      d.numCU = cu > 0 ? cu : 256;
+      d.ptr = p;
+    }
+  }
+  launch_gram(a, rows, rank, (double*)d.ptr, gram_slots_for(rank, kStaticScratchBytes), s, d.numCU,
+              (hipStream_t)hip_stream);
+  e = hipGetLastError();
   if (e != hipSuccess) return fail_hip(e, "Gram kernel launch");
   return HBCSF_OK;
 } HBCSF_CATCH_ALL
