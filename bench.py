@@ -98,9 +98,10 @@ def algorithmic_bytes(st: dict, rank: int, order: int) -> dict:
         out[name] = st["stream_bytes"][g] + row * gathered + row * st["group_slices"][g]
     # define kernel: the owned-row bitmap once + every row no kernel stores (zero fill)
     out["define"] = 4 * ((rows_total + 31) // 32) + row * (rows_total - st["owned_rows"])
-    # rows merged with atomics are counted once in their kernel above and once as zero fill;
-    # take the zero fill out again so that the dense output is counted exactly once in the total
-    out["total"] = sum(out[k] for k in KERNELS) - row * st["shared_slices"]
+    # the whole mode: format arrays and distinct factor rows per kernel, plus the dense output exactly once (a row
+    # that several kernels or pieces add to is still one row) and the owned-row bitmap
+    out["total"] = (sum(out[k] - row * st["group_slices"][g] for g, k in enumerate(("coo", "csl", "csf")) if out[k])
+                    + 4 * ((rows_total + 31) // 32) + row * rows_total)
     return out
 
 
@@ -217,7 +218,8 @@ def time_device_build(torch, np, B, HbcsfTensor, t, host_tensor, args, log):
             t0 = time.perf_counter()
             dev = HbcsfTensor.from_device_coo(t.dims, di, dv, compact=False, fiber_threshold=args.fiber_threshold,
                                               slice_threshold=args.slice_threshold,
-                                              mode_order_policy=args.mode_order_policy, group_mask=args.group_mask)
+                                              mode_order_policy=args.mode_order_policy, group_mask=args.group_mask,
+                                              coo_row_flags=args.coo_row_flags)
             torch.cuda.synchronize()
             times.append(time.perf_counter() - t0)
             same = B.device_bytes(dev.handle) == B.device_bytes(host_tensor.handle)
@@ -321,7 +323,8 @@ def measure(name: str, args, headline: bool, log) -> dict:
     t0 = time.time()
     ht = HbcsfTensor(t.dims, t.inds, t.vals, fiber_threshold=args.fiber_threshold,
                      slice_threshold=args.slice_threshold, mode_order_policy=args.mode_order_policy,
-                     group_mask=args.group_mask)
+                     group_mask=args.group_mask, hybrid_granularity=args.hybrid_granularity,
+                     coo_row_flags=args.coo_row_flags)
     build_s = time.time() - t0
     t0 = time.time()
     ht.to_device()
@@ -333,7 +336,8 @@ def measure(name: str, args, headline: bool, log) -> dict:
         st["rows"] = t.dims[m]
         stats.append(st)
     log(f"[bench] format built in {build_s:.1f}s, uploaded {B.device_bytes(ht.handle) / 1e9:.2f} GB in {upload_s:.1f}s")
-    dev_build = time_device_build(torch, np, B, HbcsfTensor, t, ht, args, log) if headline else None
+    dev_build = (time_device_build(torch, np, B, HbcsfTensor, t, ht, args, log)
+                 if headline and not args.hybrid_granularity else None)
     dfacs = [torch.from_numpy(f).cuda() for f in facs]
     outs = [torch.empty((t.dims[m], rank), dtype=torch.float32, device="cuda") for m in range(order)]
 
@@ -463,6 +467,10 @@ def main() -> int:
     ap.add_argument("--slice-threshold", type=int, default=0)
     ap.add_argument("--mode-order-policy", type=int, default=0)
     ap.add_argument("--group-mask", type=int, default=0)
+    ap.add_argument("--coo-row-flags", type=int, default=0,
+                    help="1: the COO group stores row flags instead of a root index per nonzero")
+    ap.add_argument("--hybrid-granularity", type=int, default=0,
+                    help="1: COO / CSL / CSF chosen per fiber inside heavy slices (host builder only)")
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--kernel-steps", type=int, default=0)
     ap.add_argument("--als-iterations", type=int, default=3,

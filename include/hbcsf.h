@@ -56,6 +56,19 @@ typedef struct hbcsf_opts {
   uint32_t group_mask;        /* HB-CSF groups in use (Section V): bit0 = COO group, bit1 = CSL
                                  group.  Default (0) = 3 = both.  4 = neither (plain B-CSF),
                                  for ablation.  Slices of a disabled group go to the CSF group.    */
+  uint32_t hybrid_granularity;/* 0 = the group is chosen per slice (Section V).  1 = per fiber inside
+                                 heavy slices (Section VI-F leaves the sparse portion open to further
+                                 work): a slice of at least 2 T_f nonzeros with at least an eighth of
+                                 them in singleton deepest-level fibers is stored as two pieces with
+                                 the same root index, the singleton-fiber nonzeros in the CSL group and
+                                 the others in the CSF group; both pieces are merged with atomic adds.
+                                 Needs the CSL group enabled; otherwise ignored.                     */
+  uint32_t coo_row_flags;     /* 1 = the COO group stores no root index per nonzero (N-1 instead of N
+                                 index words each): its nonzeros are kept in row order, and one flag
+                                 per output row (HBCSF_ARR_COO_BITS) with a running count per 32 rows
+                                 (HBCSF_ARR_COO_PTR) says which row each belongs to.  hbcsf_mttkrp then
+                                 always computes the group's rows in the output-definition pass.  0
+                                 (default): root indices are stored and either kernel can be used.    */
 } hbcsf_opts;
 
 /* Per-mode statistics of the built representation.  "words" are 4-byte index words as the

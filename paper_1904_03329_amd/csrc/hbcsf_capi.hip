@@ -83,6 +83,8 @@ int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint
   if (!pow2_in(o.fiber_threshold, 8, 64)) return fail(HBCSF_EINVAL, "fiber_threshold must be 8, 16, 32 or 64");
   if (o.mode_order_policy > 2) return fail(HBCSF_EINVAL, "mode_order_policy must be 0, 1 or 2");
   if (o.group_mask > 4) return fail(HBCSF_EINVAL, "group_mask must be 0..4");
+  if (o.hybrid_granularity > 1) return fail(HBCSF_EINVAL, "hybrid_granularity must be 0 or 1");
+  if (o.coo_row_flags > 1) return fail(HBCSF_EINVAL, "coo_row_flags must be 0 or 1");
   std::unique_ptr<hbcsf_tensor> t(new (std::nothrow) hbcsf_tensor);
   if (!t) return fail(HBCSF_ENOMEM, "out of host memory");
   t->order = order;
@@ -191,7 +193,9 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
   // 1. define every output row that no plain store will write; the COO group's rows are written
   //    in the same pass
   // (measured: the fused pass saves a launch on small outputs but hides latency worse on large ones)
-  const bool wantFuse = t->fuseCoo == 1 || (t->fuseCoo == 2 && f.rows * (uint64_t)rank * 4ull <= (64ull << 20));
+  // (without stored root indices only the fused pass can place the COO group's rows)
+  const bool wantFuse = f.cooRowFlags || t->fuseCoo == 1 ||
+                        (t->fuseCoo == 2 && f.rows * (uint64_t)rank * 4ull <= (64ull << 20));
   const bool fuseCoo = wantFuse && (t->kernelMask & 3u) == 3u && f.g[kCoo].nnz > 0;
   if (t->kernelMask & 1u) {
     // one wavefront per 8 x 32 rows, capped at 64 wavefronts per compute unit
@@ -224,7 +228,7 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
   for (int g = 0; g < 3; ++g) {
     const GroupFormat& gf = f.g[g];
     bool launched = false;
-    if (gf.nnz > 0 && (t->kernelMask & (2u << g)) && !(g == kCoo && fuseCoo)) {
+    if (gf.nnz > 0 && (t->kernelMask & (2u << g)) && !(g == kCoo && (fuseCoo || f.cooRowFlags))) {
       GroupArgs a = group_args(g);
       a.val = (const float*)(base + gf.val.off);
       a.out = out;

@@ -34,7 +34,7 @@ struct Spec {
   int N, NF;
   int shift[HBCSF_MAX_ORDER];
   uint64_t mask[HBCSF_MAX_ORDER];
-  uint32_t L, cooOn, cslOn;
+  uint32_t L, cooOn, cslOn, cooRowFlags;
 };
 
 struct C6 {  // running slice and nonzero counts of the three groups
@@ -242,7 +242,7 @@ __global__ void fill_nonzeros_kernel(const Key* K, const uint32_t* V, size_t M, 
   for (int l = 0; l < sp.N; ++l) idx[l] = (uint32_t)((uint64_t)(key >> sp.shift[l]) & sp.mask[l]);
   const uint32_t v = V[p];
   if (g == kCoo) {
-    for (int l = 0; l < sp.N; ++l) o.cooInd[l][pos] = idx[l];
+    for (int l = sp.cooRowFlags ? 1 : 0; l < sp.N; ++l) o.cooInd[l][pos] = idx[l];
     for (int l = 1; l < sp.N; ++l) mark_row(o.seen[kCoo][l], idx[l]);
     o.cooVal[pos] = v;
     atomicOr(&o.cooBits[idx[0] >> 5], 1u << (idx[0] & 31));
@@ -443,6 +443,9 @@ int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* 
   if (!(ft == 8 || ft == 16 || ft == 32 || ft == 64)) return fail(HBCSF_EINVAL, "fiber_threshold must be 8, 16, 32 or 64");
   if (o->mode_order_policy > 2) return fail(HBCSF_EINVAL, "mode_order_policy must be 0, 1 or 2");
   if (o->group_mask > 4) return fail(HBCSF_EINVAL, "group_mask must be 0..4");
+  if (o->coo_row_flags > 1) return fail(HBCSF_EINVAL, "coo_row_flags must be 0 or 1");
+  if (o->hybrid_granularity != 0)
+    return fail(HBCSF_EINVAL, "hybrid_granularity = 1 is built by hbcsf_build_format (host) only");
   *totalBits = total;
   return HBCSF_OK;
 }
@@ -465,6 +468,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   const uint32_t gmask = opts.group_mask == 0 ? 3u : (opts.group_mask & 3u);
   sp.cooOn = gmask & 1u;
   sp.cslOn = (gmask & 2u) ? 1u : 0u;
+  sp.cooRowFlags = opts.coo_row_flags == 1 ? 1u : 0u;
   int lv[HBCSF_MAX_ORDER];
   level_order(N, dims, mode, opts.mode_order_policy, lv);
   int total = 0;
@@ -477,6 +481,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   out->order = N;
   out->mode = mode;
   out->L = sp.L;
+  out->cooRowFlags = sp.cooRowFlags != 0;
   out->rows = dims[mode];
   for (int l = 0; l < N; ++l) out->levelMode[l] = lv[l];
 

@@ -101,6 +101,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   out->order = N;
   out->mode = mode;
   out->L = L;
+  out->cooRowFlags = opts.coo_row_flags == 1;
   out->rows = dims[mode];
   for (int l = 0; l < N; ++l) out->levelMode[l] = lv[l];
 
@@ -167,8 +168,18 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   sStart[S] = (uint32_t)M;
 
   // ---- classify slices (Section V; Section VI-D) ----
+  // Per slice (the paper's rule): one nonzero -> COO; every deepest-level fiber a singleton -> CSL; else CSF.
+  // With hybrid_granularity = 1 the choice is made per fiber inside heavy slices: a slice of at least 2 L
+  // nonzeros (it spans several runs, so its row is merged with atomic adds anyway) of which at least an eighth
+  // sit in singleton deepest-level fibers is split: those nonzeros form a CSL-group slice of the same root index,
+  // the others a CSF-group slice; both pieces are marked shared.
   const int NF = N - 2;  // fiber levels 1..NF
+  const bool perFiber = opts.hybrid_granularity == 1 && cslOn;
+  // a nonzero whose deepest-level fiber holds only itself
+  auto single = [&](size_t p, size_t e) -> bool { return fresh(NF, p) && (p + 1 == e || fresh(NF, p + 1)); };
+  constexpr uint8_t kSplit = 3;  // CSL piece + CSF piece
   std::vector<uint8_t> grp(S);
+  std::vector<uint32_t> nSingle(perFiber ? S : 0);
   uint64_t fibNat[2] = {0, 0};
   uint64_t fibNatCsf[2] = {0, 0};
   {
@@ -186,38 +197,81 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
       if (n == 1 && cooOn) g = kCoo;
       else if (deep == n && cslOn) g = kCsl;
       else g = kCsf;
+      uint64_t kept[2] = {nf[0], nf[1]};  // fibers that stay in the CSF group
+      if (perFiber && g == kCsf && n >= 2ull * L) {
+        uint64_t ns = 0;
+        for (size_t p = b; p < e; ++p) ns += single(p, e);
+        if (ns * 8 >= n) {
+          g = kSplit;
+          nSingle[s] = (uint32_t)ns;
+          // fibers of the CSF piece: a fiber level counts once per run of kept nonzeros that share it
+          kept[0] = kept[1] = 0;
+          bool pend[2] = {false, false};
+          for (size_t p = b; p < e; ++p) {
+            pend[0] = pend[0] || fresh(1, p);
+            if (NF == 2) pend[1] = pend[1] || fresh(2, p);
+            if (single(p, e)) continue;
+            for (int f = 0; f < NF; ++f) {
+              kept[f] += pend[f];
+              pend[f] = false;
+            }
+          }
+        }
+      }
       grp[s] = g;
       f0 += nf[0];
       f1 += nf[1];
-      if (g == kCsf) { c0 += nf[0]; c1 += nf[1]; }
+      if (g == kCsf || g == kSplit) { c0 += kept[0]; c1 += kept[1]; }
     }
     fibNat[0] = f0; fibNat[1] = f1; fibNatCsf[0] = c0; fibNatCsf[1] = c1;
   }
 
-  // ---- position of each slice inside its group ----
-  std::vector<uint32_t> ord(S), off(S);
+  // ---- position of each slice (piece) inside its group ----
+  // ord / off: the slice's entry and first nonzero in its group; a split slice's CSL piece is in ordL / offL
+  std::vector<uint32_t> ord(S), off(S), ordL(perFiber ? S : 0), offL(perFiber ? S : 0);
   uint64_t gS[3] = {0, 0, 0}, gM[3] = {0, 0, 0};
   for (uint64_t s = 0; s < S; ++s) {
+    const uint64_t n = sStart[s + 1] - sStart[s];
+    if (grp[s] == kSplit) {
+      ordL[s] = (uint32_t)gS[kCsl];
+      offL[s] = (uint32_t)gM[kCsl];
+      gS[kCsl] += 1;
+      gM[kCsl] += nSingle[s];
+      ord[s] = (uint32_t)gS[kCsf];
+      off[s] = (uint32_t)gM[kCsf];
+      gS[kCsf] += 1;
+      gM[kCsf] += n - nSingle[s];
+      continue;
+    }
     const int g = grp[s];
     ord[s] = (uint32_t)gS[g];
     off[s] = (uint32_t)gM[g];
     gS[g] += 1;
-    gM[g] += sStart[s + 1] - sStart[s];
+    gM[g] += n;
   }
 
   // ---- count fiber segments of the CSF group (fbr-split on the run grid) ----
+  // A segment starts at a kept nonzero that lies on the run grid or is the first kept one of its fiber.
   std::vector<uint32_t> segOff[2];
   uint64_t nSeg[2] = {0, 0};
   for (int f = 0; f < NF; ++f) segOff[f].assign(S + 1, 0);
 #pragma omp parallel for schedule(dynamic, 512)
   for (int64_t s = 0; s < (int64_t)S; ++s) {
-    if (grp[s] != kCsf) continue;
+    if (grp[s] != kCsf && grp[s] != kSplit) continue;
     const size_t b = sStart[s], e = sStart[s + 1];
+    const bool split = grp[s] == kSplit;
     uint32_t c[2] = {0, 0};
+    uint32_t pos = off[s];
+    bool pend[2] = {false, false};
     for (size_t p = b; p < e; ++p) {
-      const bool cut = ((off[s] + (uint32_t)(p - b)) % L) == 0;
-      c[0] += cut || fresh(1, p);
-      if (NF == 2) c[1] += cut || fresh(2, p);
+      pend[0] = pend[0] || fresh(1, p);
+      if (NF == 2) pend[1] = pend[1] || fresh(2, p);
+      if (split && single(p, e)) continue;
+      const bool cut = (pos % L) == 0;
+      c[0] += cut || pend[0];
+      if (NF == 2) c[1] += cut || pend[1];
+      pend[0] = pend[1] = false;
+      ++pos;
     }
     segOff[0][s + 1] = c[0];
     if (NF == 2) segOff[1][s + 1] = c[1];
@@ -273,43 +327,60 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
 #pragma omp parallel for schedule(dynamic, 512) reduction(+ : sharedSlices)
   for (int64_t s = 0; s < (int64_t)S; ++s) {
     const size_t b = sStart[s], e = sStart[s + 1];
-    const uint32_t n = (uint32_t)(e - b), a = off[s], o = ord[s];
     const uint32_t root = idx(0, b);
     const int g = grp[s];
     bool own = true;
     if (g == kCoo) {
-      for (int l = 0; l < N; ++l) cooInd[l][a] = idx(l, b);
+      const uint32_t a = off[s];
+      for (int l = out->cooRowFlags ? 1 : 0; l < N; ++l) cooInd[l][a] = idx(l, b);
       cooVal[a] = V[b];
       __atomic_fetch_or(&cooBits[root >> 5], 1u << (root & 31), __ATOMIC_RELAXED);
     } else {
-      own = (a / L) == ((a + n - 1) / L);
-      uint32_t* run0 = g == kCsl ? cslRun : csfRun[0];
-      for (uint32_t r = (a + L - 1) / L; r <= (a + n - 1) / L; ++r) run0[r] = o;
-      if (g == kCsl) {
+      const bool split = g == kSplit;
+      // the CSL piece (a whole CSL slice, or the singleton-fiber nonzeros of a split slice)
+      if (g == kCsl || split) {
+        const uint32_t a = split ? offL[s] : off[s], o = split ? ordL[s] : ord[s];
+        const uint32_t n = split ? nSingle[s] : (uint32_t)(e - b);
+        own = !split && (a / L) == ((a + n - 1) / L);
+        for (uint32_t r = (a + L - 1) / L; r <= (a + n - 1) / L; ++r) cslRun[r] = o;
         cslInd[0][o] = root | (own ? kOwnedBit : 0u);
         cslPtr[o] = a;
+        uint32_t pos = a;
         for (size_t p = b; p < e; ++p) {
-          const uint32_t pos = a + (uint32_t)(p - b);
+          if (split && !single(p, e)) continue;
           for (int l = 1; l < N; ++l) cslInd[l][pos] = idx(l, p);
           cslVal[pos] = V[p];
+          ++pos;
         }
-      } else {
+      }
+      // the CSF piece
+      if (g == kCsf || split) {
+        const uint32_t a = off[s], o = ord[s];
+        const uint32_t n = split ? (uint32_t)(e - b) - nSingle[s] : (uint32_t)(e - b);
+        own = !split && (a / L) == ((a + n - 1) / L);
+        for (uint32_t r = (a + L - 1) / L; r <= (a + n - 1) / L; ++r) csfRun[0][r] = o;
         csfInd[0][o] = root | (own ? kOwnedBit : 0u);
         csfPtr[0][o] = a;
         uint32_t f[2] = {segOff[0][s], NF == 2 ? segOff[1][s] : 0u};
+        uint32_t pos = a;
+        bool pend[2] = {false, false};
         for (size_t p = b; p < e; ++p) {
-          const uint32_t pos = a + (uint32_t)(p - b);
+          pend[0] = pend[0] || fresh(1, p);
+          if (NF == 2) pend[1] = pend[1] || fresh(2, p);
+          if (split && single(p, e)) continue;
           const bool cut = (pos % L) == 0;
           for (int l = 1; l <= NF; ++l) {
-            if (cut || fresh(l, p)) {
+            if (cut || pend[l - 1]) {
               csfInd[l][f[l - 1]] = idx(l, p);
               csfPtr[l][f[l - 1]] = pos;
               if (cut) csfRun[l][pos / L] = f[l - 1];
               ++f[l - 1];
             }
           }
+          pend[0] = pend[1] = false;
           csfInd[N - 1][pos] = idx(N - 1, p);
           csfVal[pos] = V[p];
+          ++pos;
         }
       }
       if (!own) ++sharedSlices;

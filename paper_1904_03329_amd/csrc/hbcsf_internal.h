@@ -42,6 +42,7 @@ struct ModeFormat {
   int order = 0;
   int mode = 0;
   uint32_t L = 64;                 // run length = fiber threshold T_f
+  bool cooRowFlags = false;        // the COO group has no root index array (rows come from cooBits / cooPtr)
   int levelMode[HBCSF_MAX_ORDER] = {0, 0, 0, 0};
   uint64_t rows = 0;               // dims[mode]
   GroupFormat g[3];
@@ -81,7 +82,7 @@ inline void layout_mode(ModeFormat* out, int N, const uint64_t gS[3], const uint
   }
   {
     GroupFormat& G = out->g[kCoo];
-    for (int l = 0; l < N; ++l) G.ind[l] = add(G.nnz);
+    for (int l = 0; l < N; ++l) G.ind[l] = add(l == 0 && out->cooRowFlags ? 0 : G.nnz);
     G.val = add(G.nnz);
   }
   {

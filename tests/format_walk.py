@@ -30,6 +30,14 @@ def read_mode(h, mode, order):
         d["slices"] = st["group_slices"][g]
         fmt[gname] = d
     fmt["owned"] = B.host_array(h, mode, 0, 0, B.ARR_OWNED_BITS)
+    coo = fmt["coo"]
+    fmt["coo_row_flags"] = coo["nnz"] > 0 and len(coo["ind"][0]) == 0
+    if fmt["coo_row_flags"]:
+        # no stored root indices: the nonzeros are in row order and the row bitmap says which rows they are
+        bits = B.host_array(h, mode, 0, 0, B.ARR_COO_BITS)
+        rows = np.flatnonzero(np.unpackbits(bits.view(np.uint8), bitorder="little"))
+        assert rows.shape[0] == coo["nnz"]
+        coo["ind"][0] = rows.astype(np.uint32)
     return fmt
 
 

@@ -291,3 +291,64 @@ def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
         assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("order", [3, 4])
+def test_per_fiber_hybrid_splits_heavy_slices(oracle, order):
+    """hybrid_granularity = 1 (Section VI-F's open point): inside a slice of at least 2 T_f nonzeros the nonzeros of
+    singleton deepest-level fibers go to the CSL group and the others to the CSF group, as two pieces with the same
+    root index, both merged with atomic adds; light slices and slices with few singleton fibers stay whole."""
+    rng = np.random.default_rng(5 + order)
+    L = 8
+    dims = (6, 40, 50) if order == 3 else (6, 4, 40, 50)
+    rows = []
+
+    def add(root, mids, leaves):          # nonzeros (root, [mid...], leaf)
+        for m, l in zip(mids, leaves):
+            rows.append((root,) + tuple(m) + (l,))
+
+    mid = (lambda j: (j,)) if order == 3 else (lambda j: (1, j))
+    # slice 0: 30 nonzeros, 20 in singleton fibers + one fiber of 10 -> split
+    add(0, [mid(j) for j in range(20)] + [mid(30)] * 10, list(range(20)) + list(range(10)))
+    # slice 1: 30 nonzeros, 2 singleton fibers + 4 fibers of 7 -> too few singletons: stays in the CSF group
+    add(1, [mid(0), mid(1)] + [mid(5 + q) for q in range(4) for _ in range(7)], [0, 1] + [r for _ in range(4) for r in range(7)])
+    # slice 2: 10 nonzeros (below 2 T_f), 6 singleton fibers + one of 4 -> stays in the CSF group
+    add(2, [mid(j) for j in range(6)] + [mid(9)] * 4, list(range(6)) + list(range(4)))
+    # slice 3: all singleton fibers -> CSL as a whole; slice 4: one nonzero -> COO
+    add(3, [mid(j) for j in range(20)], list(range(20)))
+    add(4, [mid(3)], [3])
+    arr = np.array(rows, dtype=np.uint32)
+    arr = arr[rng.permutation(arr.shape[0])]
+    inds = [np.ascontiguousarray(arr[:, m]) for m in range(order)]
+    vals = rng.uniform(-1, 1, size=arr.shape[0]).astype(np.float32)
+    facs = [rng.uniform(0, 1, size=(d, 8)).astype(np.float32) for d in dims]
+    h = B.build_format(dims, inds, vals, fiber_threshold=L, mode_order_policy=2, hybrid_granularity=1)
+    h0 = B.build_format(dims, inds, vals, fiber_threshold=L, mode_order_policy=2)
+    try:
+        st, st0 = B.get_stats(h, 0), B.get_stats(h0, 0)
+        assert st0["group_nnz"] == [1, 20, 70] and st0["group_slices"] == [1, 1, 3]
+        assert st["group_nnz"] == [1, 40, 50] and st["group_slices"] == [1, 2, 3]
+        fmt = FW.read_mode(h, 0, order)
+        csl_roots = (fmt["csl"]["ind"][0][:2] & 0x7FFFFFFF).tolist()
+        csl_owned = (fmt["csl"]["ind"][0][:2] >> 31).tolist()
+        csf_roots = (fmt["csf"]["ind"][0][:3] & 0x7FFFFFFF).tolist()
+        csf_owned = (fmt["csf"]["ind"][0][:3] >> 31).tolist()
+        assert csl_roots == [0, 3] and csf_roots == [0, 1, 2]
+        assert csl_owned[0] == 0 and csf_owned[0] == 0            # both pieces of the split slice are shared
+        assert not (fmt["owned"][0] & 1)                           # so its row is zero-filled, not stored
+        # the CSL piece of slice 0 holds exactly the 20 singleton-fiber nonzeros
+        ptr = fmt["csl"]["ptr"][0]
+        assert ptr[1] - ptr[0] == 20
+        assert sorted(fmt["csl"]["ind"][order - 2][ptr[0]:ptr[1]].tolist()) == list(range(20))
+        # the CSF piece keeps the fiber of 10, cut on the run grid
+        assert st["segments"][order - 3] >= 1 + 6 + 2
+        for mode in range(order):
+            f = FW.read_mode(h, mode, order)
+            want = oracle.mttkrp(dims, inds, vals, facs, mode)
+            np.testing.assert_allclose(FW.walk_algorithms(f, facs, dims[mode], 8), want, rtol=1e-10, atol=1e-12)
+            np.testing.assert_allclose(FW.emulate_kernels(f, facs, dims[mode], 8), want, rtol=1e-10, atol=1e-12)
+        with pytest.raises(B.HbcsfError):
+            B.build_format(dims, inds, vals, hybrid_granularity=2)
+    finally:
+        B.free(h)
+        B.free(h0)

@@ -52,7 +52,9 @@ def test_ranks_and_orders(oracle, dims, nnz, rank):
 
 @pytest.mark.parametrize("opts", [dict(fiber_threshold=8), dict(fiber_threshold=64), dict(group_mask=4),
                                   dict(group_mask=1), dict(group_mask=2), dict(mode_order_policy=1),
-                                  dict(mode_order_policy=2), dict(tune_ts=256), dict(tune_ts=100_000)])
+                                  dict(mode_order_policy=2), dict(tune_ts=256), dict(tune_ts=100_000),
+                                  dict(hybrid_granularity=1), dict(hybrid_granularity=1, fiber_threshold=8),
+                                  dict(coo_row_flags=1)])
 @pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000)])
 def test_build_options_do_not_change_the_result(oracle, dims, nnz, opts):
     rng = np.random.default_rng(len(dims) + 7)
@@ -69,6 +71,12 @@ def test_hypersparse_groups(oracle, synth):
     print("hypersparse", t.dims, t.nnz, flush=True)
     stats = _check_all_modes(oracle, t.dims, t.inds, t.vals, facs, "hypersparse")
     assert stats[0]["group_nnz"][0] > 0 and stats[0]["group_nnz"][1] > 0 and stats[0]["group_nnz"][2] > 0
+    # the per-fiber choice moves the singleton-fiber nonzeros of heavy slices from the CSF to the CSL group
+    split = _check_all_modes(oracle, t.dims, t.inds, t.vals, facs, "hypersparse, per-fiber groups", hybrid_granularity=1)
+    assert split[0]["group_nnz"][1] > stats[0]["group_nnz"][1] and split[0]["group_nnz"][0] == stats[0]["group_nnz"][0]
+    # COO group without stored root indices (row flags): one index word less per nonzero, same result
+    flags = _check_all_modes(oracle, t.dims, t.inds, t.vals, facs, "hypersparse, COO row flags", coo_row_flags=1)
+    assert flags[0]["stream_bytes"][0] < stats[0]["stream_bytes"][0] and flags[0]["group_nnz"] == stats[0]["group_nnz"]
 
 
 @pytest.mark.parametrize("dims,nnz,alpha", [((34_000_000, 34_000_000, 100), 1_500_000, (1.05, 1.05, 0.0)),
