@@ -1,6 +1,6 @@
 /* hbcsf.h -- C ABI of the MI355X (gfx950) sparse-MTTKRP library.
  *
- * The library computes mode-n sparse MTTKRP on 3- and 4-order tensors,
+ * The library computes mode-n sparse MTTKRP on tensors of order 3, 4 and 5,
  *
  *     Y(i_n, :) = sum over nonzeros X(i_1..i_N) * hadamard_{m != n} A_m(i_m, :)
  *
@@ -36,7 +36,8 @@ extern "C" {
 #define HBCSF_ESTATE  -4  /* hbcsf_mttkrp before hbcsf_upload                                */
 #define HBCSF_EHIP    -5  /* a HIP call failed; hbcsf_last_error() names it                  */
 
-#define HBCSF_MAX_ORDER 4
+#define HBCSF_MAX_ORDER 5
+#define HBCSF_MAX_FIBER_LEVELS (HBCSF_MAX_ORDER - 2)
 
 typedef struct hbcsf_tensor hbcsf_tensor; /* opaque, owned by the library, freed by hbcsf_free */
 
@@ -45,7 +46,7 @@ typedef struct hbcsf_tensor hbcsf_tensor; /* opaque, owned by the library, freed
 typedef struct hbcsf_opts {
   uint32_t fiber_threshold;   /* T_f of fbr-split (Section IV-B, VI-B): no fiber segment holds more
                                  than T_f nonzeros.  Cuts fall on multiples of T_f in a group's
-                                 nonzero stream.  8, 16, 32 or 64.  Default 64 (order 3), 32 (order 4). */
+                                 nonzero stream.  8, 16, 32 or 64.  Default 64 (order 3), 32 (orders 4, 5). */
   uint32_t slice_threshold;   /* T_s of slc-split (Section IV-A): nonzeros one wavefront works
                                  through before it merges its partial rows; a slice of n nonzeros
                                  is shared by at most ceil(n/T_s)+1 wavefronts.  0 = sized from
@@ -77,8 +78,8 @@ typedef struct hbcsf_opts {
 typedef struct hbcsf_stats {
   uint64_t nnz;               /* M                                                            */
   uint64_t slices;            /* S: non-empty slices of this mode                             */
-  uint64_t fibers[2];         /* F per fiber level before fbr-split ([1] only for order 4)    */
-  uint64_t segments[2];       /* fiber segments per fiber level in the CSF group (F')         */
+  uint64_t fibers[HBCSF_MAX_FIBER_LEVELS];   /* F per fiber level (1 .. order-2) before fbr-split */
+  uint64_t segments[HBCSF_MAX_FIBER_LEVELS]; /* fiber segments per fiber level in the CSF group (F') */
   uint64_t group_nnz[3];      /* nonzeros in the COO, CSL, CSF groups                         */
   uint64_t group_slices[3];   /* slices in the COO, CSL, CSF groups                           */
   uint64_t shared_slices;     /* slices merged with atomic adds (they span several runs)      */
@@ -97,7 +98,7 @@ typedef struct hbcsf_stats {
 
 /* Builds the per-mode HB-CSF representations on the host (sort by mode, CSF, fbr-split,
  * slice classification into the COO / CSL / CSF groups, run tables for slc-split).
- *   order  3 or 4.         dims   host [order].          nnz  number of stored nonzeros (>= 0).
+ *   order  3, 4 or 5.      dims   host [order].          nnz  number of stored nonzeros (>= 0).
  *   inds   host [order] pointers to host [nnz] index arrays, inds[m][z] < dims[m].
  *   vals   host [nnz].     opts   host, may be NULL.
  *   out    receives the handle.  The inputs are not referenced after the call returns.

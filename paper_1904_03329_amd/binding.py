@@ -14,7 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhbcsf.so")
 
-HBCSF_MAX_ORDER = 4
+HBCSF_MAX_ORDER = 5
 ARR_IND, ARR_PTR, ARR_VAL, ARR_RUNFIRST, ARR_OWNED_BITS, ARR_COO_BITS, ARR_COO_PTR = 0, 1, 2, 3, 4, 5, 6
 TUNE_SLICE_THRESHOLD, TUNE_PROFILE, TUNE_WAVES_PER_CU, TUNE_STEPS, TUNE_KERNEL_MASK = 0, 1, 2, 3, 4
 TUNE_TRACE_BUFFER, TUNE_TRACE_CAPACITY, TUNE_PERSISTENT, TUNE_STREAM_BYTES, TUNE_FUSE_COO = 5, 6, 7, 8, 9
@@ -40,8 +40,8 @@ class hbcsf_opts(ctypes.Structure):
 
 class hbcsf_stats(ctypes.Structure):
     _fields_ = [
-        ("nnz", ctypes.c_uint64), ("slices", ctypes.c_uint64), ("fibers", ctypes.c_uint64 * 2),
-        ("segments", ctypes.c_uint64 * 2), ("group_nnz", ctypes.c_uint64 * 3),
+        ("nnz", ctypes.c_uint64), ("slices", ctypes.c_uint64), ("fibers", ctypes.c_uint64 * (HBCSF_MAX_ORDER - 2)),
+        ("segments", ctypes.c_uint64 * (HBCSF_MAX_ORDER - 2)), ("group_nnz", ctypes.c_uint64 * 3),
         ("group_slices", ctypes.c_uint64 * 3), ("shared_slices", ctypes.c_uint64),
         ("runs", ctypes.c_uint64 * 3), ("words_coo", ctypes.c_uint64), ("words_csf", ctypes.c_uint64),
         ("words_hbcsf", ctypes.c_uint64), ("stream_bytes", ctypes.c_uint64 * 3),

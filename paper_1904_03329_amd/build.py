@@ -33,7 +33,7 @@ def build(verbose: bool = False) -> str:
     # the kernels are compiled once per (lanes per row, order) pair, in parallel
     jobs = []
     for g in (2, 4, 8, 16, 32):
-        for n in (3, 4):
+        for n in (3, 4, 5):
             o = os.path.join(CSRC, f"hbcsf_kernels_g{g}_n{n}.o")
             defs = [f"-DHBCSF_G={g}", f"-DHBCSF_N={n}"] + (["-DHBCSF_WITH_DEFINE"] if (g, n) == (8, 3) else [])
             jobs.append(["hipcc"] + HIP_FLAGS + inc + defs + ["-c", os.path.join(CSRC, "hbcsf_kernels.hip"), "-o", o])

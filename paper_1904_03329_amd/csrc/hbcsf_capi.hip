@@ -69,7 +69,7 @@ int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint
                        const float* vals, const hbcsf_opts* opts, hbcsf_tensor** out) try {
   if (!out) return fail(HBCSF_EINVAL, "out is null");
   *out = nullptr;
-  if (order != 3 && order != 4) return fail(HBCSF_EINVAL, "order must be 3 or 4");
+  if (order < 3 || order > HBCSF_MAX_ORDER) return fail(HBCSF_EINVAL, "order must be 3, 4 or 5");
   if (!dims) return fail(HBCSF_EINVAL, "dims is null");
   if (nnz > 0 && (!inds || !vals)) return fail(HBCSF_EINVAL, "inds or vals is null");
   if (nnz >= 0xffff0000ull) return fail(HBCSF_ERANGE, "nnz must be below 2^32 - 2^16");
@@ -249,7 +249,7 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
         blocks = round_up8(b);
         a.unitsPerWave = 0;
       } else {
-        const int RW = N == 3 ? 4 : 8;
+        const int RW = N == 3 ? 4 : 8;  // LDS words per nonzero record
         const size_t ldsWave = (size_t)NG * (L + 1) * RW * 4;
         int wpb = 4;
         while (wpb > 1 && ldsWave * wpb > 48 * 1024) wpb >>= 1;

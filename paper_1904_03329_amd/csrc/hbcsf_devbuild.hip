@@ -428,7 +428,8 @@ uint64_t arena_bound(int N, const uint64_t* dims, uint64_t M, uint32_t L) {
 }
 
 int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* opts, hbcsf_opts* o, int* totalBits) {
-  if (order != 3 && order != 4) return fail(HBCSF_EINVAL, "order must be 3 or 4");
+  if (order != 3 && order != 4)
+    return fail(HBCSF_EINVAL, "the device-side builder handles orders 3 and 4 (order 5: hbcsf_build_format)");
   if (!dims) return fail(HBCSF_EINVAL, "dims is null");
   if (nnz >= 0xffff0000ull) return fail(HBCSF_ERANGE, "nnz must be below 2^32 - 2^16");
   int total = 0;
@@ -485,7 +486,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   out->rows = dims[mode];
   for (int l = 0; l < N; ++l) out->levelMode[l] = lv[l];
 
-  uint64_t S = 0, gS[3] = {0, 0, 0}, gM[3] = {0, 0, 0}, nSeg[2] = {0, 0}, fibNat[2] = {0, 0};
+  uint64_t S = 0, gS[3] = {0, 0, 0}, gM[3] = {0, 0, 0}, nSeg[HBCSF_MAX_FIBER_LEVELS] = {0, 0, 0}, fibNat[HBCSF_MAX_FIBER_LEVELS] = {0, 0, 0};
   unsigned long long hostCnt[kCounters];
   std::memset(hostCnt, 0, sizeof(hostCnt));
   HIP_TRY(hipMemsetAsync(w.cnt, 0, kCounters * 8, st), "hipMemsetAsync");
@@ -648,7 +649,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   HIP_TRY(hipGetLastError(), "format kernels");
   HIP_TRY(hipMemcpyAsync(hostCnt, w.cnt, kCounters * 8, hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
   HIP_TRY(hipStreamSynchronize(st), "hipStreamSynchronize");
-  const uint64_t fibNatCsf[2] = {hostCnt[2], hostCnt[3]};
+  const uint64_t fibNatCsf[HBCSF_MAX_FIBER_LEVELS] = {hostCnt[2], hostCnt[3], 0};
   fill_count_stats(out, N, M, S, fibNat, fibNatCsf, nSeg, gS, gM, hostCnt[1]);
   out->stats.owned_rows = hostCnt[4];
   for (int g = 0; g < 3; ++g)

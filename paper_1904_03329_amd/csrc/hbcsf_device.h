@@ -11,11 +11,11 @@ enum KernelKind { kCooKernel = 0, kCslKernel = 1, kCsfKernel = 2 };
 
 // Device pointers of one slice group of one mode, by tree level (0 = root .. order-1 = leaf).
 struct GroupArgs {
-  const uint32_t* ind[4];       // index arrays (per slice / segment / nonzero, by group kind)
-  const uint32_t* ptr[4];       // starts in the group's nonzero stream (n+1 entries)
-  const uint32_t* runFirst[4];  // slice / segment holding the first nonzero of each run
+  const uint32_t* ind[5];       // index arrays (per slice / segment / nonzero, by group kind)
+  const uint32_t* ptr[5];       // starts in the group's nonzero stream (n+1 entries)
+  const uint32_t* runFirst[5];  // slice / segment holding the first nonzero of each run
   const float* val;             // values in stream order
-  const float* fac[4];          // factor matrix of each tree level (fac[0] unused)
+  const float* fac[5];          // factor matrix of each tree level (fac[0] unused)
   float* out;                   // [rows][rank]
   uint32_t nnz;                 // nonzeros in the group
   uint32_t runs;                // ceil(nnz / L)
@@ -32,7 +32,7 @@ struct GroupArgs {
   uint32_t traceCapacity;       // records the buffer can hold
 };
 
-// kind: KernelKind; order 3 or 4; G = rank / 4 lanes per factor row (2, 4, 8, 16 or 32);
+// kind: KernelKind; order 3, 4 or 5; G = rank / 4 lanes per factor row (2, 4, 8, 16 or 32);
 // steps = records a lane group keeps in flight (4 or 8); wide = some gathered factor matrix
 // is 4 GiB or larger (64-bit row addressing).  One launch function per (G, order) pair, each
 // compiled in its own object file.  For the CSL and B-CSF kernels `blocks` is the number of compute
@@ -53,14 +53,20 @@ HBCSF_DECLARE_LAUNCH(4, 4)
 HBCSF_DECLARE_LAUNCH(8, 4)
 HBCSF_DECLARE_LAUNCH(16, 4)
 HBCSF_DECLARE_LAUNCH(32, 4)
+HBCSF_DECLARE_LAUNCH(2, 5)
+HBCSF_DECLARE_LAUNCH(4, 5)
+HBCSF_DECLARE_LAUNCH(8, 5)
+HBCSF_DECLARE_LAUNCH(16, 5)
+HBCSF_DECLARE_LAUNCH(32, 5)
 #undef HBCSF_DECLARE_LAUNCH
 
 inline hipError_t launch_group(int kind, int order, int G, int steps, bool wide, const GroupArgs& a,
                                uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s) {
 #define HBCSF_CASE(GV)                                                                              \
   case GV:                                                                                          \
-    return order == 3 ? launch_group_g##GV##_n3(kind, steps, wide, a, blocks, threads, ldsBytes, s) \
-                      : launch_group_g##GV##_n4(kind, steps, wide, a, blocks, threads, ldsBytes, s);
+    return order == 3   ? launch_group_g##GV##_n3(kind, steps, wide, a, blocks, threads, ldsBytes, s) \
+           : order == 4 ? launch_group_g##GV##_n4(kind, steps, wide, a, blocks, threads, ldsBytes, s) \
+                        : launch_group_g##GV##_n5(kind, steps, wide, a, blocks, threads, ldsBytes, s);
   switch (G) {
     HBCSF_CASE(2)
     HBCSF_CASE(4)
@@ -79,8 +85,9 @@ inline hipError_t launch_define_coo(int order, int G, bool wide, const GroupArgs
                                     uint32_t blocks, hipStream_t s) {
 #define HBCSF_CASE(GV)                                                                                     \
   case GV:                                                                                                 \
-    return order == 3 ? launch_define_coo_g##GV##_n3(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s) \
-                      : launch_define_coo_g##GV##_n4(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s);
+    return order == 3   ? launch_define_coo_g##GV##_n3(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s) \
+           : order == 4 ? launch_define_coo_g##GV##_n4(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s) \
+                        : launch_define_coo_g##GV##_n5(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s);
   switch (G) {
     HBCSF_CASE(2)
     HBCSF_CASE(4)

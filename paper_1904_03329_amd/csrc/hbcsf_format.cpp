@@ -180,24 +180,23 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   constexpr uint8_t kSplit = 3;  // CSL piece + CSF piece
   std::vector<uint8_t> grp(S);
   std::vector<uint32_t> nSingle(perFiber ? S : 0);
-  uint64_t fibNat[2] = {0, 0};
-  uint64_t fibNatCsf[2] = {0, 0};
+  constexpr int kFL = HBCSF_MAX_FIBER_LEVELS;
+  uint64_t fibNat[kFL] = {0, 0, 0};
+  uint64_t fibNatCsf[kFL] = {0, 0, 0};
   {
-    uint64_t f0 = 0, f1 = 0, c0 = 0, c1 = 0;
-#pragma omp parallel for schedule(dynamic, 512) reduction(+ : f0, f1, c0, c1)
+    uint64_t f0 = 0, f1 = 0, f2 = 0, c0 = 0, c1 = 0, c2 = 0;
+#pragma omp parallel for schedule(dynamic, 512) reduction(+ : f0, f1, f2, c0, c1, c2)
     for (int64_t s = 0; s < (int64_t)S; ++s) {
       const size_t b = sStart[s], e = sStart[s + 1];
-      uint64_t nf[2] = {0, 0};
-      for (size_t p = b; p < e; ++p) {
-        nf[0] += fresh(1, p);
-        if (NF == 2) nf[1] += fresh(2, p);
-      }
+      uint64_t nf[kFL] = {0, 0, 0};
+      for (size_t p = b; p < e; ++p)
+        for (int f = 0; f < NF; ++f) nf[f] += fresh(f + 1, p);
       const uint64_t n = e - b, deep = nf[NF - 1];
       uint8_t g;
       if (n == 1 && cooOn) g = kCoo;
       else if (deep == n && cslOn) g = kCsl;
       else g = kCsf;
-      uint64_t kept[2] = {nf[0], nf[1]};  // fibers that stay in the CSF group
+      uint64_t kept[kFL] = {nf[0], nf[1], nf[2]};  // fibers that stay in the CSF group
       if (perFiber && g == kCsf && n >= 2ull * L) {
         uint64_t ns = 0;
         for (size_t p = b; p < e; ++p) ns += single(p, e);
@@ -205,11 +204,10 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
           g = kSplit;
           nSingle[s] = (uint32_t)ns;
           // fibers of the CSF piece: a fiber level counts once per run of kept nonzeros that share it
-          kept[0] = kept[1] = 0;
-          bool pend[2] = {false, false};
+          kept[0] = kept[1] = kept[2] = 0;
+          bool pend[kFL] = {false, false, false};
           for (size_t p = b; p < e; ++p) {
-            pend[0] = pend[0] || fresh(1, p);
-            if (NF == 2) pend[1] = pend[1] || fresh(2, p);
+            for (int f = 0; f < NF; ++f) pend[f] = pend[f] || fresh(f + 1, p);
             if (single(p, e)) continue;
             for (int f = 0; f < NF; ++f) {
               kept[f] += pend[f];
@@ -221,9 +219,11 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
       grp[s] = g;
       f0 += nf[0];
       f1 += nf[1];
-      if (g == kCsf || g == kSplit) { c0 += kept[0]; c1 += kept[1]; }
+      f2 += nf[2];
+      if (g == kCsf || g == kSplit) { c0 += kept[0]; c1 += kept[1]; c2 += kept[2]; }
     }
-    fibNat[0] = f0; fibNat[1] = f1; fibNatCsf[0] = c0; fibNatCsf[1] = c1;
+    fibNat[0] = f0; fibNat[1] = f1; fibNat[2] = f2;
+    fibNatCsf[0] = c0; fibNatCsf[1] = c1; fibNatCsf[2] = c2;
   }
 
   // ---- position of each slice (piece) inside its group ----
@@ -252,29 +252,28 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
 
   // ---- count fiber segments of the CSF group (fbr-split on the run grid) ----
   // A segment starts at a kept nonzero that lies on the run grid or is the first kept one of its fiber.
-  std::vector<uint32_t> segOff[2];
-  uint64_t nSeg[2] = {0, 0};
+  std::vector<uint32_t> segOff[kFL];
+  uint64_t nSeg[kFL] = {0, 0, 0};
   for (int f = 0; f < NF; ++f) segOff[f].assign(S + 1, 0);
 #pragma omp parallel for schedule(dynamic, 512)
   for (int64_t s = 0; s < (int64_t)S; ++s) {
     if (grp[s] != kCsf && grp[s] != kSplit) continue;
     const size_t b = sStart[s], e = sStart[s + 1];
     const bool split = grp[s] == kSplit;
-    uint32_t c[2] = {0, 0};
+    uint32_t c[kFL] = {0, 0, 0};
     uint32_t pos = off[s];
-    bool pend[2] = {false, false};
+    bool pend[kFL] = {false, false, false};
     for (size_t p = b; p < e; ++p) {
-      pend[0] = pend[0] || fresh(1, p);
-      if (NF == 2) pend[1] = pend[1] || fresh(2, p);
+      for (int f = 0; f < NF; ++f) pend[f] = pend[f] || fresh(f + 1, p);
       if (split && single(p, e)) continue;
       const bool cut = (pos % L) == 0;
-      c[0] += cut || pend[0];
-      if (NF == 2) c[1] += cut || pend[1];
-      pend[0] = pend[1] = false;
+      for (int f = 0; f < NF; ++f) {
+        c[f] += cut || pend[f];
+        pend[f] = false;
+      }
       ++pos;
     }
-    segOff[0][s + 1] = c[0];
-    if (NF == 2) segOff[1][s + 1] = c[1];
+    for (int f = 0; f < NF; ++f) segOff[f][s + 1] = c[f];
   }
   for (int f = 0; f < NF; ++f) {
     uint64_t run = 0;
@@ -361,12 +360,12 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
         for (uint32_t r = (a + L - 1) / L; r <= (a + n - 1) / L; ++r) csfRun[0][r] = o;
         csfInd[0][o] = root | (own ? kOwnedBit : 0u);
         csfPtr[0][o] = a;
-        uint32_t f[2] = {segOff[0][s], NF == 2 ? segOff[1][s] : 0u};
+        uint32_t f[kFL] = {0, 0, 0};
+        for (int q = 0; q < NF; ++q) f[q] = segOff[q][s];
         uint32_t pos = a;
-        bool pend[2] = {false, false};
+        bool pend[kFL] = {false, false, false};
         for (size_t p = b; p < e; ++p) {
-          pend[0] = pend[0] || fresh(1, p);
-          if (NF == 2) pend[1] = pend[1] || fresh(2, p);
+          for (int q = 0; q < NF; ++q) pend[q] = pend[q] || fresh(q + 1, p);
           if (split && single(p, e)) continue;
           const bool cut = (pos % L) == 0;
           for (int l = 1; l <= NF; ++l) {
@@ -377,7 +376,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
               ++f[l - 1];
             }
           }
-          pend[0] = pend[1] = false;
+          pend[0] = pend[1] = pend[2] = false;
           csfInd[N - 1][pos] = idx(N - 1, p);
           csfVal[pos] = V[p];
           ++pos;

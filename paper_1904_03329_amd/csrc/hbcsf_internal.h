@@ -30,7 +30,7 @@ struct ArrayRef {
 //         every ptr indexes the group's nonzero stream; ind[order-1] per nonzero, val.
 struct GroupFormat {
   uint64_t nnz = 0;
-  uint64_t n[HBCSF_MAX_ORDER] = {0, 0, 0, 0};  // entries per level above the leaf
+  uint64_t n[HBCSF_MAX_ORDER] = {};            // entries per level above the leaf
   uint64_t runs = 0;                           // ceil(nnz / L)
   ArrayRef ind[HBCSF_MAX_ORDER];
   ArrayRef ptr[HBCSF_MAX_ORDER];
@@ -43,7 +43,7 @@ struct ModeFormat {
   int mode = 0;
   uint32_t L = 64;                 // run length = fiber threshold T_f
   bool cooRowFlags = false;        // the COO group has no root index array (rows come from cooBits / cooPtr)
-  int levelMode[HBCSF_MAX_ORDER] = {0, 0, 0, 0};
+  int levelMode[HBCSF_MAX_ORDER] = {};
   uint64_t rows = 0;               // dims[mode]
   GroupFormat g[3];
   ArrayRef ownedBits;
@@ -64,7 +64,7 @@ struct ModeFormat {
 // device) call this, so the two produce the same byte layout.  gS / gM: slices and nonzeros per group;
 // nSeg: fiber segments of the CSF group per fiber level.  Sets out->blobBytes.
 inline void layout_mode(ModeFormat* out, int N, const uint64_t gS[3], const uint64_t gM[3],
-                        const uint64_t nSeg[2]) {
+                        const uint64_t nSeg[HBCSF_MAX_FIBER_LEVELS]) {
   uint64_t bytes = 0;
   auto add = [&bytes](uint64_t count) {
     ArrayRef r;
@@ -114,8 +114,10 @@ inline void layout_mode(ModeFormat* out, int N, const uint64_t gS[3], const uint
 }
 
 // The statistics that follow from counts alone (call after layout_mode).
-inline void fill_count_stats(ModeFormat* out, int N, uint64_t M, uint64_t S, const uint64_t fibNat[2],
-                             const uint64_t fibNatCsf[2], const uint64_t nSeg[2], const uint64_t gS[3],
+inline void fill_count_stats(ModeFormat* out, int N, uint64_t M, uint64_t S,
+                             const uint64_t fibNat[HBCSF_MAX_FIBER_LEVELS],
+                             const uint64_t fibNatCsf[HBCSF_MAX_FIBER_LEVELS],
+                             const uint64_t nSeg[HBCSF_MAX_FIBER_LEVELS], const uint64_t gS[3],
                              const uint64_t gM[3], uint64_t sharedSlices) {
   hbcsf_stats& st = out->stats;
   st = hbcsf_stats{};
@@ -160,8 +162,8 @@ inline void fill_count_stats(ModeFormat* out, int N, uint64_t M, uint64_t S, con
 // vector registers, 8 KB of LDS records per wavefront).  Order 4 records are twice as large and the kernel holds
 // two fiber-level rows per step, so the same choice leaves 8 wavefronts per CU; runs of 32 and 4 gathers in
 // flight give 16 and were 25 % faster on a 50 M-nonzero order-4 tensor.
-inline uint32_t default_fiber_threshold(int order) { return order == 4 ? 32u : 64u; }
-inline int default_steps(int order) { return order == 4 ? 4 : 8; }
+inline uint32_t default_fiber_threshold(int order) { return order >= 4 ? 32u : 64u; }
+inline int default_steps(int order) { return order >= 4 ? 4 : 8; }
 
 // Tree levels of a mode's representation: the root is the mode itself, the others follow the policy
 // (0: shortest mode first, 1: longest first, 2: natural order).

@@ -182,7 +182,7 @@ __device__ __forceinline__ uint32_t mark_of_slice(uint32_t si) {
 // ---------------------------------------------------------------------------------------
 struct UnitBounds {
   uint32_t rf;      // lane t <= NG: slice holding the first nonzero of run r0 + t (clipped to runs)
-  uint32_t fHi[2];  // fiber levels 1, 2: first segment of the next unit (wave-uniform)
+  uint32_t fHi[3];  // fiber levels 1..3: first segment of the next unit (wave-uniform)
 };
 
 template <int G, int N, bool CSF>
@@ -191,7 +191,7 @@ __device__ __forceinline__ UnitBounds load_bounds(const GroupArgs& a, uint32_t u
   UnitBounds b;
   const uint32_t r0 = u * NG;
   b.rf = a.runFirst[0][min(r0 + (uint32_t)min(lane, NG), a.runs)];
-  b.fHi[0] = b.fHi[1] = 0;
+  b.fHi[0] = b.fHi[1] = b.fHi[2] = 0;
   if (CSF) {
     const uint32_t rN = min(r0 + NG, a.runs);
 #pragma unroll
@@ -209,14 +209,14 @@ struct UnitEnds {
 // fLo: first segment of this unit per fiber level (wave-uniform; = previous unit's fHi).
 template <int G, int N, int LS, bool CSF>
 __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __restrict__ rec, uint32_t u,
-                                               const UnitBounds& b, const uint32_t (&fLo)[2], int lane) {
+                                               const UnitBounds& b, const uint32_t (&fLo)[3], int lane) {
   constexpr int NG = 64 / G;
   constexpr int NF = N - 2;
   constexpr int RW = (N == 3) ? 4 : 8;
   constexpr int KV = 8;  // stream loads per lane issued together (covers 512 nonzeros)
   constexpr int KF = 4;  // segment loads per lane and level issued together (256 segments)
   constexpr int KS = 2;  // slice loads per lane issued together (128 slices)
-  constexpr int markWord = (N == 3) ? 3 : 4;
+  constexpr int markWord = (N == 3) ? 3 : N;  // slice mark: after the N-2 segment marks (B-CSF) / the value (CSL)
   constexpr uint32_t ls = LS, L = 1u << LS;
   constexpr uint32_t slots = (uint32_t)NG << LS;
   const uint32_t r0 = u * NG;
@@ -228,12 +228,13 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
   const uint32_t hs = __shfl(b.rf, g), ts = __shfl(b.rf, g + 1);
   const uint32_t headRaw = a.ind[0][hs], tailRaw = a.ind[0][ts];
   // -- issue: stream data
-  uint32_t w0[KV], w1[KV], w2[KV], w3[KV];
+  // B-CSF: w0 = leaf index, w1 = value.  CSL: w0..w(N-2) = the N-1 non-root indices, w(N-1) = value.
+  uint32_t w0[KV], w1[KV], w2[KV], w3[KV], w4[KV];
   if (z0 + slots <= a.nnz) {  // wave-uniform: every slot of the unit holds a nonzero
 #pragma unroll
     for (int t = 0; t < KV; ++t) {
       const uint32_t p = (uint32_t)t * 64u + lane;
-      w0[t] = w1[t] = w2[t] = w3[t] = 0;
+      w0[t] = w1[t] = w2[t] = w3[t] = w4[t] = 0;
       if ((uint32_t)t * 64u < slots) {
         if (CSF) {
           w0[t] = __builtin_nontemporal_load(a.ind[N - 1] + z0 + p);
@@ -241,8 +242,9 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
         } else {
           w0[t] = __builtin_nontemporal_load(a.ind[1] + z0 + p);
           w1[t] = __builtin_nontemporal_load(a.ind[2] + z0 + p);
-          if (N == 4) w2[t] = __builtin_nontemporal_load(a.ind[3] + z0 + p);
-          w3[t] = __builtin_nontemporal_load(valb + z0 + p);
+          if (N >= 4) w2[t] = __builtin_nontemporal_load(a.ind[3] + z0 + p);
+          if (N >= 5) w3[t] = __builtin_nontemporal_load(a.ind[4] + z0 + p);
+          (N == 3 ? w2[t] : N == 4 ? w3[t] : w4[t]) = __builtin_nontemporal_load(valb + z0 + p);
         }
       }
     }
@@ -251,7 +253,7 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
     for (int t = 0; t < KV; ++t) {
       const uint32_t p = (uint32_t)t * 64u + lane;
       const uint32_t z = z0 + p;
-      w0[t] = w1[t] = w2[t] = w3[t] = 0;
+      w0[t] = w1[t] = w2[t] = w3[t] = w4[t] = 0;
       if (p < slots && z < a.nnz) {
         if (CSF) {
           w0[t] = __builtin_nontemporal_load(a.ind[N - 1] + z);
@@ -259,14 +261,15 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
         } else {
           w0[t] = __builtin_nontemporal_load(a.ind[1] + z);
           w1[t] = __builtin_nontemporal_load(a.ind[2] + z);
-          if (N == 4) w2[t] = __builtin_nontemporal_load(a.ind[3] + z);
-          w3[t] = __builtin_nontemporal_load(valb + z);
+          if (N >= 4) w2[t] = __builtin_nontemporal_load(a.ind[3] + z);
+          if (N >= 5) w3[t] = __builtin_nontemporal_load(a.ind[4] + z);
+          (N == 3 ? w2[t] : N == 4 ? w3[t] : w4[t]) = __builtin_nontemporal_load(valb + z);
         }
       }
     }
   }
   // -- issue: fiber-segment ends and indices
-  uint32_t fe[2][KF], fi[2][KF];
+  uint32_t fe[3][KF], fi[3][KF];
   if (CSF) {
 #pragma unroll
     for (int l = 1; l <= NF; ++l) {
@@ -305,18 +308,18 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
       uint4* dst = reinterpret_cast<uint4*>(rec + (size_t)(p + (p >> ls)) * RW);
       if (CSF) {
         dst[0] = make_uint4(w0[t], w1[t], 0u, 0u);
-        if (N == 4) dst[1] = make_uint4(0u, 0u, 0u, 0u);
+        if (N >= 4) dst[1] = make_uint4(0u, 0u, 0u, 0u);
       } else if (N == 3) {
-        dst[0] = make_uint4(w0[t], w1[t], w3[t], 0u);
+        dst[0] = make_uint4(w0[t], w1[t], w2[t], 0u);
       } else {
         dst[0] = make_uint4(w0[t], w1[t], w2[t], w3[t]);
-        dst[1] = make_uint4(0u, 0u, 0u, 0u);
+        dst[1] = make_uint4(N == 5 ? w4[t] : 0u, 0u, 0u, 0u);
       }
     }
   }
   for (uint32_t p = (uint32_t)KV * 64u + lane; p < slots; p += 64) {  // units above 512 nonzeros
     const uint32_t z = z0 + p;
-    uint32_t x0 = 0, x1 = 0, x2 = 0, x3 = 0;
+    uint32_t x0 = 0, x1 = 0, x2 = 0, x3 = 0, x4 = 0;
     if (z < a.nnz) {
       if (CSF) {
         x0 = a.ind[N - 1][z];
@@ -324,19 +327,20 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
       } else {
         x0 = a.ind[1][z];
         x1 = a.ind[2][z];
-        if (N == 4) x2 = a.ind[3][z];
-        x3 = valb[z];
+        if (N >= 4) x2 = a.ind[3][z];
+        if (N >= 5) x3 = a.ind[4][z];
+        (N == 3 ? x2 : N == 4 ? x3 : x4) = valb[z];
       }
     }
     uint4* dst = reinterpret_cast<uint4*>(rec + (size_t)(p + (p >> ls)) * RW);
     if (CSF) {
       dst[0] = make_uint4(x0, x1, 0u, 0u);
-      if (N == 4) dst[1] = make_uint4(0u, 0u, 0u, 0u);
+      if (N >= 4) dst[1] = make_uint4(0u, 0u, 0u, 0u);
     } else if (N == 3) {
-      dst[0] = make_uint4(x0, x1, x3, 0u);
+      dst[0] = make_uint4(x0, x1, x2, 0u);
     } else {
       dst[0] = make_uint4(x0, x1, x2, x3);
-      dst[1] = make_uint4(0u, 0u, 0u, 0u);
+      dst[1] = make_uint4(N == 5 ? x4 : 0u, 0u, 0u, 0u);
     }
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -419,9 +423,10 @@ __global__ __launch_bounds__(256) void define_rows_kernel(float4* __restrict__ o
 #endif  // HBCSF_WITH_DEFINE
 
 // ---------------------------------------------------------------------------------------
-// B-CSF group.  N = tensor order (3 or 4); G = lanes per factor row.
+// B-CSF group.  N = tensor order (3, 4 or 5); G = lanes per factor row.
 // LDS record per nonzero: N = 3: {leaf, val, seg1 mark, slice mark};
-//                         N = 4: {leaf, val, seg2 mark, seg1 mark, slice mark, -, -, -}.
+//                         N = 4: {leaf, val, seg2 mark, seg1 mark, slice mark, -, -, -};
+//                         N = 5: {leaf, val, seg3 mark, seg2 mark, seg1 mark, slice mark, -, -}.
 // A segment mark is index+1 at the segment's last nonzero, else 0.  A slice mark is
 // (row+1) | owned bit at the slice's last nonzero, else 0.
 // ---------------------------------------------------------------------------------------
@@ -441,7 +446,8 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
 
   const float* __restrict__ facLeaf = a.fac[N - 1];
   const float* __restrict__ facDeep = a.fac[N - 2];   // deepest fiber level
-  const float* __restrict__ facTop = a.fac[1];        // level 1 (same as facDeep when N = 3)
+  const float* __restrict__ facNext = a.fac[N >= 4 ? N - 3 : 1];  // the fiber level above it (N >= 4)
+  const float* __restrict__ facTop = a.fac[1];        // level 1 (N = 5: the third fiber level from the leaf)
 
   const unsigned long long traceStart = a.trace ? wall_clock64() : 0ull;
   const SpanWalk walk = span_walk(a, wib, wpb);
@@ -453,7 +459,7 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
   uint32_t pendRow = 0;
 
   UnitBounds cur = load_bounds<G, N, true>(a, u, lane);
-  uint32_t fLo[2] = {0, 0};
+  uint32_t fLo[3] = {0, 0, 0};
 #pragma unroll
   for (int l = 1; l <= NF; ++l) fLo[l - 1] = a.runFirst[l][u * NG];
 
@@ -464,6 +470,7 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
     const uint32_t headRow = ends.headRow, tailRow = ends.tailRow, ng = ends.ng;
     fLo[0] = cur.fHi[0];
     fLo[1] = cur.fHi[1];
+    fLo[2] = cur.fHi[2];
     cur = nxt;
 
     if (ng > 0) {
@@ -471,18 +478,33 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
         row_atomic<G>(a.out, pendRow, c, acc);
         acc = f4zero();
       }
+      // tmp: sum over the leaves of the open deepest-level segment; tmp1 / tmp2: sums over the closed segments
+      // of the next levels up (N >= 4 / N = 5); acc: the slice's row.  Marks are nested: a segment of a level
+      // can only end where one of every deeper level ends.
       float4 tmp = f4zero();
       float4 tmp1 = f4zero();
+      float4 tmp2 = f4zero();
       const uint32_t* myrec = rec + (size_t)g * (L + 1) * RW;
       for (uint32_t sb = 0; sb < L; sb += kSteps) {
         uint4 rr[kSteps];
-        uint32_t mi[kSteps];
-        float4 cr[kSteps], br[kSteps], ar[kSteps];
+        uint32_t m1[kSteps];   // N = 5: mark of fiber level 1
+        uint32_t mi[kSteps];   // slice mark
+        float4 cr[kSteps], br[kSteps], nr[kSteps], ar[kSteps];
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
           const uint4* src = reinterpret_cast<const uint4*>(myrec + (size_t)(sb + t) * RW);
           rr[t] = src[0];
-          mi[t] = (N == 3) ? rr[t].w : reinterpret_cast<const uint32_t*>(src)[4];
+          if (N == 3) {
+            mi[t] = rr[t].w;
+            m1[t] = 0;
+          } else if (N == 4) {
+            mi[t] = reinterpret_cast<const uint32_t*>(src)[4];
+            m1[t] = 0;
+          } else {
+            const uint2 hi = reinterpret_cast<const uint2*>(src)[2];
+            m1[t] = hi.x;
+            mi[t] = hi.y;
+          }
         }
         // Conditional loads first: loads return in order, so once a leaf row has arrived every
         // load issued before it has arrived too, and the leaf rows can be awaited one by one.
@@ -492,9 +514,13 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
             br[t] = (a.streamLevel & (1u << (N - 2))) ? row_load_streaming<G, WIDE>(facDeep, rr[t].z - 1u, c)
                                                        : row_load<G, WIDE>(facDeep, rr[t].z - 1u, c);
           }
-          if (N == 4 && rr[t].w) {
-            ar[t] = (a.streamLevel & 2u) ? row_load_streaming<G, WIDE>(facTop, rr[t].w - 1u, c)
-                                         : row_load<G, WIDE>(facTop, rr[t].w - 1u, c);
+          if (N >= 4 && rr[t].w) {
+            nr[t] = (a.streamLevel & (1u << (N - 3))) ? row_load_streaming<G, WIDE>(facNext, rr[t].w - 1u, c)
+                                                       : row_load<G, WIDE>(facNext, rr[t].w - 1u, c);
+          }
+          if (N == 5 && m1[t]) {
+            ar[t] = (a.streamLevel & 2u) ? row_load_streaming<G, WIDE>(facTop, m1[t] - 1u, c)
+                                         : row_load<G, WIDE>(facTop, m1[t] - 1u, c);
           }
         }
 #pragma unroll
@@ -508,7 +534,15 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
             } else {
               fma4(tmp1, tmp, br[t]);
               if (rr[t].w) {
-                fma4(acc, tmp1, ar[t]);
+                if (N == 4) {
+                  fma4(acc, tmp1, nr[t]);
+                } else {
+                  fma4(tmp2, tmp1, nr[t]);
+                  if (m1[t]) {
+                    fma4(acc, tmp2, ar[t]);
+                    tmp2 = f4zero();
+                  }
+                }
                 tmp1 = f4zero();
               }
             }
@@ -523,7 +557,7 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
         }
       }
       // the run leaves a partial row behind unless its last nonzero ends a slice
-      pend = myrec[(size_t)(ng - 1) * RW + (N == 3 ? 3 : 4)] == 0u;
+      pend = myrec[(size_t)(ng - 1) * RW + (N == 3 ? 3 : N)] == 0u;
       pendRow = tailRow;
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -551,7 +585,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
 // ---------------------------------------------------------------------------------------
 // CSL group (Algorithm "CSL-MTTKRP"): every nonzero carries all its non-root indices; the
 // slice pointer goes straight to the nonzeros.
-// LDS record: N = 3: {j, k, val, slice mark}; N = 4: {a, b, l, val, slice mark, -, -, -}.
+// LDS record: N = 3: {j, k, val, slice mark}; N = 4: {a, b, l, val, slice mark, -, -, -};
+//             N = 5: {a, b, c, l, val, slice mark, -, -}.
 // ---------------------------------------------------------------------------------------
 template <int G, int N, int LS, int kSteps, bool WIDE>
 __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
@@ -576,7 +611,7 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
   uint32_t pendRow = 0;
 
   UnitBounds cur = load_bounds<G, N, false>(a, u, lane);
-  const uint32_t fLo[2] = {0, 0};
+  const uint32_t fLo[3] = {0, 0, 0};
 
   for (; u < uEnd; ++u) {
     const UnitBounds nxt = load_bounds<G, N, false>(a, min(u + 1, a.nUnits - 1), lane);
@@ -592,25 +627,38 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
       const uint32_t* myrec = rec + (size_t)g * (L + 1) * RW;
       for (uint32_t sb = 0; sb < L; sb += kSteps) {
         uint4 rr[kSteps];
-        uint32_t mi[kSteps];
-        float4 x1[kSteps], x2[kSteps], x3[kSteps];
+        uint32_t vv[kSteps];   // value bits
+        uint32_t mi[kSteps];   // slice mark
+        float4 x1[kSteps], x2[kSteps], x3[kSteps], x4[kSteps];
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
           const uint4* src = reinterpret_cast<const uint4*>(myrec + (size_t)(sb + t) * RW);
           rr[t] = src[0];
-          mi[t] = (N == 3) ? rr[t].w : reinterpret_cast<const uint32_t*>(src)[4];
+          if (N == 3) {
+            vv[t] = rr[t].z;
+            mi[t] = rr[t].w;
+          } else if (N == 4) {
+            vv[t] = rr[t].w;
+            mi[t] = reinterpret_cast<const uint32_t*>(src)[4];
+          } else {
+            const uint2 hi = reinterpret_cast<const uint2*>(src)[2];
+            vv[t] = hi.x;
+            mi[t] = hi.y;
+          }
         }
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
           x1[t] = row_load<G, WIDE>(a.fac[1], rr[t].x, c);
           x2[t] = row_load<G, WIDE>(a.fac[2], rr[t].y, c);
-          if (N == 4) x3[t] = row_load<G, WIDE>(a.fac[3], rr[t].z, c);
+          if (N >= 4) x3[t] = row_load<G, WIDE>(a.fac[3], rr[t].z, c);
+          if (N >= 5) x4[t] = row_load<G, WIDE>(a.fac[4], rr[t].w, c);
         }
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
           float4 pr = mul4(x1[t], x2[t]);
-          if (N == 4) pr = mul4(pr, x3[t]);
-          fma4(acc, __uint_as_float(N == 3 ? rr[t].z : rr[t].w), pr);
+          if (N >= 4) pr = mul4(pr, x3[t]);
+          if (N >= 5) pr = mul4(pr, x4[t]);
+          fma4(acc, __uint_as_float(vv[t]), pr);
           if (mi[t]) {
             const uint32_t row = (mi[t] & 0x7fffffffu) - 1u;
             if (mi[t] & 0x80000000u) row_store<G>(a.out, row, c, acc);
@@ -620,7 +668,7 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
         }
       }
       // the run leaves a partial row behind unless its last nonzero ends a slice
-      pend = myrec[(size_t)(ng - 1) * RW + (N == 3 ? 3 : 4)] == 0u;
+      pend = myrec[(size_t)(ng - 1) * RW + (N == 3 ? 3 : N)] == 0u;
       pendRow = tailRow;
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -648,19 +696,20 @@ __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
   // (coalesced), then lane group g takes nonzero base + step*NG + g from lane step*NG + g.
   for (uint64_t base = (uint64_t)wave * 64u; base < a.nnz; base += (uint64_t)waves * 64u) {
     const uint64_t z = base + lane;
-    uint32_t m0 = 0, m1 = 0, m2 = 0, m3 = 0, mv = 0;
+    uint32_t m0 = 0, m1 = 0, m2 = 0, m3 = 0, m4 = 0, mv = 0;
     if (z < a.nnz) {
       m0 = __builtin_nontemporal_load(a.ind[0] + z);
       m1 = __builtin_nontemporal_load(a.ind[1] + z);
       m2 = __builtin_nontemporal_load(a.ind[2] + z);
-      if (N == 4) m3 = __builtin_nontemporal_load(a.ind[3] + z);
+      if (N >= 4) m3 = __builtin_nontemporal_load(a.ind[3] + z);
+      if (N >= 5) m4 = __builtin_nontemporal_load(a.ind[4] + z);
       mv = __builtin_nontemporal_load(valb + z);
     }
     const uint32_t left = (uint32_t)min((uint64_t)64, a.nnz - base);
 #pragma unroll
     for (int sb = 0; sb < G; sb += kU) {
       uint32_t i0[kU], v[kU];
-      float4 x1[kU], x2[kU], x3[kU];
+      float4 x1[kU], x2[kU], x3[kU], x4[kU];
       bool ok[kU];
 #pragma unroll
       for (int t = 0; t < kU; ++t) {
@@ -669,18 +718,21 @@ __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
         i0[t] = __shfl(m0, src);
         v[t] = __shfl(mv, src);
         const uint32_t i1 = __shfl(m1, src), i2 = __shfl(m2, src);
-        const uint32_t i3 = N == 4 ? __shfl(m3, src) : 0u;
+        const uint32_t i3 = N >= 4 ? __shfl(m3, src) : 0u;
+        const uint32_t i4 = N >= 5 ? __shfl(m4, src) : 0u;
         if (ok[t]) {
           x1[t] = row_load<G, WIDE>(a.fac[1], i1, c);
           x2[t] = row_load<G, WIDE>(a.fac[2], i2, c);
-          if (N == 4) x3[t] = row_load<G, WIDE>(a.fac[3], i3, c);
+          if (N >= 4) x3[t] = row_load<G, WIDE>(a.fac[3], i3, c);
+          if (N >= 5) x4[t] = row_load<G, WIDE>(a.fac[4], i4, c);
         }
       }
 #pragma unroll
       for (int t = 0; t < kU; ++t) {
         if (ok[t]) {
           float4 pr = mul4(x1[t], x2[t]);
-          if (N == 4) pr = mul4(pr, x3[t]);
+          if (N >= 4) pr = mul4(pr, x3[t]);
+          if (N >= 5) pr = mul4(pr, x4[t]);
           row_store<G>(a.out, i0[t], c, scale4(__uint_as_float(v[t]), pr));
         }
       }
@@ -716,7 +768,7 @@ __global__ __launch_bounds__(256) void define_coo_kernel(const GroupArgs a, cons
     const uint32_t zBase = cooPtr[wd];
 #pragma unroll
     for (int qb = 0; qb < RPG; qb += CH) {
-      uint32_t i1[CH], i2[CH], i3[CH], v[CH];
+      uint32_t i1[CH], i2[CH], i3[CH], i4[CH], v[CH];
       bool isCoo[CH], fill[CH];
 #pragma unroll
       for (int q = 0; q < CH; ++q) {
@@ -724,22 +776,24 @@ __global__ __launch_bounds__(256) void define_coo_kernel(const GroupArgs a, cons
         const uint64_t row = (wd << 5) + bit;
         isCoo[q] = ((wc >> bit) & 1u) != 0u;
         fill[q] = row < rows && !isCoo[q] && ((wo >> bit) & 1u) == 0u;
-        i1[q] = i2[q] = i3[q] = v[q] = 0;
+        i1[q] = i2[q] = i3[q] = i4[q] = v[q] = 0;
         if (isCoo[q]) {
           const uint32_t z = zBase + (uint32_t)__builtin_popcount(wc & ((1u << bit) - 1u));
           i1[q] = a.ind[1][z];
           i2[q] = a.ind[2][z];
-          if (N == 4) i3[q] = a.ind[3][z];
+          if (N >= 4) i3[q] = a.ind[3][z];
+          if (N >= 5) i4[q] = a.ind[4][z];
           v[q] = valb[z];
         }
       }
-      float4 x1[CH], x2[CH], x3[CH];
+      float4 x1[CH], x2[CH], x3[CH], x4[CH];
 #pragma unroll
       for (int q = 0; q < CH; ++q) {
         if (isCoo[q]) {
           x1[q] = row_load<G, WIDE>(a.fac[1], i1[q], c);
           x2[q] = row_load<G, WIDE>(a.fac[2], i2[q], c);
-          if (N == 4) x3[q] = row_load<G, WIDE>(a.fac[3], i3[q], c);
+          if (N >= 4) x3[q] = row_load<G, WIDE>(a.fac[3], i3[q], c);
+          if (N >= 5) x4[q] = row_load<G, WIDE>(a.fac[4], i4[q], c);
         }
       }
 #pragma unroll
@@ -748,7 +802,8 @@ __global__ __launch_bounds__(256) void define_coo_kernel(const GroupArgs a, cons
         float4* dst = reinterpret_cast<float4*>(a.out + (((wd << 5) + bit) * (uint64_t)(4 * G) + (uint64_t)(4 * c)));
         if (isCoo[q]) {
           float4 pr = mul4(x1[q], x2[q]);
-          if (N == 4) pr = mul4(pr, x3[q]);
+          if (N >= 4) pr = mul4(pr, x3[q]);
+          if (N >= 5) pr = mul4(pr, x4[q]);
           store_streaming(dst, scale4(__uint_as_float(v[q]), pr));
         } else if (fill[q]) {
           store_streaming(dst, f4zero());

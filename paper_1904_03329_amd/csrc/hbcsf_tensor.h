@@ -12,7 +12,7 @@
 
 struct hbcsf_tensor {
   int order = 0;
-  uint64_t dims[HBCSF_MAX_ORDER] = {0, 0, 0, 0};
+  uint64_t dims[HBCSF_MAX_ORDER] = {};
   uint64_t nnz = 0;
   double normSq = 0.0;  // sum of the squared values (for the CPD fit)
   hbcsf_opts opts{};

@@ -77,7 +77,8 @@ def test_storage_and_operation_closed_forms():
     B.free(h)
 
 
-@pytest.mark.parametrize("dims,nnz", [((30, 20, 25), 1500), ((12, 9, 10, 7), 1200), ((40, 3, 500), 900)])
+@pytest.mark.parametrize("dims,nnz", [((30, 20, 25), 1500), ((12, 9, 10, 7), 1200), ((40, 3, 500), 900),
+                                      ((9, 6, 7, 5, 4), 1500)])
 @pytest.mark.parametrize("tf", [8, 32])
 def test_round_trip_and_structure(dims, nnz, tf):
     rng = np.random.default_rng(len(dims) * 100 + tf)
@@ -143,7 +144,7 @@ def test_round_trip_and_structure(dims, nnz, tf):
 
 
 @pytest.mark.parametrize("dims,nnz,rank", [((30, 20, 25), 1500, 8), ((12, 9, 10, 7), 1200, 8), ((5, 400, 6), 1000, 32),
-                                           ((9, 8, 7, 6), 700, 32)])
+                                           ((9, 8, 7, 6), 700, 32), ((8, 6, 7, 5, 4), 1500, 8), ((6, 5, 4, 3, 50), 900, 32)])
 @pytest.mark.parametrize("opts", [dict(), dict(fiber_threshold=8), dict(group_mask=4), dict(group_mask=1),
                                   dict(group_mask=2, mode_order_policy=1)])
 def test_cpu_walks_match_oracle(oracle, dims, nnz, rank, opts):

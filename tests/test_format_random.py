@@ -10,8 +10,8 @@ from paper_1904_03329_amd import binding as B
 
 @st.composite
 def tensors(draw):
-    order = draw(st.sampled_from([3, 4]))
-    dims = tuple(draw(st.integers(1, 12)) for _ in range(order))
+    order = draw(st.sampled_from([3, 4, 5]))
+    dims = tuple(draw(st.integers(1, 12 if order < 5 else 6)) for _ in range(order))
     nnz = draw(st.integers(0, 300))
     seed = draw(st.integers(0, 2**31 - 1))
     skew = draw(st.booleans())

@@ -95,6 +95,14 @@ def test_one_iteration_fourth_order(rank):
     _check(dims, inds, vals, facs, rank)
 
 
+def test_one_iteration_fifth_order():
+    rng = np.random.default_rng(555)
+    dims = (70, 33, 17, 9, 5)
+    inds, vals = _random_tensor(rng, dims, 30000)
+    facs = [rng.uniform(-1, 1, size=(d, 16)).astype(np.float32) for d in dims]
+    _check(dims, inds, vals, facs, 16)
+
+
 def test_three_iterations_reuse_gram_matrices():
     rng = np.random.default_rng(300)
     dims = (400, 300, 200)

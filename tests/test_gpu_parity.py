@@ -40,7 +40,8 @@ def test_cfg1_every_element(oracle, synth):
 
 
 @pytest.mark.parametrize("rank", [8, 16, 32, 64, 128])
-@pytest.mark.parametrize("dims,nnz", [((3000, 700, 90), 60_000), ((900, 300, 40, 25), 50_000)])
+@pytest.mark.parametrize("dims,nnz", [((3000, 700, 90), 60_000), ((900, 300, 40, 25), 50_000),
+                                      ((600, 200, 30, 12, 8), 50_000)])
 def test_ranks_and_orders(oracle, dims, nnz, rank):
     rng = np.random.default_rng(rank * 10 + len(dims))
     inds, vals = _skewed(rng, dims, nnz)
@@ -55,7 +56,8 @@ def test_ranks_and_orders(oracle, dims, nnz, rank):
                                   dict(mode_order_policy=2), dict(tune_ts=256), dict(tune_ts=100_000),
                                   dict(hybrid_granularity=1), dict(hybrid_granularity=1, fiber_threshold=8),
                                   dict(coo_row_flags=1)])
-@pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000)])
+@pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000),
+                                      ((1500, 80, 20, 9, 6), 90_000)])
 def test_build_options_do_not_change_the_result(oracle, dims, nnz, opts):
     rng = np.random.default_rng(len(dims) + 7)
     inds, vals = _skewed(rng, dims, nnz)
@@ -252,8 +254,8 @@ def test_launch_variants_and_diagnostics(oracle):
 def test_random_small_tensors(oracle, seed):
     """Small random tensors with duplicates, empty slices and every option drawn at random."""
     rng = np.random.default_rng(1000 + seed)
-    order = int(rng.choice([3, 4]))
-    dims = tuple(int(x) for x in rng.integers(1, 60, size=order))
+    order = int(rng.choice([3, 4, 5]))
+    dims = tuple(int(x) for x in rng.integers(1, 60 if order < 5 else 25, size=order))
     nnz = int(rng.integers(0, 6000))
     inds = [rng.integers(0, d, size=nnz).astype(np.uint32) for d in dims]
     vals = rng.uniform(-1, 1, size=nnz).astype(np.float32)
