@@ -271,9 +271,19 @@ int hbcsf_gram(const float *a, uint64_t rows, int rank, void *workspace, uint64_
  * their streams; calls one after the other need no clearing in between. */
 int hbcsf_gram_noalloc(const float *a, uint64_t rows, int rank, double *s, void *hip_stream);
 
+#define HBCSF_ALS_LAZY_NORMALISATION 2 /* flag: the column normalisation that closes an iteration of
+                                  Algorithm "CPD-ALS" may be put off: on return factors[m] can hold the
+                                  unit-norm factor with column r multiplied by a norm the state remembers
+                                  (lambda, the fit and the state's Gram matrices are those of the normalised
+                                  factors either way).  At rank 32 the product kernel then also forms the
+                                  new factor's Gram matrix, so the MTTKRP result is read once per mode
+                                  update instead of twice.  A later call without the flag, or
+                                  hbcsf_als_normalise, writes the unit-norm factors.  Use together with
+                                  HBCSF_ALS_KEEP_GRAMS on the calls that follow.                        */
+
 /* Device workspace an ALS state needs for this tensor and rank: one [max dim][rank] fp32 matrix
- * for the MTTKRP result, two rank x rank matrices and the Gram computation's scratch
- * (hbcsf_gram_workspace_bytes). */
+ * for the MTTKRP result, two rank x rank matrices, one [rank] vector per mode and the Gram
+ * computation's scratch (hbcsf_gram_workspace_bytes). */
 int hbcsf_als_workspace_bytes(const hbcsf_tensor *t, int rank, uint64_t *bytes);
 
 /* Creates an ALS state for an uploaded tensor.  workspace: device memory, 256-byte aligned, at
@@ -288,16 +298,24 @@ int hbcsf_als_create(const hbcsf_tensor *t, int rank, void *workspace, uint64_t 
  * fp32 row-major, read and overwritten in place (factors[0]'s content on entry is not used, as in
  * the algorithm).  lambda: device [rank] fp32, written; may be null.  fit: host, may be null;
  * receives 1 - ||X - model|| / ||X|| computed from the Gram matrices and the last MTTKRP (the
- * nonzero coordinates are taken to be distinct).  flags: 0 or HBCSF_ALS_KEEP_GRAMS.
+ * nonzero coordinates are taken to be distinct).  flags: 0 or any of HBCSF_ALS_KEEP_GRAMS,
+ * HBCSF_ALS_LAZY_NORMALISATION.
  * Blocking: the host reads an R x R matrix back for every mode, so the call returns after the
  * work on hip_stream has finished.  Two calls on one state must not overlap.  Errors: EINVAL,
  * and whatever hbcsf_mttkrp reports. */
 int hbcsf_als_iteration(hbcsf_als *a, float *const *factors, float *lambda, int flags, double *fit,
                         void *hip_stream);
 
+/* Carries out the column normalisation that calls with HBCSF_ALS_LAZY_NORMALISATION put off: every
+ * factor whose columns still carry a remembered norm is scaled in place (one pass each), after which
+ * factors[m] are the unit-norm factors that match the last lambda.  factors: as left by the last
+ * hbcsf_als_iteration on this state.  Blocking.  No effect when nothing is pending. */
+int hbcsf_als_normalise(hbcsf_als *a, float *const *factors, void *hip_stream);
+
 /* The algorithm's outer loop: iterations until the fit changes by less than `tolerance` between two
  * consecutive iterations, or `max_iterations` (>= 1) are done.  The first iteration computes the
- * factors' Gram matrices, the later ones carry them over.  iterations_done, fit: host, may be null.
+ * factors' Gram matrices, the later ones carry them over; the normalisation is put off inside the loop
+ * and carried out once at its end.  iterations_done, fit: host, may be null.
  * Other arguments and errors as hbcsf_als_iteration. */
 int hbcsf_als_run(hbcsf_als *a, float *const *factors, float *lambda, int max_iterations,
                   double tolerance, int *iterations_done, double *fit, void *hip_stream);

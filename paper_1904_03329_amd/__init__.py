@@ -120,8 +120,9 @@ class CpdAls:
         self.handle = binding.als_create(tensor.handle, self.rank, self._ws.data_ptr(), n)
         self.lam = torch.ones(self.rank, dtype=torch.float32, device="cuda")
 
-    def iteration(self, factors, keep_grams: bool = False) -> float:
-        """Updates the CUDA float32 factor matrices in place, stores lambda in self.lam, returns the fit."""
+    def iteration(self, factors, keep_grams: bool = False, lazy: bool = False) -> float:
+        """Updates the CUDA float32 factor matrices in place, stores lambda in self.lam, returns the fit.
+        lazy: the closing column normalisation may be put off (see normalise)."""
         import torch
 
         for m, f in enumerate(factors):
@@ -129,8 +130,15 @@ class CpdAls:
                     or tuple(f.shape) != (self.tensor.dims[m], self.rank)):
                 raise ValueError(f"factor {m} must be a contiguous float32 CUDA tensor [{self.tensor.dims[m]}, {self.rank}]")
         return binding.als_iteration(self.handle, [f.data_ptr() for f in factors], self.lam.data_ptr(),
-                                     binding.ALS_KEEP_GRAMS if keep_grams else 0, True,
+                                     (binding.ALS_KEEP_GRAMS if keep_grams else 0)
+                                     | (binding.ALS_LAZY_NORMALISATION if lazy else 0), True,
                                      torch.cuda.current_stream().cuda_stream)
+
+    def normalise(self, factors):
+        """Writes the unit-norm factors after iterations with lazy=True."""
+        import torch
+
+        binding.als_normalise(self.handle, [f.data_ptr() for f in factors], torch.cuda.current_stream().cuda_stream)
 
     def run(self, factors, max_iterations: int = 50, tolerance: float = 1e-5):
         """Iterates until the fit changes by less than `tolerance`; returns (iterations done, fit)."""

@@ -21,12 +21,13 @@ TUNE_TRACE_BUFFER, TUNE_TRACE_CAPACITY, TUNE_PERSISTENT, TUNE_STREAM_BYTES, TUNE
 GROUP_COO, GROUP_CSL, GROUP_CSF = 0, 1, 2
 OWNED_BIT = 0x80000000
 ALS_KEEP_GRAMS = 1
+ALS_LAZY_NORMALISATION = 2
 
 EXPORTS = (
     "hbcsf_build_format", "hbcsf_device_bytes", "hbcsf_upload", "hbcsf_mttkrp", "hbcsf_get_stats",
     "hbcsf_host_array", "hbcsf_tune", "hbcsf_kernel_ms", "hbcsf_probe_row_gather", "hbcsf_free",
     "hbcsf_strerror", "hbcsf_last_error",
-    "hbcsf_als_workspace_bytes", "hbcsf_als_create", "hbcsf_als_iteration", "hbcsf_als_run", "hbcsf_als_phase_ms", "hbcsf_als_free", "hbcsf_sym_pinv",
+    "hbcsf_als_workspace_bytes", "hbcsf_als_create", "hbcsf_als_iteration", "hbcsf_als_normalise", "hbcsf_als_run", "hbcsf_als_phase_ms", "hbcsf_als_free", "hbcsf_sym_pinv",
     "hbcsf_gram_workspace_bytes", "hbcsf_gram", "hbcsf_gram_noalloc",
     "hbcsf_device_build_bytes", "hbcsf_build_format_device", "hbcsf_download", "hbcsf_relocate",
 )
@@ -98,6 +99,8 @@ def lib():
         L.hbcsf_als_create.argtypes = [vp, i32, vp, u64, ctypes.POINTER(vp)]
         L.hbcsf_als_iteration.restype = i32
         L.hbcsf_als_iteration.argtypes = [vp, vp, vp, i32, ctypes.POINTER(ctypes.c_double), vp]
+        L.hbcsf_als_normalise.restype = i32
+        L.hbcsf_als_normalise.argtypes = [vp, vp, vp]
         L.hbcsf_als_run.restype = i32
         L.hbcsf_als_run.argtypes = [vp, vp, vp, i32, ctypes.c_double, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double), vp]
         L.hbcsf_als_phase_ms.restype = i32
@@ -272,6 +275,12 @@ def als_iteration(a, factor_ptrs, lambda_ptr: int = 0, flags: int = 0, want_fit:
     _check(lib().hbcsf_als_iteration(a, ctypes.cast(arr, ctypes.c_void_p), ctypes.c_void_p(lambda_ptr or None), flags,
                                      ctypes.byref(fit) if want_fit else None, ctypes.c_void_p(stream)))
     return float(fit.value) if want_fit else None
+
+
+def als_normalise(a, factor_ptrs, stream: int = 0):
+    """hbcsf_als_normalise: carries out the put-off column normalisation on the factors (device addresses)."""
+    arr = (ctypes.c_void_p * len(factor_ptrs))(*factor_ptrs)
+    _check(lib().hbcsf_als_normalise(a, ctypes.cast(arr, ctypes.c_void_p), ctypes.c_void_p(stream or None)))
 
 
 def als_run(a, factor_ptrs, lambda_ptr: int = 0, max_iterations: int = 50, tolerance: float = 1e-5, stream: int = 0):

@@ -144,6 +144,84 @@ __global__ __launch_bounds__(256) void apply32_kernel(const float* __restrict__ 
   }
 }
 
+// R = 32: out = M P as apply32_kernel, and in the same pass the Gram matrix of the rows just computed:
+// the 32 x 32 product tile leaves the matrix unit as sixteen registers whose lane (h, c) entries are
+// out[row 8 (v / 4) + 4 h + v % 4][c], i.e. for every v two different rows of the tile with lane c on
+// column c -- exactly the operand shape of gram32_partial_kernel -- so sixteen more matrix instructions
+// add the tile's out^T out without moving any data.  The partial Gram sums go to the block's scratch slot
+// (reduced by gram_reduce_kernel), so M is read once per mode update instead of twice.
+__global__ __launch_bounds__(256) void apply_gram32_kernel(const float* __restrict__ m, uint64_t rows,
+                                                           const float* __restrict__ p, float* __restrict__ out,
+                                                           uint64_t blocksPerWave, double* __restrict__ partial) {
+  __shared__ double red[4][1024];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int h = lane >> 5, c = lane & 31;
+  float pb[16];
+#pragma unroll
+  for (int t = 0; t < 16; ++t) pb[t] = p[(16 * h + t) * 32 + c];
+  const uint64_t w = (uint64_t)blockIdx.x * 4 + wave;
+  const uint64_t nBlocks = (rows + 31) / 32;
+  uint64_t b = w * blocksPerWave;
+  const uint64_t bEnd = (b + blocksPerWave < nBlocks) ? b + blocksPerWave : nBlocks;
+  double acc64[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc64[v] = 0.0;
+  while (b < bEnd) {
+    f32x16 gacc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) gacc[v] = 0.f;
+    for (int it = 0; it < kGramFlush && b < bEnd; ++it, ++b) {   // fp32 Gram sums over at most 128 rows
+      const uint64_t r = b * 32 + c;
+      float4 x[4];
+      if (r < rows) {
+        const float4* src = reinterpret_cast<const float4*>(m + r * 32 + 16 * h);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) x[q] = src[q];
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) x[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      f32x16 acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[q].x, pb[4 * q + 0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[q].y, pb[4 * q + 1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[q].z, pb[4 * q + 2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[q].w, pb[4 * q + 3], acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const uint64_t ro = b * 32 + (uint64_t)(8 * (v / 4) + 4 * h + (v % 4));
+        if (ro < rows) __builtin_nontemporal_store(acc[v], out + ro * 32 + c);
+      }
+      // rows past the end of the matrix were computed from zeros and add nothing
+#pragma unroll
+      for (int v = 0; v < 16; ++v) gacc = __builtin_amdgcn_mfma_f32_32x32x2f32(acc[v], acc[v], gacc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc64[v] += (double)gacc[v];
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) red[wave][(8 * (v / 4) + 4 * h + (v % 4)) * 32 + c] = acc64[v];
+  __syncthreads();
+  double* mine = partial + (size_t)blockIdx.x * 1024;
+  for (int e = threadIdx.x; e < 1024; e += 256) mine[e] = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+}
+
+// a[i][r] *= s[r]: the column normalisation of Algorithm "CPD-ALS" when it was put off (rank = 4 << gshift / ...).
+__global__ __launch_bounds__(256) void scale_columns_kernel(float4* __restrict__ a, uint64_t nvec,
+                                                            const float* __restrict__ s, int vecPerRow) {
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (uint64_t)gridDim.x * 256) {
+    const float4 sc = reinterpret_cast<const float4*>(s)[i % (uint64_t)vecPerRow];
+    float4 v = a[i];
+    v.x *= sc.x; v.y *= sc.y; v.z *= sc.z; v.w *= sc.w;
+    a[i] = v;
+  }
+}
+
 // ---------------------------------------------------------------------------------------------------
 // Other ranks: plain vector-ALU kernels (correct for any R in the supported list, not tuned).
 // ---------------------------------------------------------------------------------------------------
@@ -240,6 +318,32 @@ void launch_gram(const float* a, uint64_t rows, int rank, double* scratch, uint3
   }
   // with no rows no slot is read and the result is all zeros
   hipLaunchKernelGGL(gram_reduce_kernel, dim3((rr + 63) / 64), dim3(1024), 0, st, scratch, used, rr, s);
+}
+
+// R = 32 only: out = m p and g (device, [32][32] fp64) = out^T out in one pass over m.
+void launch_apply_gram32(const float* m, uint64_t rows, const float* p, float* out, double* scratch,
+                         uint32_t slots, double* g, int numCU, hipStream_t st) {
+  uint32_t used = 0;
+  if (rows > 0) {
+    const uint64_t nBlocks = (rows + 31) / 32;
+    uint64_t waves = (uint64_t)numCU * 32;
+    if (waves > (uint64_t)slots * 4) waves = (uint64_t)slots * 4;
+    const uint64_t per = (nBlocks + waves - 1) / waves;
+    const uint64_t nWaves = (nBlocks + per - 1) / per;
+    used = (uint32_t)((nWaves + 3) / 4);
+    hipLaunchKernelGGL(apply_gram32_kernel, dim3(used), dim3(256), 0, st, m, rows, p, out, per, scratch);
+  }
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3(16), dim3(1024), 0, st, scratch, used, 1024u, g);
+}
+
+void launch_scale_columns(float* a, uint64_t rows, int rank, const float* s, int numCU, hipStream_t st) {
+  if (rows == 0) return;
+  const uint64_t nvec = rows * (uint64_t)(rank / 4);
+  uint64_t blocks = (nvec + 255) / 256;
+  const uint64_t cap = (uint64_t)numCU * 32;
+  if (blocks > cap) blocks = cap;
+  hipLaunchKernelGGL(scale_columns_kernel, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<float4*>(a),
+                     nvec, s, rank / 4);
 }
 
 void launch_apply(const float* m, uint64_t rows, int rank, const float* p, float* out, int numCU,
@@ -399,11 +503,16 @@ struct hbcsf_als {
   double* s = nullptr;   // workspace: Gram matrix [R][R]
   double* gramScratch = nullptr;  // workspace: per-block partial sums of the Gram kernel
   uint32_t gramSlots = 0;
-  float* p = nullptr;    // workspace: right-hand R x R matrix of the update [R][R]
+  float* p = nullptr;    // workspace: right-hand R x R matrix of the update [R][R], then one [R] column-scale
+                         // vector per mode
   double* hostS = nullptr;  // pinned staging
   float* hostP = nullptr;   // pinned staging
   float* hostLambda = nullptr;
-  Mat gram[HBCSF_MAX_ORDER];  // Gram matrices of the factors as the last iteration left them
+  float* hostScale = nullptr;   // pinned staging: [order][R] column factors for the put-off normalisation
+  Mat gram[HBCSF_MAX_ORDER];  // Gram matrices of the factors as stored in device memory after the last iteration
+  // The algorithm's factor A_m is the stored matrix with column r divided by colScale[m][r].  All ones when
+  // the factors were left normalised; the column norms when the normalisation was put off (lazy flag).
+  std::vector<double> colScale[HBCSF_MAX_ORDER];
   bool gramsValid = false;
   hipEvent_t ev[HBCSF_MAX_ORDER][5];
   int eventsCreated = 0;  // events are created in order; this many exist
@@ -523,7 +632,7 @@ int hbcsf_als_workspace_bytes(const hbcsf_tensor* t, int rank, uint64_t* bytes) 
   uint64_t gramBytes = 0;
   (void)hbcsf_gram_workspace_bytes(rank, &gramBytes);
   *bytes = round256(maxDim * (uint64_t)rank * 4) + round256((uint64_t)rank * rank * 8) +
-           round256((uint64_t)rank * rank * 4) + round256(gramBytes);
+           round256(((uint64_t)rank * rank + (uint64_t)HBCSF_MAX_ORDER * rank) * 4) + round256(gramBytes);
   return HBCSF_OK;
 } HBCSF_CATCH_ALL
 
@@ -550,16 +659,20 @@ int hbcsf_als_create(const hbcsf_tensor* t, int rank, void* workspace, uint64_t 
   a->s = (double*)w;
   w += round256((uint64_t)rank * rank * 8);
   a->p = (float*)w;
-  w += round256((uint64_t)rank * rank * 4);
+  w += round256(((uint64_t)rank * rank + (uint64_t)HBCSF_MAX_ORDER * rank) * 4);
   a->gramScratch = (double*)w;
   uint64_t gramBytes = 0;
   (void)hbcsf_gram_workspace_bytes(rank, &gramBytes);
   a->gramSlots = gram_slots_for(rank, gramBytes);
   const size_t rr = (size_t)rank * rank;
-  hipError_t e = hipHostMalloc((void**)&a->hostS, rr * 8 + HBCSF_MAX_ORDER * rr * 4 + (size_t)rank * 4, hipHostMallocDefault);
+  hipError_t e = hipHostMalloc((void**)&a->hostS,
+                               rr * 8 + HBCSF_MAX_ORDER * rr * 4 + (size_t)rank * 4 + (size_t)HBCSF_MAX_ORDER * rank * 4,
+                               hipHostMallocDefault);
   if (e != hipSuccess) return fail_hip(e, "hipHostMalloc");
   a->hostP = (float*)(a->hostS + rr);
   a->hostLambda = a->hostP + HBCSF_MAX_ORDER * rr;
+  a->hostScale = a->hostLambda + rank;
+  for (int m = 0; m < t->order; ++m) a->colScale[m].assign((size_t)rank, 1.0);
   for (int k = 0; k < HBCSF_MAX_ORDER * 5; ++k) {
     e = hipEventCreate(&a->ev[k / 5][k % 5]);
     if (e != hipSuccess) return fail_hip(e, "hipEventCreate");  // the destructor releases what exists
@@ -569,6 +682,35 @@ int hbcsf_als_create(const hbcsf_tensor* t, int rank, void* workspace, uint64_t 
   return HBCSF_OK;
 } HBCSF_CATCH_ALL
 
+namespace {
+
+// Scales the columns of every stored factor whose normalisation was put off, so that the stored matrices are the
+// algorithm's unit-norm factors again; the Gram matrices the state keeps are scaled with them.
+int apply_pending_normalisation(hbcsf_als* a, float* const* factors, hipStream_t st) {
+  const hbcsf_tensor* t = a->t;
+  const int order = t->order, R = a->rank;
+  for (int m = 0; m < order; ++m) {
+    bool pending = false;
+    for (int r = 0; r < R; ++r) pending = pending || a->colScale[m][r] != 1.0;
+    if (!pending) continue;
+    float* hs = a->hostScale + (size_t)m * R;
+    float* ds = a->p + (size_t)R * R + (size_t)m * R;
+    for (int r = 0; r < R; ++r) hs[r] = (float)(1.0 / a->colScale[m][r]);
+    hipError_t e = hipMemcpyAsync(ds, hs, (size_t)R * 4, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync");
+    launch_scale_columns(factors[m], t->dims[m], R, ds, t->numCU, st);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "column scaling kernel launch");
+    if (a->gramsValid)
+      for (int i = 0; i < R; ++i)
+        for (int j = 0; j < R; ++j) a->gram[m][(size_t)i * R + j] /= a->colScale[m][i] * a->colScale[m][j];
+    a->colScale[m].assign((size_t)R, 1.0);
+  }
+  return HBCSF_OK;
+}
+
+}  // namespace
+
 int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int flags, double* fit,
                         void* hip_stream) try {
   if (!a || !factors) return fail(HBCSF_EINVAL, "null argument");
@@ -577,7 +719,10 @@ int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int 
   const size_t rr = (size_t)R * R;
   for (int m = 0; m < order; ++m)
     if (!factors[m]) return fail(HBCSF_EINVAL, "a factor pointer is null");
-  if (flags & ~HBCSF_ALS_KEEP_GRAMS) return fail(HBCSF_EINVAL, "unknown flag");
+  if (flags & ~(HBCSF_ALS_KEEP_GRAMS | HBCSF_ALS_LAZY_NORMALISATION)) return fail(HBCSF_EINVAL, "unknown flag");
+  const bool lazy = (flags & HBCSF_ALS_LAZY_NORMALISATION) != 0;
+  // the product kernel that also forms the new factor's Gram matrix exists for R = 32
+  const bool fused = lazy && R == 32;
   hipStream_t st = (hipStream_t)hip_stream;
   hipError_t e;
 
@@ -593,8 +738,10 @@ int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int 
     return HBCSF_OK;
   };
 
-  // Gram matrices of the factors that are read before they are updated (all but the first mode's)
+  // Gram matrices of the factors that are read before they are updated (all but the first mode's).  Without
+  // the keep flag the caller may have replaced the factors: they are then taken as they are (scale 1).
   if (!(flags & HBCSF_ALS_KEEP_GRAMS) || !a->gramsValid) {
+    for (int m = 0; m < order; ++m) a->colScale[m].assign((size_t)R, 1.0);
     for (int m = 1; m < order; ++m) {
       const int rc = gram_to_host(factors[m], t->dims[m], a->gram[m]);
       if (rc != HBCSF_OK) return rc;
@@ -602,10 +749,16 @@ int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int 
   }
   a->gramsValid = false;
 
-  std::vector<double> scale(R, 1.0);  // M_true = M_device diag(scale): norms of the factors written so far
+  // Book-keeping: the algorithm's current factor A_m is stored_m diag(1 / c_m) with c_m = colScale[m]; algGram[m]
+  // is its Gram matrix.  Column scaling commutes with every step of the update, so the device works on the
+  // stored matrices and the host folds the diagonals into the R x R matrices.
   Mat norms[HBCSF_MAX_ORDER];
-  Mat trueGram[HBCSF_MAX_ORDER];      // Gram matrices of the unnormalised factors, as the algorithm sees them
-  for (int m = 1; m < order; ++m) trueGram[m] = a->gram[m];
+  Mat algGram[HBCSF_MAX_ORDER];
+  for (int m = 1; m < order; ++m) {
+    algGram[m] = a->gram[m];
+    for (int i = 0; i < R; ++i)
+      for (int j = 0; j < R; ++j) algGram[m][(size_t)i * R + j] /= a->colScale[m][i] * a->colScale[m][j];
+  }
   double inner = 0.0;
 
   for (int n = 0; n < order; ++n) {
@@ -615,56 +768,105 @@ int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int 
     const int rc = hbcsf_mttkrp(t, n, R, facs, a->m, st);
     if (rc != HBCSF_OK) return rc;
     (void)hipEventRecord(a->ev[n][1], st);
-    Mat S;
-    const int rg = gram_to_host(a->m, t->dims[n], S);
-    if (rg != HBCSF_OK) return rg;
-    (void)hipEventRecord(a->ev[n][2], st);
-    for (int i = 0; i < R; ++i)
-      for (int j = 0; j < R; ++j) S[(size_t)i * R + j] *= scale[i] * scale[j];
+    // M of the algorithm = M of the device diag(d), d_r = product over the other modes of 1 / c_m[r]
+    std::vector<double> d((size_t)R, 1.0);
+    for (int m = 0; m < order; ++m)
+      if (m != n)
+        for (int r = 0; r < R; ++r) d[r] /= a->colScale[m][r];
     Mat V(rr, 1.0);
     for (int m = 0; m < order; ++m)
       if (m != n)
-        for (size_t k = 0; k < rr; ++k) V[k] *= trueGram[m][k];
-    const Mat Vp = pinv_of_gram_product(V, R);
-    trueGram[n] = matmul(matmul(Vp, S, R), Vp, R);
-    norms[n].assign(R, 1.0);
+        for (size_t k = 0; k < rr; ++k) V[k] *= algGram[m][k];
     float* hostP = a->hostP + (size_t)n * rr;  // one staging copy per mode: no wait before it is reused
-    for (int r = 0; r < R; ++r) {
-      const double d = trueGram[n][(size_t)r * R + r];
-      norms[n][r] = d > 0.0 ? std::sqrt(d) : 1.0;
-    }
-    for (int i = 0; i < R; ++i)
-      for (int j = 0; j < R; ++j) hostP[(size_t)i * R + j] = (float)(scale[i] * Vp[(size_t)i * R + j] / norms[n][j]);
-    if (n == order - 1) {
-      inner = 0.0;  // <X, model> = trace(M^T A_n) = trace(S V^+)
+    norms[n].assign(R, 1.0);
+    if (fused) {
+      // A_n = M V^+ written unnormalised, its Gram matrix G formed in the same pass; <X, model> = trace(M^T A_n)
+      // = trace(V G) because V^+ V V^+ = V^+.
+      (void)hipEventRecord(a->ev[n][2], st);
+      const Mat Vp = pinv_of_gram_product(V, R);
       for (int i = 0; i < R; ++i)
-        for (int j = 0; j < R; ++j) inner += S[(size_t)i * R + j] * Vp[(size_t)j * R + i];
+        for (int j = 0; j < R; ++j) hostP[(size_t)i * R + j] = (float)(d[i] * Vp[(size_t)i * R + j]);
+      (void)hipEventRecord(a->ev[n][3], st);
+      e = hipMemcpyAsync(a->p, hostP, rr * 4, hipMemcpyHostToDevice, st);
+      if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync");
+      launch_apply_gram32(a->m, t->dims[n], a->p, factors[n], a->gramScratch, a->gramSlots, a->s, t->numCU, st);
+      e = hipGetLastError();
+      if (e != hipSuccess) return fail_hip(e, "product kernel launch");
+      e = hipMemcpyAsync(a->hostS, a->s, rr * 8, hipMemcpyDeviceToHost, st);
+      if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync");
+      e = hipStreamSynchronize(st);
+      if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+      (void)hipEventRecord(a->ev[n][4], st);
+      algGram[n].assign(a->hostS, a->hostS + rr);
+      a->gram[n] = algGram[n];                 // stored = the algorithm's unnormalised factor
+      a->colScale[n].assign((size_t)R, 1.0);
+      for (int r = 0; r < R; ++r) {
+        const double g = algGram[n][(size_t)r * R + r];
+        norms[n][r] = g > 0.0 ? std::sqrt(g) : 1.0;
+      }
+      if (n == order - 1) {
+        inner = 0.0;
+        for (size_t k = 0; k < rr; ++k) inner += V[k] * algGram[n][k];   // both symmetric: trace(V G)
+      }
+    } else {
+      Mat S;
+      const int rg = gram_to_host(a->m, t->dims[n], S);
+      if (rg != HBCSF_OK) return rg;
+      (void)hipEventRecord(a->ev[n][2], st);
+      for (int i = 0; i < R; ++i)
+        for (int j = 0; j < R; ++j) S[(size_t)i * R + j] *= d[i] * d[j];
+      const Mat Vp = pinv_of_gram_product(V, R);
+      algGram[n] = matmul(matmul(Vp, S, R), Vp, R);   // A_n^T A_n = V^+ S V^+ without another pass
+      for (int r = 0; r < R; ++r) {
+        const double g = algGram[n][(size_t)r * R + r];
+        norms[n][r] = g > 0.0 ? std::sqrt(g) : 1.0;
+      }
+      // the factor is written with unit-norm columns at once: stored = A_n diag(1 / norms), so c_n = 1 / norms
+      // until the algorithm's closing normalisation makes it 1
+      for (int i = 0; i < R; ++i)
+        for (int j = 0; j < R; ++j) hostP[(size_t)i * R + j] = (float)(d[i] * Vp[(size_t)i * R + j] / norms[n][j]);
+      if (n == order - 1) {
+        inner = 0.0;  // <X, model> = trace(M^T A_n) = trace(S V^+)
+        for (int i = 0; i < R; ++i)
+          for (int j = 0; j < R; ++j) inner += S[(size_t)i * R + j] * Vp[(size_t)j * R + i];
+      }
+      (void)hipEventRecord(a->ev[n][3], st);
+      e = hipMemcpyAsync(a->p, hostP, rr * 4, hipMemcpyHostToDevice, st);
+      if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync");
+      launch_apply(a->m, t->dims[n], R, a->p, factors[n], t->numCU, st);
+      e = hipGetLastError();
+      if (e != hipSuccess) return fail_hip(e, "apply kernel launch");
+      (void)hipEventRecord(a->ev[n][4], st);
+      a->gram[n] = algGram[n];
+      for (int i = 0; i < R; ++i)
+        for (int j = 0; j < R; ++j) a->gram[n][(size_t)i * R + j] /= norms[n][i] * norms[n][j];
+      for (int r = 0; r < R; ++r) a->colScale[n][r] = 1.0 / norms[n][r];
     }
-    (void)hipEventRecord(a->ev[n][3], st);
-    e = hipMemcpyAsync(a->p, hostP, rr * 4, hipMemcpyHostToDevice, st);
-    if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync");
-    launch_apply(a->m, t->dims[n], R, a->p, factors[n], t->numCU, st);
-    e = hipGetLastError();
-    if (e != hipSuccess) return fail_hip(e, "apply kernel launch");
-    (void)hipEventRecord(a->ev[n][4], st);
-    for (int r = 0; r < R; ++r) scale[r] *= norms[n][r];
   }
 
-  // lambda: product over the modes of the column norms; the model's squared norm from the Gram matrices
+  // lambda: product over the modes of the column norms; the model's squared norm from the Gram matrices of the
+  // unnormalised factors
   double modelSq = 0.0;
   for (size_t k = 0; k < rr; ++k) {
     double prod = 1.0;
-    for (int m = 0; m < order; ++m) prod *= trueGram[m][k];
+    for (int m = 0; m < order; ++m) prod *= algGram[m][k];
     modelSq += prod;
   }
-  for (int m = 0; m < order; ++m) {
-    a->gram[m] = trueGram[m];
-    for (int i = 0; i < R; ++i)
-      for (int j = 0; j < R; ++j) a->gram[m][(size_t)i * R + j] /= norms[m][i] * norms[m][j];
-  }
+  // the algorithm's closing normalisation: A_m <- A_m diag(1 / norms_m), i.e. c_m <- c_m norms_m
+  std::vector<double> lam((size_t)R, 1.0);
+  for (int m = 0; m < order; ++m)
+    for (int r = 0; r < R; ++r) {
+      a->colScale[m][r] *= norms[m][r];
+      if (std::fabs(a->colScale[m][r] - 1.0) < 1e-12) a->colScale[m][r] = 1.0;   // written normalised already
+      lam[r] *= norms[m][r];
+    }
   a->gramsValid = true;
+  if (!lazy) {
+    const int rn = apply_pending_normalisation(a, factors, st);
+    if (rn != HBCSF_OK) return rn;
+  }
   if (lambda) {
-    for (int r = 0; r < R; ++r) a->hostLambda[r] = (float)scale[r];
+    for (int r = 0; r < R; ++r) a->hostLambda[r] = (float)lam[r];
     e = hipMemcpyAsync(lambda, a->hostLambda, (size_t)R * 4, hipMemcpyHostToDevice, st);
     if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync");
   }
@@ -683,6 +885,17 @@ int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int 
   return HBCSF_OK;
 } HBCSF_CATCH_ALL
 
+int hbcsf_als_normalise(hbcsf_als* a, float* const* factors, void* hip_stream) try {
+  if (!a || !factors) return fail(HBCSF_EINVAL, "null argument");
+  for (int m = 0; m < a->t->order; ++m)
+    if (!factors[m]) return fail(HBCSF_EINVAL, "a factor pointer is null");
+  const int rc = apply_pending_normalisation(a, factors, (hipStream_t)hip_stream);
+  if (rc != HBCSF_OK) return rc;
+  const hipError_t e = hipStreamSynchronize((hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+  return HBCSF_OK;
+} HBCSF_CATCH_ALL
+
 int hbcsf_als_run(hbcsf_als* a, float* const* factors, float* lambda, int max_iterations, double tolerance,
                   int* iterations_done, double* fit, void* hip_stream) try {
   if (!a || !factors) return fail(HBCSF_EINVAL, "null argument");
@@ -690,7 +903,9 @@ int hbcsf_als_run(hbcsf_als* a, float* const* factors, float* lambda, int max_it
   double prev = 0.0, cur = 0.0;
   int it = 0;
   for (; it < max_iterations; ++it) {
-    const int rc = hbcsf_als_iteration(a, factors, lambda, it > 0 ? HBCSF_ALS_KEEP_GRAMS : 0, &cur, hip_stream);
+    const int rc = hbcsf_als_iteration(a, factors, lambda,
+                                       (it > 0 ? HBCSF_ALS_KEEP_GRAMS : 0) | HBCSF_ALS_LAZY_NORMALISATION, &cur,
+                                       hip_stream);
     if (rc != HBCSF_OK) return rc;
     if (it > 0 && std::fabs(cur - prev) < tolerance) {
       ++it;
@@ -698,6 +913,8 @@ int hbcsf_als_run(hbcsf_als* a, float* const* factors, float* lambda, int max_it
     }
     prev = cur;
   }
+  const int rn = hbcsf_als_normalise(a, factors, hip_stream);
+  if (rn != HBCSF_OK) return rn;
   if (iterations_done) *iterations_done = it;
   if (fit) *fit = cur;
   return HBCSF_OK;

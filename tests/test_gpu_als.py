@@ -41,7 +41,7 @@ def _worst_cond(dims, inds, vals, facs):
     return worst
 
 
-def _run_gpu(dims, inds, vals, facs, rank, iterations=1, keep=False):
+def _run_gpu(dims, inds, vals, facs, rank, iterations=1, keep=False, lazy=False):
     import torch
     from paper_1904_03329_amd import CpdAls, HbcsfTensor
 
@@ -50,7 +50,9 @@ def _run_gpu(dims, inds, vals, facs, rank, iterations=1, keep=False):
     dfacs = [torch.from_numpy(np.ascontiguousarray(f)).cuda() for f in facs]
     fits = []
     for it in range(iterations):
-        fits.append(als.iteration(dfacs, keep_grams=keep and it > 0))
+        fits.append(als.iteration(dfacs, keep_grams=keep and it > 0, lazy=lazy))
+    if lazy:
+        als.normalise(dfacs)
     torch.cuda.synchronize()
     out = [f.cpu().numpy() for f in dfacs]
     lam = als.lam.cpu().numpy()
@@ -60,8 +62,8 @@ def _run_gpu(dims, inds, vals, facs, rank, iterations=1, keep=False):
     return out, lam, fits, phases
 
 
-def _check(dims, inds, vals, facs, rank, iterations=1, keep=False):
-    got, lam, fits, _ = _run_gpu(dims, inds, vals, facs, rank, iterations, keep)
+def _check(dims, inds, vals, facs, rank, iterations=1, keep=False, lazy=False):
+    got, lam, fits, _ = _run_gpu(dims, inds, vals, facs, rank, iterations, keep, lazy)
     want = [np.array(f, dtype=np.float64) for f in facs]
     cond = 1.0
     for _ in range(iterations):
@@ -112,6 +114,39 @@ def test_three_iterations_reuse_gram_matrices():
     fits_fresh = _check(dims, inds, vals, facs, 32, iterations=3, keep=False)
     np.testing.assert_allclose(fits_keep, fits_fresh, atol=1e-5)
     assert fits_keep[2] >= fits_keep[1] - 1e-6 >= fits_keep[0] - 2e-6      # ALS never lowers the fit
+
+
+@pytest.mark.parametrize("rank", [32, 16])
+@pytest.mark.parametrize("dims", [(1000, 333, 77), (130, 65, 31, 9)])
+def test_put_off_normalisation(rank, dims):
+    """HBCSF_ALS_LAZY_NORMALISATION: three iterations whose closing normalisation is put off (at R = 32 the product
+    kernel then also forms the new factor's Gram matrix), hbcsf_als_normalise at the end; factors, lambda and every
+    iteration's fit as the oracle's.  Then an ordinary iteration on a state that still has norms pending."""
+    import torch
+    from paper_1904_03329_amd import CpdAls, HbcsfTensor
+
+    rng = np.random.default_rng(4000 + rank + len(dims))
+    inds, vals = _random_tensor(rng, dims, 40000)
+    facs = [rng.uniform(-1, 1, size=(d, rank)).astype(np.float32) for d in dims]
+    fits_lazy = _check(dims, inds, vals, facs, rank, iterations=3, keep=True, lazy=True)
+    fits_eager = _check(dims, inds, vals, facs, rank, iterations=3, keep=True, lazy=False)
+    np.testing.assert_allclose(fits_lazy, fits_eager, atol=1e-5)
+    # two put-off iterations, then one that normalises by itself: same as three ordinary ones
+    t = HbcsfTensor(dims, inds, vals).to_device()
+    als = CpdAls(t, rank)
+    dfacs = [torch.from_numpy(f).cuda() for f in facs]
+    als.iteration(dfacs, lazy=True)
+    als.iteration(dfacs, keep_grams=True, lazy=True)
+    fit = als.iteration(dfacs, keep_grams=True)
+    want = [f.astype(np.float64) for f in facs]
+    for _ in range(3):
+        want, want_lam = cpd_als.als_iteration(dims, inds, vals, want)
+    for g, w in zip(dfacs, want):
+        assert np.max(np.abs(g.cpu().numpy() - w)) <= 2e-4 * np.max(np.abs(w))
+    np.testing.assert_allclose(torch.sqrt((dfacs[1].double() ** 2).sum(dim=0)).cpu().numpy(), 1.0, atol=1e-4)
+    assert abs(fit - fits_eager[2]) <= 1e-5
+    als.close()
+    t.close()
 
 
 def test_recovers_an_exact_low_rank_tensor():
