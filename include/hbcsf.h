@@ -185,6 +185,12 @@ int hbcsf_host_array(const hbcsf_tensor *t, int mode, int group, int level, int 
                                         reported under "define" and the COO kernel is not
                                         launched); 0: separate COO kernel; 2 (default): fused when
                                         the output is at most 64 MiB, where it saves a launch     */
+#define HBCSF_TUNE_DENSE_MID        10 /* 1: B-CSF kernel at rank 32, orders 3 and 4 with T_f 32 or 64 (ignored
+                                        elsewhere): the factor rows of the fiber levels are gathered once per
+                                        block of steps for the whole wavefront (all lanes of each load
+                                        instruction busy) into an LDS row cache instead of at the step where a
+                                        segment ends.  A measured alternative that lost (fewer load
+                                        instructions, but a longer dependent chain per block); 0 (default): off */
 int hbcsf_tune(hbcsf_tensor *t, int key, uint64_t value);
 
 /* With HBCSF_TUNE_PROFILE on: milliseconds of the four kernels (define, COO, CSL, CSF; 0 for a

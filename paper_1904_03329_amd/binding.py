@@ -18,6 +18,7 @@ HBCSF_MAX_ORDER = 5
 ARR_IND, ARR_PTR, ARR_VAL, ARR_RUNFIRST, ARR_OWNED_BITS, ARR_COO_BITS, ARR_COO_PTR = 0, 1, 2, 3, 4, 5, 6
 TUNE_SLICE_THRESHOLD, TUNE_PROFILE, TUNE_WAVES_PER_CU, TUNE_STEPS, TUNE_KERNEL_MASK = 0, 1, 2, 3, 4
 TUNE_TRACE_BUFFER, TUNE_TRACE_CAPACITY, TUNE_PERSISTENT, TUNE_STREAM_BYTES, TUNE_FUSE_COO = 5, 6, 7, 8, 9
+TUNE_DENSE_MID = 10
 GROUP_COO, GROUP_CSL, GROUP_CSF = 0, 1, 2
 OWNED_BIT = 0x80000000
 ALS_KEEP_GRAMS = 1

@@ -250,7 +250,15 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
         a.unitsPerWave = 0;
       } else {
         const int RW = N == 3 ? 4 : 8;  // LDS words per nonzero record
-        const size_t ldsWave = (size_t)NG * (L + 1) * RW * 4;
+        size_t ldsWave = (size_t)NG * (L + 1) * RW * 4;
+        // B-CSF tuning variant: the fiber-level rows gathered densely through an LDS row cache (off by default:
+        // it lowered the vector-memory instruction count as intended but lengthened every block's dependent chain
+        // and measured 40-100 % slower on the benchmark tensors)
+        a.denseMid = 0;
+        if (g == kCsf && t->denseMid == 1 && dense_mid_available(N, G, lshift)) {
+          a.denseMid = 1;
+          ldsWave += dense_mid_lds_bytes(G);
+        }
         int wpb = 4;
         while (wpb > 1 && ldsWave * wpb > 48 * 1024) wpb >>= 1;
         threads = 64 * wpb;
@@ -379,6 +387,11 @@ int hbcsf_tune(hbcsf_tensor* t, int key, uint64_t value) try {
   if (key == HBCSF_TUNE_KERNEL_MASK) {
     if (value > 15) return fail(HBCSF_EINVAL, "kernel mask must be 0..15");
     t->kernelMask = (uint32_t)value;
+    return HBCSF_OK;
+  }
+  if (key == HBCSF_TUNE_DENSE_MID) {
+    if (value > 1) return fail(HBCSF_EINVAL, "dense-gather mode must be 0 or 1");
+    t->denseMid = (int)value;
     return HBCSF_OK;
   }
   if (key == HBCSF_TUNE_STEPS) {

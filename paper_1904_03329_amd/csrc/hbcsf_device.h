@@ -9,6 +9,14 @@ namespace hbcsf {
 
 enum KernelKind { kCooKernel = 0, kCslKernel = 1, kCsfKernel = 2 };
 
+// The B-CSF kernel's dense fiber-row gather: rows its per-wavefront LDS cache holds, the instantiations that
+// exist (rank 32, orders 3 and 4, runs of 32 or 64 nonzeros), and the LDS bytes it adds per wavefront.
+constexpr int kDenseCacheRows = 32;
+inline bool dense_mid_available(int order, int G, uint32_t lshift) {
+  return G == 8 && (order == 3 || order == 4) && (lshift == 5 || lshift == 6);
+}
+inline size_t dense_mid_lds_bytes(int G) { return 256 + (size_t)kDenseCacheRows * 16 * (size_t)G; }
+
 // Device pointers of one slice group of one mode, by tree level (0 = root .. order-1 = leaf).
 struct GroupArgs {
   const uint32_t* ind[5];       // index arrays (per slice / segment / nonzero, by group kind)
@@ -25,6 +33,8 @@ struct GroupArgs {
   uint32_t nSpans;              // ceil(nUnits / unitsPerWave)
   uint32_t streamLevel;         // bit l: the factor rows of fiber level l are gathered with streaming loads
   uint32_t persistent;          // 1: resident wavefronts take spans round-robin; 0: one wavefront per span
+  uint32_t denseMid;            // B-CSF kernel: 1 = fiber-level rows gathered once per block of steps for the whole
+                                // wavefront through an LDS row cache (needs dense_mid_available and its LDS size)
   // Optional wavefront trace (profiling only, nullptr = off): trace[0] counts records; record i
   // is the four words at trace[4 + 4 i]: {kernel kind, XCC_ID << 32 | HW_ID, start, end} with
   // start / end from the constant-rate wall clock.

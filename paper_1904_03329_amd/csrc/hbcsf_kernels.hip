@@ -27,6 +27,8 @@ namespace hbcsf {
 
 namespace {
 
+constexpr int kDenseCache = kDenseCacheRows;  // rows of the dense variant's per-wavefront row cache
+
 
 __device__ __forceinline__ float4 f4zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
 
@@ -430,18 +432,32 @@ __global__ __launch_bounds__(256) void define_rows_kernel(float4* __restrict__ o
 // A segment mark is index+1 at the segment's last nonzero, else 0.  A slice mark is
 // (row+1) | owned bit at the slice's last nonzero, else 0.
 // ---------------------------------------------------------------------------------------
-template <int G, int N, int LS, int kSteps, bool WIDE>
+//
+// DENSE (orders 3 and 4): the rows of the fiber levels are not gathered at the step where a segment ends (one
+// load instruction per step in which ANY lane group ends a segment, most of its lanes idle) but once per block of
+// kSteps steps for the whole wavefront: every lane group counts the marks in its kSteps records, a prefix sum over
+// the lane groups gives each mark a slot, the row numbers go to a list in LDS, and ceil(marks / NG) load
+// instructions with all lanes busy bring the rows into an LDS row cache, from which the steps then read them.
+// Every vector-memory instruction keeps the CU's address unit busy for the same 16 cycles however many lanes
+// are active, and that unit is what bounds this kernel when the factor matrices are cache-resident.  The cache
+// holds kDenseCache rows; marks beyond it (rare when segments average a few nonzeros) load their row directly.
+template <int G, int N, int LS, int kSteps, bool WIDE, bool DENSE>
 __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
   constexpr int NG = 64 / G;
   constexpr int NF = N - 2;
   constexpr int RW = (N == 3) ? 4 : 8;
+  static_assert(!DENSE || N <= 4, "the dense fiber-row gather handles orders 3 and 4");
   extern __shared__ uint32_t lds[];
   const int lane = threadIdx.x & 63;
   const int wib = threadIdx.x >> 6;
   const int wpb = blockDim.x >> 6;
   const int g = lane / G, c = lane % G;
   constexpr uint32_t L = 1u << LS;
-  uint32_t* rec = lds + (size_t)wib * (NG * (L + 1) * RW);
+  constexpr uint32_t recWords = NG * (L + 1) * RW;
+  constexpr uint32_t waveWords = recWords + (DENSE ? 64u + (uint32_t)kDenseCache * G * 4u : 0u);
+  uint32_t* rec = lds + (size_t)wib * waveWords;
+  uint32_t* list = rec + recWords;                                   // DENSE: row numbers by slot
+  float4* cache = reinterpret_cast<float4*>(rec + recWords + 64);    // DENSE: rows by slot, G float4 each
 
 
   const float* __restrict__ facLeaf = a.fac[N - 1];
@@ -473,8 +489,11 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
     fLo[2] = cur.fHi[2];
     cur = nxt;
 
-    if (ng > 0) {
-      if (pend && pendRow != headRow) {
+    // A lane group whose run lies beyond the end of the stream (ng = 0, last unit only) has all-zero records.  The
+    // dense variant's block loop is collective (prefix sum over the lane groups, shared list and row cache), so
+    // every lane group runs it, live or not; zero records hold no marks and so change nothing.
+    {
+      if (ng > 0 && pend && pendRow != headRow) {
         row_atomic<G>(a.out, pendRow, c, acc);
         acc = f4zero();
       }
@@ -485,6 +504,100 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
       float4 tmp1 = f4zero();
       float4 tmp2 = f4zero();
       const uint32_t* myrec = rec + (size_t)g * (L + 1) * RW;
+      if constexpr (DENSE) {
+      for (uint32_t sb = 0; sb < L; sb += kSteps) {
+        uint4 rr[kSteps];
+        uint32_t mi[kSteps];   // slice mark
+        uint32_t sl[kSteps];   // slot (within this lane group) of the deepest level's mark, then of the next level's
+        float4 cr[kSteps];
+#pragma unroll
+        for (int t = 0; t < kSteps; ++t) {
+          const uint4* src = reinterpret_cast<const uint4*>(myrec + (size_t)(sb + t) * RW);
+          rr[t] = src[0];
+          mi[t] = (N == 3) ? rr[t].w : reinterpret_cast<const uint32_t*>(src)[4];
+        }
+        // marks of this block per lane group, and where its slots start
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int t = 0; t < kSteps; ++t) {
+          sl[t] = cnt;
+          cnt += rr[t].z ? 1u : 0u;
+          if (N == 4) cnt += rr[t].w ? 1u : 0u;   // its slot is sl[t] + 1 (a level-1 mark implies a level-2 mark)
+        }
+        uint32_t incl = cnt;
+#pragma unroll
+        for (int o = G; o < 64; o <<= 1) {
+          const uint32_t up = __shfl_up(incl, o);
+          if (lane >= o) incl += up;
+        }
+        const uint32_t base = incl - cnt;
+        const uint32_t total = __builtin_amdgcn_readlane(incl, 63);
+#pragma unroll
+        for (int t = 0; t < kSteps; ++t) {
+          sl[t] += base;
+          if (rr[t].z && sl[t] < (uint32_t)kDenseCache) list[sl[t]] = rr[t].z - 1u;
+          if (N == 4 && rr[t].w && sl[t] + 1u < (uint32_t)kDenseCache) list[sl[t] + 1u] = (rr[t].w - 1u) | 0x80000000u;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        // the rows, NG per load instruction
+        const uint32_t nq = min(total, (uint32_t)kDenseCache);
+        constexpr int kRounds = kDenseCache / NG;
+        float4 mr[kRounds];
+#pragma unroll
+        for (int u2 = 0; u2 < kRounds; ++u2) {
+          const uint32_t q = (uint32_t)u2 * NG + g;
+          if ((uint32_t)u2 * NG < nq) {        // wave-uniform: rounds past the last slot issue nothing
+            if (q < nq) {
+              const uint32_t e = list[q];
+              const uint32_t row = e & 0x7fffffffu;
+              if (N == 4 && (e >> 31)) {
+                mr[u2] = (a.streamLevel & 2u) ? row_load_streaming<G, WIDE>(facNext, row, c)
+                                              : row_load<G, WIDE>(facNext, row, c);
+              } else {
+                mr[u2] = (a.streamLevel & (1u << (N - 2))) ? row_load_streaming<G, WIDE>(facDeep, row, c)
+                                                           : row_load<G, WIDE>(facDeep, row, c);
+              }
+            }
+          }
+        }
+#pragma unroll
+        for (int t = 0; t < kSteps; ++t) cr[t] = row_load<G, WIDE>(facLeaf, rr[t].x, c);
+#pragma unroll
+        for (int u2 = 0; u2 < kRounds; ++u2) {
+          const uint32_t q = (uint32_t)u2 * NG + g;
+          if ((uint32_t)u2 * NG < nq && q < nq) cache[(size_t)q * G + c] = mr[u2];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int t = 0; t < kSteps; ++t) {
+          fma4(tmp, __uint_as_float(rr[t].y), cr[t]);
+          if (rr[t].z) {
+            const float4 br = sl[t] < (uint32_t)kDenseCache ? cache[(size_t)sl[t] * G + c]
+                                                             : row_load<G, WIDE>(facDeep, rr[t].z - 1u, c);
+            if (N == 3) {
+              fma4(acc, tmp, br);
+            } else {
+              fma4(tmp1, tmp, br);
+              if (rr[t].w) {
+                const float4 nr = sl[t] + 1u < (uint32_t)kDenseCache ? cache[(size_t)(sl[t] + 1u) * G + c]
+                                                                      : row_load<G, WIDE>(facNext, rr[t].w - 1u, c);
+                fma4(acc, tmp1, nr);
+                tmp1 = f4zero();
+              }
+            }
+            tmp = f4zero();
+            if (mi[t]) {  // a slice can only end where a segment ends
+              const uint32_t row = (mi[t] & 0x7fffffffu) - 1u;
+              if (mi[t] & 0x80000000u) row_store<G>(a.out, row, c, acc);
+              else row_atomic<G>(a.out, row, c, acc);
+              acc = f4zero();
+            }
+          }
+        }
+        // the next block rewrites the list and the cache
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      }
+      } else if (ng > 0) {
       for (uint32_t sb = 0; sb < L; sb += kSteps) {
         uint4 rr[kSteps];
         uint32_t m1[kSteps];   // N = 5: mark of fiber level 1
@@ -556,9 +669,12 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
           }
         }
       }
+      }  // classic / dense
       // the run leaves a partial row behind unless its last nonzero ends a slice
-      pend = myrec[(size_t)(ng - 1) * RW + (N == 3 ? 3 : N)] == 0u;
-      pendRow = tailRow;
+      if (ng > 0) {
+        pend = myrec[(size_t)(ng - 1) * RW + (N == 3 ? 3 : N)] == 0u;
+        pendRow = tailRow;
+      }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   }
@@ -569,7 +685,12 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
 
 template <int G, int N, int LS, int kSteps, bool WIDE>
 __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
-  csf_group_body<G, N, LS, kSteps, WIDE>(a);
+  csf_group_body<G, N, LS, kSteps, WIDE, false>(a);
+}
+
+template <int G, int N, int LS, int kSteps, bool WIDE>
+__global__ __launch_bounds__(256) void csf_group_dense_kernel(const GroupArgs a) {
+  csf_group_body<G, N, LS, kSteps, WIDE, true>(a);
 }
 
 // The order-3, R = 32, 32-bit-offset instantiation needs 132 vector registers, four more than fit four
@@ -579,7 +700,7 @@ __global__ __launch_bounds__(256) void csf_group_kernel(const GroupArgs a) {
 // per SIMD) measured no gain; both keep the plain kernel.
 template <int G, int N, int LS, int kSteps>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void csf_group_kernel_occ4(const GroupArgs a) {
-  csf_group_body<G, N, LS, kSteps, false>(a);
+  csf_group_body<G, N, LS, kSteps, false, false>(a);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -823,6 +944,9 @@ namespace {
 template <int G, int N, int LS, int S, bool WIDE>
 hipError_t launch_one(int kind, const GroupArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
   auto csf = (G == 8 && N == 3 && S == 8 && !WIDE) ? csf_group_kernel_occ4<G, N, LS, S> : csf_group_kernel<G, N, LS, S, WIDE>;
+  if constexpr (G == 8 && N <= 4 && (LS == 5 || LS == 6)) {
+    if (a.denseMid) csf = csf_group_dense_kernel<G, N, LS, S, WIDE>;
+  }
   auto csl = csl_group_kernel<G, N, LS, S, WIDE>;
   const int which = kind == kCsfKernel ? 1 : 0;
   const uint32_t wpb = block.x >> 6;

@@ -26,6 +26,7 @@ struct hbcsf_tensor {
   int steps = 8;             // records in flight per lane group
   uint32_t kernelMask = 15;  // bit0 define, bit1 COO, bit2 CSL, bit3 CSF
   bool persistent = false;   // resident wavefronts walk the spans round-robin
+  int denseMid = 0;          // B-CSF fiber-row gather through an LDS row cache (tuning variant): 0 off, 1 on
   int fuseCoo = 2;           // COO-group rows written by the output-definition pass: 0 never, 1 always, 2 small outputs
   uint64_t streamBytes = 1ull << 30;  // fiber-level factors at least this large are gathered with streaming loads
   unsigned long long* trace = nullptr;  // caller's device buffer for wavefront traces

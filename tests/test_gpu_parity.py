@@ -55,7 +55,8 @@ def test_ranks_and_orders(oracle, dims, nnz, rank):
                                   dict(group_mask=1), dict(group_mask=2), dict(mode_order_policy=1),
                                   dict(mode_order_policy=2), dict(tune_ts=256), dict(tune_ts=100_000),
                                   dict(hybrid_granularity=1), dict(hybrid_granularity=1, fiber_threshold=8),
-                                  dict(coo_row_flags=1)])
+                                  dict(coo_row_flags=1), dict(tune_dense=1),
+                                  dict(tune_dense=1, fiber_threshold=32), dict(tune_dense=1, group_mask=4, tune_ts=256)])
 @pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000),
                                       ((1500, 80, 20, 9, 6), 90_000)])
 def test_build_options_do_not_change_the_result(oracle, dims, nnz, opts):
@@ -114,6 +115,21 @@ def test_factor_matrices_above_4GiB(oracle, synth, dims, nnz, alpha):
               f"max|diff|/max|M| = {rel:.2e}", flush=True)
         del out
     ht.close()
+
+
+@pytest.mark.parametrize("dims,nnz,a", [((2000, 30, 4000), 300_000, 0.4), ((300, 3, 12, 3000), 250_000, 0.3),
+                                        ((50_000, 20_000, 300), 400_000, 1.2)])
+def test_dense_fiber_row_gather(oracle, dims, nnz, a):
+    """The B-CSF kernel's dense gather of fiber-level rows (HBCSF_TUNE_DENSE_MID = 1) on long fibers (few marks per
+    block of steps), on a 4-order tensor (two fiber levels share the row cache) and on a tensor whose fibers are
+    mostly singletons, so that a block's marks overflow the 32-row cache and take the direct-load path."""
+    rng = np.random.default_rng(len(dims) * 31 + nnz % 97)
+    inds, vals = _skewed(rng, dims, nnz, a=a)
+    facs = _factors(rng, dims, 32)
+    print("dense gather", dims, vals.shape[0], flush=True)
+    for mask in (0, 4):
+        stats = _check_all_modes(oracle, dims, inds, vals, facs, f"dense gather mask {mask}", tune_dense=1, group_mask=mask)
+    assert all(s["group_nnz"][2] == vals.shape[0] for s in stats)
 
 
 def test_degenerate_shapes(oracle):
