@@ -219,7 +219,7 @@ def time_device_build(torch, np, B, HbcsfTensor, t, host_tensor, args, log):
             dev = HbcsfTensor.from_device_coo(t.dims, di, dv, compact=False, fiber_threshold=args.fiber_threshold,
                                               slice_threshold=args.slice_threshold,
                                               mode_order_policy=args.mode_order_policy, group_mask=args.group_mask,
-                                              coo_row_flags=args.coo_row_flags)
+                                              coo_row_flags=args.coo_row_flags, mid_blocking=args.mid_blocking)
             torch.cuda.synchronize()
             times.append(time.perf_counter() - t0)
             same = B.device_bytes(dev.handle) == B.device_bytes(host_tensor.handle)
@@ -331,7 +331,7 @@ def measure(name: str, args, headline: bool, log) -> dict:
     ht = HbcsfTensor(t.dims, t.inds, t.vals, fiber_threshold=args.fiber_threshold,
                      slice_threshold=args.slice_threshold, mode_order_policy=args.mode_order_policy,
                      group_mask=args.group_mask, hybrid_granularity=args.hybrid_granularity,
-                     coo_row_flags=args.coo_row_flags)
+                     coo_row_flags=args.coo_row_flags, mid_blocking=args.mid_blocking)
     build_s = time.time() - t0
     t0 = time.time()
     ht.to_device()
@@ -474,6 +474,8 @@ def main() -> int:
     ap.add_argument("--slice-threshold", type=int, default=0)
     ap.add_argument("--mode-order-policy", type=int, default=0)
     ap.add_argument("--group-mask", type=int, default=0)
+    ap.add_argument("--mid-blocking", type=int, default=0,
+                    help="blocking of the first fiber level: 0 off, 2..13 bits (2^bits blocks) in every mode")
     ap.add_argument("--coo-row-flags", type=int, default=0,
                     help="1: the COO group stores row flags instead of a root index per nonzero")
     ap.add_argument("--hybrid-granularity", type=int, default=0,

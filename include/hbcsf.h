@@ -70,6 +70,14 @@ typedef struct hbcsf_opts {
                                  (HBCSF_ARR_COO_PTR) says which row each belongs to.  hbcsf_mttkrp then
                                  always computes the group's rows in the output-definition pass.  0
                                  (default): root indices are stored and either kernel can be used.    */
+  uint32_t mid_blocking;      /* blocking of the first fiber level (Section VIII: blocking as complementary
+                                 work): its index range is cut into 2^bits equal blocks and the nonzeros are
+                                 ordered by (block, root, level 1, .., leaf), so a slice is stored as one
+                                 piece per block (all pieces merged with atomic adds, the COO group unused)
+                                 and consecutive slices' pieces gather the same level-1 rows while they are
+                                 still in the L2.  0 or 1 = off (default); 2..13 = that many bits in every
+                                 mode whose level-1 index is wider.  A measured alternative that lost.
+                                 hbcsf_stats.slices then counts pieces.                                  */
 } hbcsf_opts;
 
 /* Per-mode statistics of the built representation.  "words" are 4-byte index words as the

@@ -85,6 +85,7 @@ int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint
   if (o.group_mask > 4) return fail(HBCSF_EINVAL, "group_mask must be 0..4");
   if (o.hybrid_granularity > 1) return fail(HBCSF_EINVAL, "hybrid_granularity must be 0 or 1");
   if (o.coo_row_flags > 1) return fail(HBCSF_EINVAL, "coo_row_flags must be 0 or 1");
+  if (o.mid_blocking > 13) return fail(HBCSF_EINVAL, "mid_blocking must be 0 or 1 (off) or 2..13 bits");
   std::unique_ptr<hbcsf_tensor> t(new (std::nothrow) hbcsf_tensor);
   if (!t) return fail(HBCSF_ENOMEM, "out of host memory");
   t->order = order;

@@ -35,6 +35,7 @@ struct Spec {
   int shift[HBCSF_MAX_ORDER];
   uint64_t mask[HBCSF_MAX_ORDER];
   uint32_t L, cooOn, cslOn, cooRowFlags;
+  int blockBits, blockShift, blockDrop;  // level-1 blocking: (index of level 1 >> blockDrop) << blockShift tops the key
 };
 
 struct C6 {  // running slice and nonzero counts of the three groups
@@ -145,6 +146,7 @@ __global__ void pack_kernel(IndPtrs inds, const float* vals, size_t M, Spec sp, 
     const uint32_t i = inds.p[l][z];
     bad = bad || (uint64_t)i >= dims[l];
     key |= (Key)i << sp.shift[l];
+    if (l == 1 && sp.blockBits) key |= (Key)(i >> sp.blockDrop) << sp.blockShift;
   }
   if (sizeof(Key) == 8) {
     K[z] = (uint64_t)key;
@@ -286,7 +288,7 @@ __global__ void fill_slices_kernel(const Key* K, size_t S, Spec sp, Tables t, Ou
       const uint32_t b = t.sStart[s], n = t.sStart[s + 1] - b;
       const uint32_t a = t.c6[s].m[g], ord = t.c6[s].s[g];
       const uint32_t root = (uint32_t)((uint64_t)(K[b] >> sp.shift[0]) & sp.mask[0]);
-      const bool own = (a / sp.L) == ((a + n - 1) / sp.L);
+      const bool own = sp.blockBits == 0 && (a / sp.L) == ((a + n - 1) / sp.L);
       if (g == kCsl) {
         o.cslInd[0][ord] = root | (own ? kOwnedBit : 0u);
         o.cslPtr[ord] = a;
@@ -427,7 +429,9 @@ uint64_t arena_bound(int N, const uint64_t* dims, uint64_t M, uint32_t L) {
   return bytes;
 }
 
-int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* opts, hbcsf_opts* o, int* totalBits) {
+// totalBits: bits of the packed (root, .., leaf) key; maxBits: the widest key of any mode, block bits included
+int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* opts, hbcsf_opts* o, int* totalBits,
+               int* maxBits) {
   if (order != 3 && order != 4)
     return fail(HBCSF_EINVAL, "the device-side builder handles orders 3 and 4 (order 5: hbcsf_build_format)");
   if (!dims) return fail(HBCSF_EINVAL, "dims is null");
@@ -445,9 +449,16 @@ int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* 
   if (o->mode_order_policy > 2) return fail(HBCSF_EINVAL, "mode_order_policy must be 0, 1 or 2");
   if (o->group_mask > 4) return fail(HBCSF_EINVAL, "group_mask must be 0..4");
   if (o->coo_row_flags > 1) return fail(HBCSF_EINVAL, "coo_row_flags must be 0 or 1");
+  if (o->mid_blocking > 13) return fail(HBCSF_EINVAL, "mid_blocking must be 0 or 1 (off) or 2..13 bits");
   if (o->hybrid_granularity != 0)
     return fail(HBCSF_EINVAL, "hybrid_granularity = 1 is built by hbcsf_build_format (host) only");
   *totalBits = total;
+  int bbMax = 0;
+  for (int m = 0; m < order; ++m) {
+    const int bb = mid_block_bits(order, dims, *o, m);
+    bbMax = bb > bbMax ? bb : bbMax;
+  }
+  *maxBits = total + bbMax;
   return HBCSF_OK;
 }
 
@@ -467,7 +478,8 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   sp.NF = N - 2;
   sp.L = opts.fiber_threshold;
   const uint32_t gmask = opts.group_mask == 0 ? 3u : (opts.group_mask & 3u);
-  sp.cooOn = gmask & 1u;
+  sp.blockBits = mid_block_bits(N, dims, opts, mode);
+  sp.cooOn = (gmask & 1u) && sp.blockBits == 0 ? 1u : 0u;   // with blocking no piece owns its row
   sp.cslOn = (gmask & 2u) ? 1u : 0u;
   sp.cooRowFlags = opts.coo_row_flags == 1 ? 1u : 0u;
   int lv[HBCSF_MAX_ORDER];
@@ -481,7 +493,10 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   }
   out->order = N;
   out->mode = mode;
+  sp.blockShift = total;
+  sp.blockDrop = sp.blockBits ? bits_for(dims[lv[1]]) - sp.blockBits : 0;
   out->L = sp.L;
+  out->blockBits = sp.blockBits;
   out->cooRowFlags = sp.cooRowFlags != 0;
   out->rows = dims[mode];
   for (int l = 0; l < N; ++l) out->levelMode[l] = lv[l];
@@ -665,16 +680,16 @@ extern "C" {
 int hbcsf_device_build_bytes(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* opts,
                              uint64_t* arena_bytes, uint64_t* workspace_bytes) try {
   hbcsf_opts o;
-  int totalBits = 0;
-  const int rc = check_args(order, dims, nnz, opts, &o, &totalBits);
+  int totalBits = 0, maxBits = 0;
+  const int rc = check_args(order, dims, nnz, opts, &o, &totalBits, &maxBits);
   if (rc != HBCSF_OK) return rc;
   if (!arena_bytes || !workspace_bytes) return fail(HBCSF_EINVAL, "null argument");
   uint64_t maxDim = 0;
   for (int m = 0; m < order; ++m) maxDim = dims[m] > maxDim ? dims[m] : maxDim;
   size_t tbytes = 0;
-  HIP_TRY(temp_bytes((size_t)nnz, (size_t)((maxDim + 31) / 32), totalBits, &tbytes), "rocPRIM scratch query");
+  HIP_TRY(temp_bytes((size_t)nnz, (size_t)((maxDim + 31) / 32), maxBits, &tbytes), "rocPRIM scratch query");
   Workspace w{};
-  carve(w, nullptr, (size_t)nnz, maxDim, tbytes, totalBits > 64);
+  carve(w, nullptr, (size_t)nnz, maxDim, tbytes, maxBits > 64);
   *workspace_bytes = w.total;
   *arena_bytes = arena_bound(order, dims, nnz, o.fiber_threshold);
   return HBCSF_OK;
@@ -686,8 +701,8 @@ int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, con
   if (!out) return fail(HBCSF_EINVAL, "out is null");
   *out = nullptr;
   hbcsf_opts o;
-  int totalBits = 0;
-  const int rc = check_args(order, dims, nnz, opts, &o, &totalBits);
+  int totalBits = 0, maxBits = 0;
+  const int rc = check_args(order, dims, nnz, opts, &o, &totalBits, &maxBits);
   if (rc != HBCSF_OK) return rc;
   if (nnz > 0 && (!inds || !vals)) return fail(HBCSF_EINVAL, "inds or vals is null");
   for (int m = 0; m < order; ++m)
@@ -699,9 +714,9 @@ int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, con
   uint64_t maxDim = 0;
   for (int m = 0; m < order; ++m) maxDim = dims[m] > maxDim ? dims[m] : maxDim;
   size_t tbytes = 0;
-  HIP_TRY(temp_bytes((size_t)nnz, (size_t)((maxDim + 31) / 32), totalBits, &tbytes), "rocPRIM scratch query");
+  HIP_TRY(temp_bytes((size_t)nnz, (size_t)((maxDim + 31) / 32), maxBits, &tbytes), "rocPRIM scratch query");
   Workspace w{};
-  carve(w, (uint8_t*)workspace, (size_t)nnz, maxDim, tbytes, totalBits > 64);
+  carve(w, (uint8_t*)workspace, (size_t)nnz, maxDim, tbytes, maxBits > 64);
   if (workspace_bytes < w.total) return fail(HBCSF_ENOMEM, "workspace is smaller than hbcsf_device_build_bytes");
 
   std::unique_ptr<hbcsf_tensor> t(new (std::nothrow) hbcsf_tensor);
@@ -720,10 +735,11 @@ int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, con
   for (int m = 0; m < order; ++m) {
     t->modes[m].reset(new (std::nothrow) ModeFormat);
     if (!t->modes[m]) return fail(HBCSF_ENOMEM, "out of host memory");
-    const int rb = totalBits > 64
-                       ? build_mode_device<u128>(order, dims, (size_t)nnz, inds, vals, o, m, totalBits, w,
+    const int modeBits = totalBits + mid_block_bits(order, dims, o, m);   // this mode's key width
+    const int rb = modeBits > 64
+                       ? build_mode_device<u128>(order, dims, (size_t)nnz, inds, vals, o, m, modeBits, w,
                                                  (uint8_t*)device_arena, arena_bytes, &used, t->modes[m].get(), st)
-                       : build_mode_device<uint64_t>(order, dims, (size_t)nnz, inds, vals, o, m, totalBits, w,
+                       : build_mode_device<uint64_t>(order, dims, (size_t)nnz, inds, vals, o, m, modeBits, w,
                                                      (uint8_t*)device_arena, arena_bytes, &used, t->modes[m].get(), st);
     if (rb != HBCSF_OK) return rb;
   }

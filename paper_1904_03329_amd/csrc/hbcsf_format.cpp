@@ -83,7 +83,8 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   const int N = order;
   const uint32_t L = opts.fiber_threshold ? opts.fiber_threshold : 64;
   const uint32_t gmask = opts.group_mask == 0 ? 3u : (opts.group_mask & 3u);
-  const bool cooOn = gmask & 1u, cslOn = gmask & 2u;
+  const int bb = mid_block_bits(order, dims, opts, mode);   // level-1 blocking: block number above the root in the key
+  const bool cooOn = (gmask & 1u) && bb == 0, cslOn = gmask & 2u;
 
   // Tree levels: root = the target mode; the other modes ordered by the policy.
   int lv[HBCSF_MAX_ORDER];
@@ -102,6 +103,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
   out->mode = mode;
   out->L = L;
   out->cooRowFlags = opts.coo_row_flags == 1;
+  out->blockBits = bb;
   out->rows = dims[mode];
   for (int l = 0; l < N; ++l) out->levelMode[l] = lv[l];
 
@@ -127,6 +129,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
       if ((uint64_t)i >= dims[lv[l]]) bad |= 1;
       key |= (Key)i << shift[l];
     }
+    if (bb) key |= (Key)(inds[lv[1]][z] >> (bits[1] - bb)) << total;
     K[z] = key;
     uint32_t vb;
     std::memcpy(&vb, &vals[z], 4);
@@ -139,7 +142,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
 #pragma omp parallel for schedule(static) reduction(| : unsorted)
   for (int64_t z = 1; z < (int64_t)M; ++z)
     if (K[z] < K[z - 1]) unsorted |= 1;
-  if (unsorted) radix_sort_pairs<Key>(K, V, K2, V2, M, total);
+  if (unsorted) radix_sort_pairs<Key>(K, V, K2, V2, M, total + bb);
   if (K == kbuf1.get()) { kbuf2.reset(); vbuf2.reset(); } else { kbuf1.reset(); vbuf1.reset(); }
 
   auto idx = [&](int l, size_t p) -> uint32_t { return (uint32_t)((uint64_t)(K[p] >> shift[l]) & mask[l]); };
@@ -340,7 +343,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
       if (g == kCsl || split) {
         const uint32_t a = split ? offL[s] : off[s], o = split ? ordL[s] : ord[s];
         const uint32_t n = split ? nSingle[s] : (uint32_t)(e - b);
-        own = !split && (a / L) == ((a + n - 1) / L);
+        own = !split && bb == 0 && (a / L) == ((a + n - 1) / L);
         for (uint32_t r = (a + L - 1) / L; r <= (a + n - 1) / L; ++r) cslRun[r] = o;
         cslInd[0][o] = root | (own ? kOwnedBit : 0u);
         cslPtr[o] = a;
@@ -356,7 +359,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
       if (g == kCsf || split) {
         const uint32_t a = off[s], o = ord[s];
         const uint32_t n = split ? (uint32_t)(e - b) - nSingle[s] : (uint32_t)(e - b);
-        own = !split && (a / L) == ((a + n - 1) / L);
+        own = !split && bb == 0 && (a / L) == ((a + n - 1) / L);
         for (uint32_t r = (a + L - 1) / L; r <= (a + n - 1) / L; ++r) csfRun[0][r] = o;
         csfInd[0][o] = root | (own ? kOwnedBit : 0u);
         csfPtr[0][o] = a;
@@ -451,7 +454,7 @@ int build_mode_t(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* 
 int build_mode(int order, const uint64_t* dims, uint64_t nnz, const uint32_t* const* inds,
                const float* vals, const hbcsf_opts& opts, int mode, ModeFormat* out,
                std::string* err) {
-  int total = 0;
+  int total = mid_block_bits(order, dims, opts, mode);
   for (int m = 0; m < order; ++m) total += bits_for(dims[m]);
   try {
     if (total <= 64)

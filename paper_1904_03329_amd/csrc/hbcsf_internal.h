@@ -43,6 +43,7 @@ struct ModeFormat {
   int mode = 0;
   uint32_t L = 64;                 // run length = fiber threshold T_f
   bool cooRowFlags = false;        // the COO group has no root index array (rows come from cooBits / cooPtr)
+  int blockBits = 0;               // level-1 blocking: a slice is stored as one piece per block, none owns its row
   int levelMode[HBCSF_MAX_ORDER] = {};
   uint64_t rows = 0;               // dims[mode]
   GroupFormat g[3];
@@ -187,6 +188,23 @@ inline int bits_for(uint64_t dim) {
   int b = 1;
   while (b < 63 && (1ull << b) < dim) ++b;
   return b;
+}
+
+// Blocking of the first fiber level (Section VIII names blocking as complementary future work).  A mode with
+// few, huge slices whose level-1 factor matrix is far larger than an L2 gathers every level-1 row once per slice,
+// each time after the whole slice has streamed through the cache.  With 2^bits blocks the level-1 index range is
+// cut into equal parts and the nonzeros are ordered by (block, root, level 1, ..., leaf): a slice is stored as
+// one piece per block, all pieces merged with atomic adds, and the pieces of consecutive slices that share a
+// block -- hence the same level-1 rows -- are neighbours in the stream, so those rows are reused from the L2.
+// Returns the number of block bits for this mode (0 = no blocking).  opts.mid_blocking: 0 or 1 = off (the
+// default: on the benchmark's one qualifying mode, 1000 slices over two 40 M-row modes, 20 / 153 / 1221 blocks
+// measured 4 / 10 / 19 % slower than none), 2..13 = that many bits wherever level 1 has more index bits than that.
+inline int mid_block_bits(int N, const uint64_t* dims, const hbcsf_opts& opts, int mode) {
+  int lv[HBCSF_MAX_ORDER];
+  level_order(N, dims, mode, opts.mode_order_policy, lv);
+  const int b1 = bits_for(dims[lv[1]]);
+  if (opts.mid_blocking >= 2) return (int)opts.mid_blocking < b1 ? (int)opts.mid_blocking : 0;
+  return 0;
 }
 
 // Builds one mode's representation.  Returns HBCSF_OK or an error code and fills `err`.

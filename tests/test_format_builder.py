@@ -353,3 +353,39 @@ def test_per_fiber_hybrid_splits_heavy_slices(oracle, order):
     finally:
         B.free(h)
         B.free(h0)
+
+
+@pytest.mark.parametrize("dims,nnz", [((6, 200, 300), 4000), ((5, 64, 9, 40), 3000), ((4, 33, 5, 3, 20), 2000)])
+def test_level_one_blocking(oracle, dims, nnz):
+    """mid_blocking (Section VIII: blocking as complementary work): with 2^b blocks over the level-1 index range the
+    stream is ordered by (block, root, level 1, ..): every slice is stored as one piece per block it has nonzeros in,
+    no piece owns its row, the COO group is unused, and the result is unchanged."""
+    rng = np.random.default_rng(len(dims) * 7 + nnz)
+    inds, vals = _skewed(rng, dims, nnz)
+    facs = _factors(rng, dims, 8)
+    order = len(dims)
+    h = B.build_format(dims, inds, vals, fiber_threshold=8, mode_order_policy=2, mid_blocking=3)
+    h0 = B.build_format(dims, inds, vals, fiber_threshold=8, mode_order_policy=2, mid_blocking=1)
+    try:
+        st, st0 = B.get_stats(h, 0), B.get_stats(h0, 0)
+        fmt = FW.read_mode(h, 0, order)
+        l1 = fmt["level_mode"][1]
+        drop = max(int(np.ceil(np.log2(dims[l1]))), 1) - 3
+        pieces = np.unique(np.stack([inds[0].astype(np.int64), inds[l1].astype(np.int64) >> drop]), axis=1).shape[1]
+        assert st["slices"] == pieces and st0["slices"] == np.unique(inds[0]).shape[0]
+        assert st["group_nnz"][0] == 0 and st["owned_rows"] == 0 and not fmt["owned"].any()
+        assert st["fibers"][0] == st0["fibers"][0]                       # a block boundary never cuts a fiber
+        # pieces are ordered by (block, root): roots restart from the smallest in every block
+        for g in ("csl", "csf"):
+            n = fmt[g]["slices"]
+            assert not (fmt[g]["ind"][0][:n] >> 31).any()                # no piece is marked owned
+        for mode in range(order):
+            f = FW.read_mode(h, mode, order)
+            want = oracle.mttkrp(dims, inds, vals, facs, mode)
+            np.testing.assert_allclose(FW.walk_algorithms(f, facs, dims[mode], 8), want, rtol=1e-10, atol=1e-12)
+            np.testing.assert_allclose(FW.emulate_kernels(f, facs, dims[mode], 8), want, rtol=1e-10, atol=1e-12)
+        with pytest.raises(B.HbcsfError):
+            B.build_format(dims, inds, vals, mid_blocking=14)
+    finally:
+        B.free(h)
+        B.free(h0)

@@ -26,7 +26,8 @@ def tensors(draw):
     vals = rng.uniform(-1, 1, size=nnz).astype(np.float32)
     opts = dict(fiber_threshold=draw(st.sampled_from([0, 8, 16, 32, 64])),
                 group_mask=draw(st.integers(0, 4)), mode_order_policy=draw(st.integers(0, 2)),
-                hybrid_granularity=draw(st.integers(0, 1)), coo_row_flags=draw(st.integers(0, 1)))
+                hybrid_granularity=draw(st.integers(0, 1)), coo_row_flags=draw(st.integers(0, 1)),
+                mid_blocking=draw(st.sampled_from([0, 1, 2, 3])))
     rank = draw(st.sampled_from([8, 16]))
     upw = draw(st.integers(1, 3))
     return dims, inds, vals, opts, rank, upw, seed

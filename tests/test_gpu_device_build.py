@@ -104,7 +104,8 @@ def test_cfg1_arrays_walks_and_mttkrp(oracle, synth):
 
 @pytest.mark.parametrize("opts", [dict(), dict(fiber_threshold=8), dict(fiber_threshold=16), dict(group_mask=4),
                                   dict(group_mask=1), dict(group_mask=2), dict(mode_order_policy=1),
-                                  dict(mode_order_policy=2), dict(coo_row_flags=1)])
+                                  dict(mode_order_policy=2), dict(coo_row_flags=1), dict(mid_blocking=3),
+                                  dict(mid_blocking=5, fiber_threshold=16)])
 @pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000)])
 def test_same_arrays_as_the_host_builder(dims, nnz, opts):
     rng = np.random.default_rng(len(dims) * 1000 + nnz)

@@ -55,7 +55,8 @@ def test_ranks_and_orders(oracle, dims, nnz, rank):
                                   dict(group_mask=1), dict(group_mask=2), dict(mode_order_policy=1),
                                   dict(mode_order_policy=2), dict(tune_ts=256), dict(tune_ts=100_000),
                                   dict(hybrid_granularity=1), dict(hybrid_granularity=1, fiber_threshold=8),
-                                  dict(coo_row_flags=1), dict(tune_dense=1),
+                                  dict(coo_row_flags=1), dict(mid_blocking=4), dict(mid_blocking=2, fiber_threshold=8),
+                                  dict(tune_dense=1),
                                   dict(tune_dense=1, fiber_threshold=32), dict(tune_dense=1, group_mask=4, tune_ts=256)])
 @pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000),
                                       ((1500, 80, 20, 9, 6), 90_000)])
