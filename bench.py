@@ -132,14 +132,27 @@ def calibrate(torch, log) -> int:
         dt = (time.perf_counter() - t0) / 10
         res[name] = {"ms": round(dt * 1e3, 4), "GB/s": round(nbytes / dt / 1e9, 1), "bytes": nbytes}
         log(f"[calibrate] {name}: {res[name]}")
-    # Row-gather ceiling: random 128-byte rows from tables of growing size, no MTTKRP work.
+    # Row-gather ceiling: 128-byte rows from tables of growing size, no MTTKRP work.  Uniform row numbers, and
+    # bounded-Zipf ones (the index laws of the benchmark tensors: popular rows are re-gathered while still cached).
+    import numpy as np
+
     from paper_1904_03329_amd import binding as B
 
     n = 1 << 26
     sink = torch.zeros(4, dtype=torch.float32, device="cuda")
-    for rows in (256, 18_000, 1_000_000, 40_000_000):
+    rng = np.random.default_rng(7)
+    cases = [(256, 0.0), (18_000, 0.0), (1_000_000, 0.0), (40_000_000, 0.0),
+             (2_000, 1.1), (18_000, 1.1), (50_000, 1.1), (40_000_000, 1.05)]
+    for rows, alpha in cases:
         table = torch.zeros((rows, 32), dtype=torch.float32, device="cuda")
-        idx = torch.randint(0, rows, (n,), dtype=torch.int64, device="cuda").to(torch.int32)
+        if alpha > 0:
+            cdf = np.cumsum(np.arange(1, rows + 1, dtype=np.float64) ** -alpha)
+            rank = np.searchsorted(cdf, rng.uniform(0.0, cdf[-1], size=n)).astype(np.int64)
+            rank = np.minimum(rank, rows - 1)
+            idx = torch.from_numpy(((rank * 2654435761) % rows).astype(np.int32)).cuda()   # popular rows scattered
+            del cdf, rank
+        else:
+            idx = torch.randint(0, rows, (n,), dtype=torch.int64, device="cuda").to(torch.int32)
         stream = torch.cuda.current_stream().cuda_stream
         got = B.probe_row_gather(idx.data_ptr(), n, table.data_ptr(), rows, sink.data_ptr(), stream)
         torch.cuda.synchronize()
@@ -148,9 +161,10 @@ def calibrate(torch, log) -> int:
             B.probe_row_gather(idx.data_ptr(), n, table.data_ptr(), rows, sink.data_ptr(), stream)
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / 5
-        res[f"gather_rows_{rows}"] = {"ms": round(dt * 1e3, 4), "Grows/s": round(got / dt / 1e9, 1),
-                                      "GB/s": round(got * 128 / dt / 1e9, 1), "table_MB": round(rows * 128 / 1e6, 1)}
-        log(f"[calibrate] gather, uniform over {rows} rows: {res[f'gather_rows_{rows}']}")
+        law = f"zipf{alpha}" if alpha > 0 else "uniform"
+        res[f"gather_rows_{rows}_{law}"] = {"ms": round(dt * 1e3, 4), "Grows/s": round(got / dt / 1e9, 1),
+                                            "GB/s": round(got * 128 / dt / 1e9, 1), "table_MB": round(rows * 128 / 1e6, 1)}
+        log(f"[calibrate] gather, {law} over {rows} rows: {res[f'gather_rows_{rows}_{law}']}")
         del table, idx
     print(json.dumps({"calibrate": res}), flush=True)
     return 0
@@ -312,6 +326,34 @@ def cpu_baseline_of(np, t, facs, rank, order, log):
     return base
 
 
+def measure_single_representation(torch, np, B, HbcsfTensor, t, facs, rank, full_bytes, steps, log) -> dict:
+    """The single-representation variant (one stored tree instead of one per mode) on the same tensor: device bytes
+    and milliseconds per mode, timed with events on the launch stream (torch's current stream)."""
+    t0 = time.time()
+    ht = HbcsfTensor(t.dims, t.inds, t.vals, single_representation=1).to_device()
+    build_s = time.time() - t0
+    dfacs = [torch.from_numpy(f).cuda() for f in facs]
+    outs = [torch.empty((t.dims[m], rank), dtype=torch.float32, device="cuda") for m in range(t.order)]
+    ms = []
+    for m in range(t.order):
+        ht.mttkrp(m, dfacs, outs[m])
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            ht.mttkrp(m, dfacs, outs[m])
+        b.record()
+        torch.cuda.synchronize()
+        ms.append(a.elapsed_time(b) / steps)
+    res = {"device_bytes": B.device_bytes(ht.handle), "device_bytes_one_per_mode": full_bytes,
+           "build_seconds": round(build_s, 2), "mode_ms": [round(x, 4) for x in ms],
+           "ms_per_step": round(sum(ms), 4),
+           "value": round(3.0 * rank * t.nnz * t.order / (sum(ms) * 1e-3) / 1e9, 1)}
+    ht.close()
+    log(f"[bench] single representation: {json.dumps(res)}")
+    return res
+
+
 def measure(name: str, args, headline: bool, log) -> dict:
     """Generates one workload, builds and uploads its format and times `args.steps` steps (one step = MTTKRP on
     every mode).  The headline workload also gets the device-side build, the CPD-ALS iterations, the per-CU
@@ -448,6 +490,9 @@ def measure(name: str, args, headline: bool, log) -> dict:
     }
     if order == 4:
         res["value_4Rnnz"] = round(value * 4.0 / 3.0, 1)
+    if headline and args.single_representation:
+        res["single_representation"] = measure_single_representation(torch, np, B, HbcsfTensor, t, facs, rank,
+                                                                     B.device_bytes(ht.handle), 5, log)
     if headline:
         if args.cu_spread:
             res["cu_busy_spread"] = trace_cu_spread(torch, np, B, ht, dfacs, outs, order, log)
@@ -474,6 +519,9 @@ def main() -> int:
     ap.add_argument("--slice-threshold", type=int, default=0)
     ap.add_argument("--mode-order-policy", type=int, default=0)
     ap.add_argument("--group-mask", type=int, default=0)
+    ap.add_argument("--single-representation", action="store_true",
+                    help="also time the single-representation variant (only mode 0's tree stored) on the headline "
+                         "workload and report its device bytes and per-mode times under \"single_representation\"")
     ap.add_argument("--mid-blocking", type=int, default=0,
                     help="blocking of the first fiber level: 0 off, 2..13 bits (2^bits blocks) in every mode")
     ap.add_argument("--coo-row-flags", type=int, default=0,
@@ -562,6 +610,8 @@ def main() -> int:
     }
     if "cu_busy_spread" in head:
         line["cu_busy_spread"] = head["cu_busy_spread"]
+    if "single_representation" in head:
+        line["single_representation"] = head["single_representation"]
     print(json.dumps(line), flush=True)
     return 0
 

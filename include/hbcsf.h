@@ -78,6 +78,14 @@ typedef struct hbcsf_opts {
                                  still in the L2.  0 or 1 = off (default); 2..13 = that many bits in every
                                  mode whose level-1 index is wider.  A measured alternative that lost.
                                  hbcsf_stats.slices then counts pieces.                                  */
+  uint32_t single_representation; /* 0 (default): one representation per mode (the "ALLMODE" setting of
+                                 Section VI-A, which the paper uses).  1: only mode 0's representation is
+                                 built and kept (about 1 / order of the device memory), plain B-CSF (no
+                                 COO / CSL groups, default T_f); hbcsf_mttkrp for another mode walks that
+                                 tree with the target at a lower level and adds every fiber's (or, for
+                                 the leaf mode, every nonzero's) contribution with atomic adds: slower,
+                                 rank 32 only for those modes.  Other fields must be 0 (defaults).
+                                 hbcsf_get_stats and hbcsf_host_array answer for mode 0 only.            */
 } hbcsf_opts;
 
 /* Per-mode statistics of the built representation.  "words" are 4-byte index words as the

@@ -38,7 +38,7 @@ class hbcsf_opts(ctypes.Structure):
     _fields_ = [("fiber_threshold", ctypes.c_uint32), ("slice_threshold", ctypes.c_uint32),
                 ("mode_order_policy", ctypes.c_uint32), ("group_mask", ctypes.c_uint32),
                 ("hybrid_granularity", ctypes.c_uint32), ("coo_row_flags", ctypes.c_uint32),
-                ("mid_blocking", ctypes.c_uint32)]
+                ("mid_blocking", ctypes.c_uint32), ("single_representation", ctypes.c_uint32)]
 
 
 class hbcsf_stats(ctypes.Structure):
@@ -135,7 +135,7 @@ def _check(rc):
 
 
 def build_format(dims, inds, vals, fiber_threshold=0, slice_threshold=0, mode_order_policy=0, group_mask=0,
-                 hybrid_granularity=0, coo_row_flags=0, mid_blocking=0):
+                 hybrid_granularity=0, coo_row_flags=0, mid_blocking=0, single_representation=0):
     """hbcsf_build_format: host numpy index arrays (uint32) and values (float32) -> handle."""
     order = len(dims)
     d = np.asarray(dims, dtype=np.uint64)
@@ -146,7 +146,7 @@ def build_format(dims, inds, vals, fiber_threshold=0, slice_threshold=0, mode_or
         if x.shape[0] != nnz:
             raise ValueError("index arrays and vals must have the same length")
     ptrs = (ctypes.c_void_p * max(order, 1))(*[x.ctypes.data for x in inds])
-    opts = hbcsf_opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask, hybrid_granularity, coo_row_flags, mid_blocking)
+    opts = hbcsf_opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask, hybrid_granularity, coo_row_flags, mid_blocking, single_representation)
     h = ctypes.c_void_p()
     _check(lib().hbcsf_build_format(order, d.ctypes.data, nnz, ctypes.cast(ptrs, ctypes.c_void_p),
                                     vals.ctypes.data, ctypes.cast(ctypes.pointer(opts), ctypes.c_void_p),
@@ -154,15 +154,15 @@ def build_format(dims, inds, vals, fiber_threshold=0, slice_threshold=0, mode_or
     return h
 
 
-def _opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask, hybrid_granularity=0, coo_row_flags=0, mid_blocking=0):
-    return hbcsf_opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask, hybrid_granularity, coo_row_flags, mid_blocking)
+def _opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask, hybrid_granularity=0, coo_row_flags=0, mid_blocking=0, single_representation=0):
+    return hbcsf_opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask, hybrid_granularity, coo_row_flags, mid_blocking, single_representation)
 
 
 def device_build_bytes(dims, nnz: int, fiber_threshold=0, slice_threshold=0, mode_order_policy=0, group_mask=0,
-                       hybrid_granularity=0, coo_row_flags=0, mid_blocking=0):
+                       hybrid_granularity=0, coo_row_flags=0, mid_blocking=0, single_representation=0):
     """hbcsf_device_build_bytes: (arena upper bound, workspace) in bytes."""
     d = np.asarray(dims, dtype=np.uint64)
-    opts = _opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask, hybrid_granularity, coo_row_flags, mid_blocking)
+    opts = _opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask, hybrid_granularity, coo_row_flags, mid_blocking, single_representation)
     a, w = ctypes.c_uint64(), ctypes.c_uint64()
     _check(lib().hbcsf_device_build_bytes(len(dims), d.ctypes.data, nnz,
                                           ctypes.cast(ctypes.pointer(opts), ctypes.c_void_p), ctypes.byref(a),
@@ -172,10 +172,10 @@ def device_build_bytes(dims, nnz: int, fiber_threshold=0, slice_threshold=0, mod
 
 def build_format_device(dims, nnz: int, ind_ptrs, val_ptr: int, arena_ptr: int, arena_bytes: int, workspace_ptr: int,
                         workspace_bytes: int, stream: int = 0, fiber_threshold=0, slice_threshold=0,
-                        mode_order_policy=0, group_mask=0, hybrid_granularity=0, coo_row_flags=0, mid_blocking=0):
+                        mode_order_policy=0, group_mask=0, hybrid_granularity=0, coo_row_flags=0, mid_blocking=0, single_representation=0):
     """hbcsf_build_format_device: device addresses of the COO arrays in, resident handle out."""
     d = np.asarray(dims, dtype=np.uint64)
-    opts = _opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask, hybrid_granularity, coo_row_flags, mid_blocking)
+    opts = _opts(fiber_threshold, slice_threshold, mode_order_policy, group_mask, hybrid_granularity, coo_row_flags, mid_blocking, single_representation)
     ptrs = (ctypes.c_void_p * len(dims))(*[(p if p else None) for p in ind_ptrs])
     h = ctypes.c_void_p()
     _check(lib().hbcsf_build_format_device(len(dims), d.ctypes.data, nnz, ctypes.cast(ptrs, ctypes.c_void_p),

@@ -61,6 +61,64 @@ bool pow2_in(uint32_t v, uint32_t lo, uint32_t hi) { return v >= lo && v <= hi &
 
 uint32_t round_up8(uint64_t v) { return (uint32_t)((v + 7) / 8 * 8); }
 
+// Single representation: mode-`mode` MTTKRP from mode 0's B-CSF tree, the target at tree level T >= 1.  The
+// output is zero-filled, then every level-T segment (T = leaf: every nonzero) adds its contribution atomically.
+int mttkrp_from_mode0(const hbcsf_tensor* t, int mode, int rank, const float* const* factors, float* out,
+                      hipStream_t s) {
+  if (rank != 32) return fail(HBCSF_EINVAL, "single representation: modes other than 0 need rank 32");
+  if (!factors[0]) return fail(HBCSF_EINVAL, "a factor pointer is null");
+  const ModeFormat& f = *t->modes[0];
+  const int N = t->order;
+  const int G = 8, NG = 8;
+  int level = 0;
+  for (int l = 1; l < N; ++l)
+    if (f.levelMode[l] == mode) level = l;
+  if (level == 0) return fail(HBCSF_EINVAL, "mode out of range");
+  const uint8_t* base = t->arena + f.devOffset;
+  const GroupFormat& gf = f.g[kCsf];
+  const uint64_t nvec = t->dims[mode] * (uint64_t)G;
+  uint64_t zb = (nvec + 255) / 256;
+  const uint64_t cap = (uint64_t)t->numCU * 32;
+  if (zb > cap) zb = cap;
+  if (zb == 0) zb = 1;
+  hipError_t e = launch_zero_rows(out, nvec, (uint32_t)zb, s);
+  if (e != hipSuccess) return fail_hip(e, "launch of the zero-fill kernel");
+  if (gf.nnz == 0) return HBCSF_OK;
+  GroupArgs a;
+  std::memset(&a, 0, sizeof(a));
+  bool wide = false;
+  for (int l = 0; l < N; ++l) {
+    a.ind[l] = gf.ind[l].present ? (const uint32_t*)(base + gf.ind[l].off) : nullptr;
+    a.ptr[l] = gf.ptr[l].present ? (const uint32_t*)(base + gf.ptr[l].off) : nullptr;
+    a.runFirst[l] = gf.runFirst[l].present ? (const uint32_t*)(base + gf.runFirst[l].off) : nullptr;
+    a.fac[l] = l == level ? nullptr : factors[f.levelMode[l]];
+    if (l != level) wide = wide || t->dims[f.levelMode[l]] * (uint64_t)rank * 4ull >= (1ull << 32);
+  }
+  uint32_t lshift = 0;
+  while ((1u << lshift) < f.L) ++lshift;
+  a.val = (const float*)(base + gf.val.off);
+  a.out = out;
+  a.nnz = (uint32_t)gf.nnz;
+  a.runs = (uint32_t)gf.runs;
+  a.lshift = lshift;
+  a.nUnits = (uint32_t)((gf.runs + NG - 1) / NG);
+  const uint64_t target = (uint64_t)t->numCU * (t->wavesPerCU ? t->wavesPerCU : 128);
+  uint64_t upw = t->sliceThreshold ? t->sliceThreshold / ((uint64_t)NG * f.L) : (a.nUnits + target - 1) / target;
+  if (upw == 0) upw = 1;
+  a.unitsPerWave = (uint32_t)upw;
+  a.nSpans = (uint32_t)((a.nUnits + upw - 1) / upw);
+  const int RW = N == 3 ? 4 : 8;
+  const size_t ldsWave = (size_t)NG * (f.L + 1) * RW * 4;
+  int wpb = 4;
+  while (wpb > 1 && ldsWave * wpb > 48 * 1024) wpb >>= 1;
+  const uint32_t threads = 64 * wpb;
+  e = N == 3   ? launch_nonroot_n3(level, wide, a, threads, ldsWave * wpb, s)
+      : N == 4 ? launch_nonroot_n4(level, wide, a, threads, ldsWave * wpb, s)
+               : launch_nonroot_n5(level, wide, a, threads, ldsWave * wpb, s);
+  if (e != hipSuccess) return fail_hip(e, "launch of the single-representation kernel");
+  return HBCSF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -86,6 +144,13 @@ int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint
   if (o.hybrid_granularity > 1) return fail(HBCSF_EINVAL, "hybrid_granularity must be 0 or 1");
   if (o.coo_row_flags > 1) return fail(HBCSF_EINVAL, "coo_row_flags must be 0 or 1");
   if (o.mid_blocking > 13) return fail(HBCSF_EINVAL, "mid_blocking must be 0 or 1 (off) or 2..13 bits");
+  if (o.single_representation > 1) return fail(HBCSF_EINVAL, "single_representation must be 0 or 1");
+  if (o.single_representation) {
+    if ((opts->fiber_threshold && opts->fiber_threshold != default_fiber_threshold(order)) || o.group_mask ||
+        o.hybrid_granularity || o.coo_row_flags || o.mid_blocking > 1)
+      return fail(HBCSF_EINVAL, "single_representation goes with default options only");
+    o.group_mask = 4;  // plain B-CSF: the kernel for the other modes walks one group
+  }
   std::unique_ptr<hbcsf_tensor> t(new (std::nothrow) hbcsf_tensor);
   if (!t) return fail(HBCSF_ENOMEM, "out of host memory");
   t->order = order;
@@ -97,8 +162,9 @@ int hbcsf_build_format(int order, const uint64_t* dims, uint64_t nnz, const uint
   double sq = 0.0;
   for (uint64_t z = 0; z < nnz; ++z) sq += (double)vals[z] * (double)vals[z];
   t->normSq = sq;
+  t->single = o.single_representation == 1;
   uint64_t off = 0;
-  for (int m = 0; m < order; ++m) {
+  for (int m = 0; m < (t->single ? 1 : order); ++m) {
     t->modes[m].reset(new (std::nothrow) ModeFormat);
     if (!t->modes[m]) return fail(HBCSF_ENOMEM, "out of host memory");
     std::string err;
@@ -120,7 +186,8 @@ int hbcsf_device_bytes(const hbcsf_tensor* t, uint64_t* bytes) try {
 
 int hbcsf_upload(hbcsf_tensor* t, void* device_arena, uint64_t bytes, void* hip_stream) try {
   if (!t || !device_arena) return fail(HBCSF_EINVAL, "null argument");
-  for (int m = 0; m < t->order; ++m)
+  const int nModes = t->single ? 1 : t->order;
+  for (int m = 0; m < nModes; ++m)
     if (!t->modes[m]->blob) return fail(HBCSF_ESTATE, "the format was built on the device: it is already resident");
   if (bytes < t->arenaBytes) return fail(HBCSF_ENOMEM, "device arena is smaller than hbcsf_device_bytes");
   if (((uintptr_t)device_arena & (kAlign - 1)) != 0) return fail(HBCSF_EINVAL, "device arena must be 256-byte aligned");
@@ -132,7 +199,7 @@ int hbcsf_upload(hbcsf_tensor* t, void* device_arena, uint64_t bytes, void* hip_
   e = hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return fail_hip(e, "hipDeviceGetAttribute");
   t->numCU = cu > 0 ? cu : 256;
-  for (int m = 0; m < t->order; ++m) {
+  for (int m = 0; m < nModes; ++m) {
     const ModeFormat& f = *t->modes[m];
     e = hipMemcpyAsync((uint8_t*)device_arena + f.devOffset, f.blob, f.blobBytes, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync");
@@ -157,6 +224,7 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
     if (!factors[m]) return fail(HBCSF_EINVAL, "a factor pointer is null");
     if (((uintptr_t)factors[m] & 15) != 0) return fail(HBCSF_EINVAL, "factors must be 16-byte aligned");
   }
+  if (t->single && mode != 0) return mttkrp_from_mode0(t, mode, rank, factors, out, (hipStream_t)hip_stream);
   const ModeFormat& f = *t->modes[mode];
   const int N = t->order;
   const int G = rank / 4;
@@ -300,6 +368,7 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
 int hbcsf_get_stats(const hbcsf_tensor* t, int mode, hbcsf_stats* stats) try {
   if (!t || !stats) return fail(HBCSF_EINVAL, "null argument");
   if (mode < 0 || mode >= t->order) return fail(HBCSF_EINVAL, "mode out of range");
+  if (t->single && mode != 0) return fail(HBCSF_ESTATE, "single representation: only mode 0 is stored");
   *stats = t->modes[mode]->stats;
   return HBCSF_OK;
 } HBCSF_CATCH_ALL
@@ -308,6 +377,7 @@ int hbcsf_host_array(const hbcsf_tensor* t, int mode, int group, int level, int 
                      const void** ptr, uint64_t* count) try {
   if (!t || !ptr || !count) return fail(HBCSF_EINVAL, "null argument");
   if (mode < 0 || mode >= t->order) return fail(HBCSF_EINVAL, "mode out of range");
+  if (t->single && mode != 0) return fail(HBCSF_ESTATE, "single representation: only mode 0 is stored");
   const ModeFormat& f = *t->modes[mode];
   const ArrayRef* r = nullptr;
   if (array_id == HBCSF_ARR_OWNED_BITS) {

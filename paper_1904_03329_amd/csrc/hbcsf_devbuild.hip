@@ -452,6 +452,8 @@ int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* 
   if (o->mid_blocking > 13) return fail(HBCSF_EINVAL, "mid_blocking must be 0 or 1 (off) or 2..13 bits");
   if (o->hybrid_granularity != 0)
     return fail(HBCSF_EINVAL, "hybrid_granularity = 1 is built by hbcsf_build_format (host) only");
+  if (o->single_representation != 0)
+    return fail(HBCSF_EINVAL, "single_representation = 1 is built by hbcsf_build_format (host) only");
   *totalBits = total;
   int bbMax = 0;
   for (int m = 0; m < order; ++m) {
@@ -777,6 +779,7 @@ int hbcsf_download(hbcsf_tensor* t, void* hip_stream) try {
   if (!t->uploaded || !t->arena) return fail(HBCSF_ESTATE, "the tensor has no device copy");
   hipStream_t st = (hipStream_t)hip_stream;
   for (int m = 0; m < t->order; ++m) {
+    if (!t->modes[m]) continue;   // single representation: only mode 0 exists
     ModeFormat& f = *t->modes[m];
     if (f.blob) continue;
     void* mem = nullptr;

@@ -113,6 +113,15 @@ inline hipError_t launch_define_coo(int order, int G, bool wide, const GroupArgs
 hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, int G,
                          uint32_t blocks, hipStream_t s);
 
+// Zero fill of nvec float4s (an output that is then only reached by atomic adds).
+hipError_t launch_zero_rows(float* out, uint64_t nvec, uint32_t blocks, hipStream_t s);
+
+// Single-representation kernels (rank 32): the target mode is at tree level `level` >= 1 of the representation
+// whose B-CSF group `a` describes (fac[l] set for every level but `level`, fac[0] included).
+hipError_t launch_nonroot_n3(int level, bool wide, const GroupArgs& a, uint32_t threads, size_t ldsBytes, hipStream_t s);
+hipError_t launch_nonroot_n4(int level, bool wide, const GroupArgs& a, uint32_t threads, size_t ldsBytes, hipStream_t s);
+hipError_t launch_nonroot_n5(int level, bool wide, const GroupArgs& a, uint32_t threads, size_t ldsBytes, hipStream_t s);
+
 // Diagnostic row-gather probe: `waves` (a multiple of 4) wavefronts, each gathering `perWave`
 // (a multiple of 64) rows of 32 floats listed in idx.
 hipError_t launch_probe_gather(const uint32_t* idx, uint64_t n, const float* table, float* sink,

@@ -209,7 +209,10 @@ struct UnitEnds {
 };
 
 // fLo: first segment of this unit per fiber level (wave-uniform; = previous unit's fHi).
-template <int G, int N, int LS, bool CSF>
+// START = false: end marks (index + 1 at the LAST nonzero of a segment / slice; slice marks carry the owned bit).
+// START = true : start marks (index + 1 at the FIRST nonzero), for the kernel that needs a level's index while
+//                its segment is still open; a slice that began before the unit has no mark in it (headRow tells).
+template <int G, int N, int LS, bool CSF, bool START = false>
 __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __restrict__ rec, uint32_t u,
                                                const UnitBounds& b, const uint32_t (&fLo)[3], int lane) {
   constexpr int NG = 64 / G;
@@ -281,15 +284,17 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
         fe[l - 1][t] = 0;
         fi[l - 1][t] = 0;
         if (f < b.fHi[l - 1]) {
-          fe[l - 1][t] = __builtin_nontemporal_load(a.ptr[l] + f + 1);
+          fe[l - 1][t] = __builtin_nontemporal_load(a.ptr[l] + f + (START ? 0 : 1));
           fi[l - 1][t] = __builtin_nontemporal_load(a.ind[l] + f);
         }
       }
     }
   }
   // -- issue: slice ends and indices
+  // END marks: the slices that end in this unit are those before the one holding the next unit's first nonzero.
+  // START marks: that slice may itself begin in this unit, so it is looked at too (a position test decides).
   const uint32_t s0 = __builtin_amdgcn_readfirstlane(b.rf);
-  const uint32_t s1 = __shfl(b.rf, NG);
+  const uint32_t s1 = __shfl(b.rf, NG) + (START ? 1u : 0u);
   uint32_t se[KS], si[KS];
 #pragma unroll
   for (int t = 0; t < KS; ++t) {
@@ -297,7 +302,7 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
     se[t] = 0;
     si[t] = 0;
     if (sl < s1) {
-      se[t] = a.ptr[0][sl + 1];
+      se[t] = a.ptr[0][sl + (START ? 0 : 1)];
       si[t] = a.ind[0][sl];
     }
   }
@@ -356,12 +361,12 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
       for (int t = 0; t < KF; ++t) {
         const uint32_t f = fLo[l - 1] + (uint32_t)t * 64u + lane;
         if (f < b.fHi[l - 1]) {
-          const uint32_t p = fe[l - 1][t] - 1u - z0;
+          const uint32_t p = fe[l - 1][t] - (START ? 0u : 1u) - z0;
           rec[(size_t)(p + (p >> ls)) * RW + word] = fi[l - 1][t] + 1u;
         }
       }
       for (uint32_t f = fLo[l - 1] + (uint32_t)KF * 64u + lane; f < b.fHi[l - 1]; f += 64) {
-        const uint32_t p = a.ptr[l][f + 1] - 1u - z0;
+        const uint32_t p = a.ptr[l][f + (START ? 0 : 1)] - (START ? 0u : 1u) - z0;
         rec[(size_t)(p + (p >> ls)) * RW + word] = a.ind[l][f] + 1u;
       }
     }
@@ -370,14 +375,17 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
 #pragma unroll
   for (int t = 0; t < KS; ++t) {
     const uint32_t sl = s0 + (uint32_t)t * 64u + lane;
-    if (sl < s1) {
-      const uint32_t p = se[t] - 1u - z0;
-      rec[(size_t)(p + (p >> ls)) * RW + markWord] = mark_of_slice(si[t]);
+    if (sl < s1 && (!START || (se[t] >= z0 && se[t] < z0 + slots && se[t] < a.nnz))) {
+      const uint32_t p = se[t] - (START ? 0u : 1u) - z0;
+      rec[(size_t)(p + (p >> ls)) * RW + markWord] = START ? (si[t] & 0x7fffffffu) + 1u : mark_of_slice(si[t]);
     }
   }
   for (uint32_t sl = s0 + (uint32_t)KS * 64u + lane; sl < s1; sl += 64) {
-    const uint32_t p = a.ptr[0][sl + 1] - 1u - z0;
-    rec[(size_t)(p + (p >> ls)) * RW + markWord] = mark_of_slice(a.ind[0][sl]);
+    const uint32_t at = a.ptr[0][sl + (START ? 0 : 1)];
+    if (START && (at < z0 || at >= z0 + slots || at >= a.nnz)) continue;
+    const uint32_t p = at - (START ? 0u : 1u) - z0;
+    const uint32_t sv = a.ind[0][sl];
+    rec[(size_t)(p + (p >> ls)) * RW + markWord] = START ? (sv & 0x7fffffffu) + 1u : mark_of_slice(sv);
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 
@@ -704,6 +712,127 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
 }
 
 // ---------------------------------------------------------------------------------------
+// Single-representation variant (Section VI-A's other setting: one representation serves every mode, at 1 / N of
+// the storage).  The target mode sits at tree level T >= 1 of another mode's B-CSF representation (all slices in
+// the CSF group).  A lane group walks its run with START marks and keeps the current row of every level above the
+// leaf; writing i_l for the index at level l,
+//     out(i_T, :) += prod_{l < T} A_l(i_l, :)  *  sum over the level-T segment of  v * prod_{l > T} A_l(i_l, :)
+// is added with atomic adds at the end of each level-T segment (T = leaf: per nonzero; then no leaf row is
+// gathered).  The rows of the levels above the leaf are loaded where they change; leaf rows kSteps at a time.
+// Rank 32 only (G = 8).  Every output row is reached by atomics, so the caller zero-fills the output first.
+// ---------------------------------------------------------------------------------------
+template <int N, int LS, int T, bool WIDE>
+__global__ __launch_bounds__(256) void csf_nonroot_kernel(const GroupArgs a) {
+  constexpr int G = 8;
+  constexpr int NG = 64 / G;
+  constexpr int NF = N - 2;
+  constexpr int RW = (N == 3) ? 4 : 8;
+  constexpr int LEAF = N - 1;
+  constexpr int kSteps = 4;
+  static_assert(T >= 1 && T <= LEAF, "the target is below the root");
+  extern __shared__ uint32_t lds[];
+  const int lane = threadIdx.x & 63;
+  const int wib = threadIdx.x >> 6;
+  const int wpb = blockDim.x >> 6;
+  const int g = lane / G, c = lane % G;
+  constexpr uint32_t L = 1u << LS;
+  uint32_t* rec = lds + (size_t)wib * (NG * (L + 1) * RW);
+
+  const SpanWalk walk = span_walk(a, wib, wpb);
+  for (uint32_t span = walk.first; span < walk.end; span += walk.stride) {
+    uint32_t u = span * a.unitsPerWave;
+    const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
+    UnitBounds cur = load_bounds<G, N, true>(a, u, lane);
+    uint32_t fLo[3] = {0, 0, 0};
+#pragma unroll
+    for (int l = 1; l <= NF; ++l) fLo[l - 1] = a.runFirst[l][u * NG];
+
+    for (; u < uEnd; ++u) {
+      const UnitBounds nxt = load_bounds<G, N, true>(a, min(u + 1, a.nUnits - 1), lane);
+      const UnitEnds ends = stage_unit<G, N, LS, true, true>(a, rec, u, cur, fLo, lane);
+      fLo[0] = cur.fHi[0];
+      fLo[1] = cur.fHi[1];
+      fLo[2] = cur.fHi[2];
+      cur = nxt;
+      const uint32_t ng = ends.ng;
+      if (ng > 0) {
+        // rows of the levels above the leaf (lr[T] unused), their products above / below the target level
+        float4 lr[LEAF];
+#pragma unroll
+        for (int l = 0; l < LEAF; ++l) lr[l] = make_float4(1.f, 1.f, 1.f, 1.f);
+        lr[0] = row_load<G, WIDE>(a.fac[0], ends.headRow, c);   // the slice may have begun in an earlier run
+        float4 up = make_float4(1.f, 1.f, 1.f, 1.f), dn = make_float4(1.f, 1.f, 1.f, 1.f);
+        float4 acc = f4zero();
+        uint32_t curT = 0;
+        bool open = false;
+        const uint32_t* myrec = rec + (size_t)g * (L + 1) * RW;
+        for (uint32_t sb = 0; sb < ng; sb += kSteps) {
+          uint4 rr[kSteps];
+          uint32_t hi0[kSteps], hi1[kSteps];   // record words 4 and 5 (N >= 4)
+          float4 cr[kSteps];
+#pragma unroll
+          for (int t = 0; t < kSteps; ++t) {
+            const uint4* src = reinterpret_cast<const uint4*>(myrec + (size_t)(sb + t) * RW);
+            rr[t] = src[0];
+            hi0[t] = hi1[t] = 0;
+            if (N >= 4) {
+              const uint2 h2 = reinterpret_cast<const uint2*>(src)[2];
+              hi0[t] = h2.x;
+              hi1[t] = h2.y;
+            }
+          }
+          if (T < LEAF) {
+#pragma unroll
+            for (int t = 0; t < kSteps; ++t) cr[t] = row_load<G, WIDE>(a.fac[LEAF], rr[t].x, c);
+          }
+#pragma unroll
+          for (int t = 0; t < kSteps; ++t) {
+            if (sb + (uint32_t)t < ng) {
+              // start marks by level: fiber level l at record word 2 + (NF - l), the slice after them
+              uint32_t mk[LEAF];
+              mk[0] = (N == 3) ? rr[t].w : (N == 4 ? hi0[t] : hi1[t]);
+              mk[LEAF - 1] = rr[t].z;                           // deepest fiber level
+              if constexpr (N >= 4) mk[LEAF - 2] = rr[t].w;
+              if constexpr (N == 5) mk[1] = hi0[t];
+              bool any = false;
+#pragma unroll
+              for (int l = 0; l < LEAF; ++l) any = any || mk[l] != 0u;
+              if (any) {
+                if (T < LEAF && mk[T < LEAF ? T : 0] != 0u) {
+                  if (open) {
+                    row_atomic<G>(a.out, curT, c, mul4(acc, up));
+                    acc = f4zero();
+                  }
+                  curT = mk[T < LEAF ? T : 0] - 1u;
+                  open = true;
+                }
+#pragma unroll
+                for (int l = 0; l < LEAF; ++l)
+                  if (l != T && mk[l] != 0u) lr[l] = row_load<G, WIDE>(a.fac[l], mk[l] - 1u, c);
+                up = lr[0];
+#pragma unroll
+                for (int l = 1; l < T && l < LEAF; ++l) up = mul4(up, lr[l]);
+                dn = make_float4(1.f, 1.f, 1.f, 1.f);
+#pragma unroll
+                for (int l = T + 1; l < LEAF; ++l) dn = mul4(dn, lr[l]);
+              }
+              const float v = __uint_as_float(rr[t].y);
+              if (T == LEAF) {
+                row_atomic<G>(a.out, rr[t].x, c, scale4(v, up));
+              } else {
+                fma4(acc, v, mul4(cr[t], dn));
+              }
+            }
+          }
+        }
+        if (T < LEAF && open) row_atomic<G>(a.out, curT, c, mul4(acc, up));
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // CSL group (Algorithm "CSL-MTTKRP"): every nonzero carries all its non-root indices; the
 // slice pointer goes straight to the nonzeros.
 // LDS record: N = 3: {j, k, val, slice mark}; N = 4: {a, b, l, val, slice mark, -, -, -};
@@ -1025,7 +1154,50 @@ hipError_t HBCSF_CAT(launch_group_g, HBCSF_G, _n, HBCSF_N)(int kind, int steps, 
   return launch_g<HBCSF_G, HBCSF_N>(kind, steps, wide, a, dim3(blocks), dim3(threads), ldsBytes, s);
 }
 
+#if HBCSF_G == 8
+namespace {
+template <int N, int LS, int T>
+hipError_t launch_nonroot_t(bool wide, const GroupArgs& a, uint32_t threads, size_t lds, hipStream_t s) {
+  const uint32_t wpb = threads >> 6;
+  const uint64_t blocks = (((uint64_t)a.nSpans + wpb - 1) / wpb + 7) / 8 * 8;
+  if (wide) hipLaunchKernelGGL((csf_nonroot_kernel<N, LS, T, true>), dim3((uint32_t)blocks), dim3(threads), lds, s, a);
+  else hipLaunchKernelGGL((csf_nonroot_kernel<N, LS, T, false>), dim3((uint32_t)blocks), dim3(threads), lds, s, a);
+  return hipGetLastError();
+}
+}  // namespace
+
+// Single-representation kernel for this object's order: target at tree level `level` (1 .. order-1) of the
+// representation in `a` (B-CSF group only, runs of the order's default length), rank 32.
+hipError_t HBCSF_CAT(launch_nonroot_n, HBCSF_N, , )(int level, bool wide, const GroupArgs& a, uint32_t threads,
+                                                     size_t ldsBytes, hipStream_t s) {
+  constexpr int LS = HBCSF_N == 3 ? 6 : 5;
+  if (a.lshift != (uint32_t)LS || a.persistent) return hipErrorInvalidValue;
+  switch (level) {
+    case 1: return launch_nonroot_t<HBCSF_N, LS, 1>(wide, a, threads, ldsBytes, s);
+    case 2: return launch_nonroot_t<HBCSF_N, LS, 2>(wide, a, threads, ldsBytes, s);
+#if HBCSF_N >= 4
+    case 3: return launch_nonroot_t<HBCSF_N, LS, 3>(wide, a, threads, ldsBytes, s);
+#endif
+#if HBCSF_N >= 5
+    case 4: return launch_nonroot_t<HBCSF_N, LS, 4>(wide, a, threads, ldsBytes, s);
+#endif
+    default: return hipErrorInvalidValue;
+  }
+}
+#endif  // HBCSF_G == 8
+
 #ifdef HBCSF_WITH_DEFINE
+// Plain zero fill of an output every row of which is then reached by atomic adds (the single-representation kernel).
+__global__ __launch_bounds__(256) void zero_rows_kernel(float4* __restrict__ out, uint64_t nvec) {
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (uint64_t)gridDim.x * 256)
+    store_streaming(out + i, f4zero());
+}
+
+hipError_t launch_zero_rows(float* out, uint64_t nvec, uint32_t blocks, hipStream_t s) {
+  hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<float4*>(out), nvec);
+  return hipGetLastError();
+}
+
 hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, int G, uint32_t blocks,
                          hipStream_t s) {
   int gshift = 0;

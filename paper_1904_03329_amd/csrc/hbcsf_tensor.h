@@ -20,6 +20,7 @@ struct hbcsf_tensor {
   uint64_t arenaBytes = 0;
   uint8_t* arena = nullptr;  // caller's device memory
   bool uploaded = false;
+  bool single = false;       // only modes[0] exists; the other modes are computed from it (single representation)
   int numCU = 256;
   uint64_t sliceThreshold = 0;
   uint64_t wavesPerCU = 0;   // launch sizing override, 0 = default

@@ -240,3 +240,61 @@ def emulate_kernels(fmt, factors, rows, rank, units_per_wave=2):
     _emulate_group("csf", fmt["csf"], fmt, fac, out, rank, lane_groups, units_per_wave)
     out.check()
     return out.y
+
+
+def emulate_nonroot(fmt, factors, target_mode, rows, rank):
+    """The schedule of the single-representation kernel (target mode at a tree level T >= 1 of another mode's
+    B-CSF representation), in fp64: every lane group walks its run of L nonzeros with START marks (index + 1 at the
+    first nonzero of each slice / fiber segment), keeps the rows of the levels above the leaf, and adds
+        out(i_T) += (product of the rows above level T) * sum over the level-T segment of v * (rows below level T)
+    at the end of each level-T segment (T = leaf: per nonzero).  Only the CSF group may hold nonzeros."""
+    order, L = fmt["order"], fmt["L"]
+    assert fmt["coo"]["nnz"] == 0 and fmt["csl"]["nnz"] == 0
+    g = fmt["csf"]
+    T = fmt["level_mode"].index(target_mode)
+    assert T >= 1
+    leaf = order - 1
+    fac = [factors[fmt["level_mode"][l]].astype(np.float64) for l in range(order)]
+    out = np.zeros((rows, rank))
+    nnz = g["nnz"]
+    runs = (nnz + L - 1) // L
+    starts = {}
+    for l in range(order - 1):
+        n = len(g["ind"][l]) - 1
+        mark = np.zeros(nnz, dtype=np.int64)
+        mark[g["ptr"][l][:n].astype(np.int64)] = (g["ind"][l][:n].astype(np.int64) & 0x7FFFFFFF) + 1
+        starts[l] = mark
+    for r in range(runs):
+        z0, z1 = r * L, min((r + 1) * L, nnz)
+        head = int(g["ind"][0][g["run"][0][r]]) & 0x7FFFFFFF
+        cur = [None] * order
+        cur[0] = head
+        acc, is_open = np.zeros(rank), False
+        up = dn = None
+        for z in range(z0, z1):
+            marks = [int(starts[l][z]) for l in range(order - 1)]
+            if any(marks):
+                if T < leaf and marks[T] and is_open:
+                    out[cur[T]] += acc * up
+                    acc = np.zeros(rank)
+                for l in range(order - 1):
+                    if marks[l]:
+                        cur[l] = marks[l] - 1
+                        if l == T:
+                            is_open = True
+                assert all(cur[l] is not None for l in range(order - 1)), "a level has no index yet: missing start mark"
+                up = np.ones(rank)
+                for l in range(T):
+                    up = up * fac[l][cur[l]]
+                dn = np.ones(rank)
+                for l in range(T + 1, leaf):
+                    dn = dn * fac[l][cur[l]]
+            v = float(g["val"][z])
+            k = int(g["ind"][leaf][z])
+            if T == leaf:
+                out[k] += v * up
+            else:
+                acc = acc + v * fac[leaf][k] * dn
+        if T < leaf and is_open:
+            out[cur[T]] += acc * up
+    return out

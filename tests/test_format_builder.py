@@ -389,3 +389,36 @@ def test_level_one_blocking(oracle, dims, nnz):
     finally:
         B.free(h)
         B.free(h0)
+
+
+@pytest.mark.parametrize("dims,nnz", [((30, 20, 25), 1500), ((12, 9, 10, 7), 1200), ((6, 5, 7, 4, 9), 1500)])
+def test_single_representation(oracle, dims, nnz):
+    """single_representation = 1 (the one-representation setting Section VI-A sets aside for ALLMODE): only mode 0's
+    plain B-CSF tree is stored; the walk that serves another mode -- start marks, target at a lower tree level, one
+    atomic contribution per level-T segment -- reproduces the oracle for every mode."""
+    rng = np.random.default_rng(len(dims) * 13 + nnz)
+    inds, vals = _skewed(rng, dims, nnz)
+    facs = _factors(rng, dims, 8)
+    order = len(dims)
+    h = B.build_format(dims, inds, vals, single_representation=1)
+    h_all = B.build_format(dims, inds, vals, group_mask=4)
+    try:
+        assert B.device_bytes(h) == pytest.approx(B.device_bytes(h_all) / order, rel=0.5)
+        assert B.device_bytes(h) < 0.6 * B.device_bytes(h_all)
+        st = B.get_stats(h, 0)
+        assert st["group_nnz"] == [0, 0, vals.shape[0]]
+        with pytest.raises(B.HbcsfError) as e:
+            B.get_stats(h, 1)
+        assert e.value.code == -4
+        fmt = FW.read_mode(h, 0, order)
+        np.testing.assert_allclose(FW.emulate_kernels(fmt, facs, dims[0], 8), oracle.mttkrp(dims, inds, vals, facs, 0),
+                                   rtol=1e-10, atol=1e-12)
+        for mode in range(1, order):
+            np.testing.assert_allclose(FW.emulate_nonroot(fmt, facs, mode, dims[mode], 8),
+                                       oracle.mttkrp(dims, inds, vals, facs, mode), rtol=1e-10, atol=1e-12)
+        for bad in (dict(group_mask=1), dict(fiber_threshold=8), dict(coo_row_flags=1), dict(mid_blocking=3)):
+            with pytest.raises(B.HbcsfError):
+                B.build_format(dims, inds, vals, single_representation=1, **bad)
+    finally:
+        B.free(h)
+        B.free(h_all)

@@ -133,6 +133,40 @@ def test_dense_fiber_row_gather(oracle, dims, nnz, a):
     assert all(s["group_nnz"][2] == vals.shape[0] for s in stats)
 
 
+@pytest.mark.parametrize("dims,nnz,a", [((3000, 700, 90), 200_000, 1.3), ((900, 300, 40, 25), 150_000, 1.2),
+                                        ((600, 200, 30, 12, 8), 120_000, 1.1), ((40, 9000, 11_000), 90_000, 0.6),
+                                        ((3, 50, 4000), 10_007, 0.0)])
+def test_single_representation(oracle, dims, nnz, a):
+    """single_representation = 1: mode 0 from its own B-CSF tree, every other mode from the same tree with the
+    target at a lower level (atomic contributions), rank 32; heavy slices, long fibers, a ragged last unit."""
+    import torch
+    from paper_1904_03329_amd import HbcsfTensor
+
+    rng = np.random.default_rng(len(dims) * 17 + nnz % 89)
+    if a > 0:
+        inds, vals = _skewed(rng, dims, nnz, a=a)
+    else:
+        inds = [rng.integers(0, d, nnz).astype(np.uint32) for d in dims]
+        vals = rng.uniform(-1, 1, nnz).astype(np.float32)
+    facs = _factors(rng, dims, 32)
+    print("single representation", dims, vals.shape[0], flush=True)
+    t = HbcsfTensor(dims, inds, vals, single_representation=1).to_device()
+    full = HbcsfTensor(dims, inds, vals, group_mask=4)
+    assert B.device_bytes(t.handle) < 0.6 * B.device_bytes(full.handle)
+    full.close()
+    dfacs = [torch.from_numpy(f).cuda() for f in facs]
+    for mode in range(len(dims)):
+        out = torch.full((dims[mode], 32), float("nan"), dtype=torch.float32, device="cuda")
+        t.mttkrp(mode, dfacs, out)
+        torch.cuda.synchronize()
+        GU.assert_close(out.cpu().numpy(), oracle.mttkrp(dims, inds, vals, facs, mode), f"single representation mode {mode}")
+    f8 = [torch.zeros((d, 8), device="cuda") for d in dims]
+    with pytest.raises(B.HbcsfError) as e:
+        t.mttkrp(1, f8, torch.zeros((dims[1], 8), device="cuda"))
+    assert e.value.code == -1
+    t.close()
+
+
 def test_degenerate_shapes(oracle):
     rng = np.random.default_rng(31)
     # one heavy slice only (every partial row merged with atomics), ragged tail
