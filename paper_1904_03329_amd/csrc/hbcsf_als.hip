@@ -567,6 +567,35 @@ int current_cu_count(int* cu) {
 
 }  // namespace
 
+namespace {
+
+// Scales the columns of every stored factor whose normalisation was put off, so that the stored matrices are the
+// algorithm's unit-norm factors again; the Gram matrices the state keeps are scaled with them.
+int apply_pending_normalisation(hbcsf_als* a, float* const* factors, hipStream_t st) {
+  const hbcsf_tensor* t = a->t;
+  const int order = t->order, R = a->rank;
+  for (int m = 0; m < order; ++m) {
+    bool pending = false;
+    for (int r = 0; r < R; ++r) pending = pending || a->colScale[m][r] != 1.0;
+    if (!pending) continue;
+    float* hs = a->hostScale + (size_t)m * R;
+    float* ds = a->p + (size_t)R * R + (size_t)m * R;
+    for (int r = 0; r < R; ++r) hs[r] = (float)(1.0 / a->colScale[m][r]);
+    hipError_t e = hipMemcpyAsync(ds, hs, (size_t)R * 4, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync");
+    launch_scale_columns(factors[m], t->dims[m], R, ds, t->numCU, st);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "column scaling kernel launch");
+    if (a->gramsValid)
+      for (int i = 0; i < R; ++i)
+        for (int j = 0; j < R; ++j) a->gram[m][(size_t)i * R + j] /= a->colScale[m][i] * a->colScale[m][j];
+    a->colScale[m].assign((size_t)R, 1.0);
+  }
+  return HBCSF_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 int hbcsf_gram_workspace_bytes(int rank, uint64_t* bytes) try {
@@ -681,35 +710,6 @@ int hbcsf_als_create(const hbcsf_tensor* t, int rank, void* workspace, uint64_t 
   *out = a.release();
   return HBCSF_OK;
 } HBCSF_CATCH_ALL
-
-namespace {
-
-// Scales the columns of every stored factor whose normalisation was put off, so that the stored matrices are the
-// algorithm's unit-norm factors again; the Gram matrices the state keeps are scaled with them.
-int apply_pending_normalisation(hbcsf_als* a, float* const* factors, hipStream_t st) {
-  const hbcsf_tensor* t = a->t;
-  const int order = t->order, R = a->rank;
-  for (int m = 0; m < order; ++m) {
-    bool pending = false;
-    for (int r = 0; r < R; ++r) pending = pending || a->colScale[m][r] != 1.0;
-    if (!pending) continue;
-    float* hs = a->hostScale + (size_t)m * R;
-    float* ds = a->p + (size_t)R * R + (size_t)m * R;
-    for (int r = 0; r < R; ++r) hs[r] = (float)(1.0 / a->colScale[m][r]);
-    hipError_t e = hipMemcpyAsync(ds, hs, (size_t)R * 4, hipMemcpyHostToDevice, st);
-    if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync");
-    launch_scale_columns(factors[m], t->dims[m], R, ds, t->numCU, st);
-    e = hipGetLastError();
-    if (e != hipSuccess) return fail_hip(e, "column scaling kernel launch");
-    if (a->gramsValid)
-      for (int i = 0; i < R; ++i)
-        for (int j = 0; j < R; ++j) a->gram[m][(size_t)i * R + j] /= a->colScale[m][i] * a->colScale[m][j];
-    a->colScale[m].assign((size_t)R, 1.0);
-  }
-  return HBCSF_OK;
-}
-
-}  // namespace
 
 int hbcsf_als_iteration(hbcsf_als* a, float* const* factors, float* lambda, int flags, double* fit,
                         void* hip_stream) try {

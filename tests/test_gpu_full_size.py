@@ -33,7 +33,9 @@ def _compare_all_rows(out, want, empty_row, what, block=1 << 21):
     return err / max(scale, 1e-30), zero_rows
 
 
-def _run_workload(oracle, synth, name):
+def _run_workload(oracle, synth, name, extra_opts=None):
+    """extra_opts: build options of a second handle whose results are compared with the same oracle results (the
+    optional format variants at full size)."""
     import torch
     from paper_1904_03329_amd import HbcsfTensor
 
@@ -43,6 +45,7 @@ def _run_workload(oracle, synth, name):
     t0 = time.time()
     ht = HbcsfTensor(t.dims, t.inds, t.vals).to_device()
     print(f"{name}: built + uploaded in {time.time() - t0:.1f}s", flush=True)
+    variant = HbcsfTensor(t.dims, t.inds, t.vals, **extra_opts).to_device() if extra_opts else None
     dfacs = [torch.from_numpy(f).cuda() for f in facs]
     invariant, scale = [], []
     for mode in range(t.order):
@@ -57,6 +60,12 @@ def _run_workload(oracle, synth, name):
         t_or = time.time() - t0
         empty_row = np.bincount(t.inds[mode], minlength=t.dims[mode]) == 0
         rel, zero_rows = _compare_all_rows(out, want, empty_row, f"{name} mode {mode}")
+        if variant is not None:
+            out.fill_(float("nan"))
+            variant.mttkrp(mode, dfacs, out)
+            torch.cuda.synchronize()
+            rel_v, _ = _compare_all_rows(out, want, empty_row, f"{name} mode {mode} with {extra_opts}")
+            print(f"{name} mode {mode} with {extra_opts}: max|diff|/max|M| = {rel_v:.2e}", flush=True)
         del want
         print(f"{name} mode {mode}: all {t.dims[mode]} rows, {zero_rows} of them zero, max|diff|/max|M| = {rel:.2e} "
               f"(oracle {t_or:.1f}s, compare {time.time() - t0 - t_or:.1f}s)", flush=True)
@@ -64,6 +73,8 @@ def _run_workload(oracle, synth, name):
     spread = (max(invariant) - min(invariant)) / max(scale)
     assert spread < 1e-5, f"{name}: cross-mode invariant differs by {spread:.2e}: {invariant}"
     del dfacs
+    if variant is not None:
+        variant.close()
     _device_build_matches(t, ht, name)
     ht.close()
 
@@ -120,7 +131,7 @@ def test_cfg3_every_element(oracle, synth):
 
 
 def test_cfg4_every_element(oracle, synth):
-    _run_workload(oracle, synth, "cfg4")
+    _run_workload(oracle, synth, "cfg4", extra_opts=dict(hybrid_granularity=1, mid_blocking=6))
 
 
 def test_cfg5_every_element(oracle, synth):
@@ -129,4 +140,5 @@ def test_cfg5_every_element(oracle, synth):
     have = _host_gib_available()
     if have < need:
         pytest.skip(f"cfg5 with the oracle's full fp64 result needs about {need:.0f} GiB of host memory, {have:.0f} GiB available")
-    _run_workload(oracle, synth, "cfg5")
+    # the second handle: COO / CSL / CSF chosen per fiber, COO rows from row flags (the fused output-definition pass)
+    _run_workload(oracle, synth, "cfg5", extra_opts=dict(hybrid_granularity=1, coo_row_flags=1))
