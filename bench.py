@@ -154,17 +154,23 @@ def calibrate(torch, log) -> int:
         else:
             idx = torch.randint(0, rows, (n,), dtype=torch.int64, device="cuda").to(torch.int32)
         stream = torch.cuda.current_stream().cuda_stream
-        got = B.probe_row_gather(idx.data_ptr(), n, table.data_ptr(), rows, sink.data_ptr(), stream)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(5):
-            B.probe_row_gather(idx.data_ptr(), n, table.data_ptr(), rows, sink.data_ptr(), stream)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / 5
         law = f"zipf{alpha}" if alpha > 0 else "uniform"
-        res[f"gather_rows_{rows}_{law}"] = {"ms": round(dt * 1e3, 4), "Grows/s": round(got / dt / 1e9, 1),
-                                            "GB/s": round(got * 128 / dt / 1e9, 1), "table_MB": round(rows * 128 / 1e6, 1)}
-        log(f"[calibrate] gather, {law} over {rows} rows: {res[f'gather_rows_{rows}_{law}']}")
+        # 8: every lane of a load instruction gathers; 2 / 1 (small tables only): the B-CSF kernel's fiber-row
+        # loads, which only the lane groups whose segment ends at that step execute
+        for active in ((8, 2, 1) if rows <= 18_000 and alpha == 0 else (8,)):
+            got, instr = B.probe_row_gather(idx.data_ptr(), n, table.data_ptr(), rows, sink.data_ptr(), stream, active)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                B.probe_row_gather(idx.data_ptr(), n, table.data_ptr(), rows, sink.data_ptr(), stream, active)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / 5
+            key = f"gather_rows_{rows}_{law}" + ("" if active == 8 else f"_active{active}of8")
+            res[key] = {"ms": round(dt * 1e3, 4), "Grows/s": round(got / dt / 1e9, 1),
+                        "GB/s": round(got * 128 / dt / 1e9, 1), "table_MB": round(rows * 128 / 1e6, 1),
+                        "active_lane_groups": active, "G_load_instr/s": round(instr / dt / 1e9, 2),
+                        "ns_per_load_instr_per_CU": round(dt * 1e9 * torch.cuda.get_device_properties(0).multi_processor_count / instr, 2)}
+            log(f"[calibrate] gather, {law} over {rows} rows, {active} of 8 lane groups per load: {res[key]}")
         del table, idx
     print(json.dumps({"calibrate": res}), flush=True)
     return 0
@@ -398,6 +404,8 @@ def measure(name: str, args, headline: bool, log) -> dict:
         B.tune(ht.handle, B.TUNE_WAVES_PER_CU, args.waves_per_cu)
     if args.kernel_steps:
         B.tune(ht.handle, B.TUNE_STEPS, args.kernel_steps)
+    if args.fiber_row_gather:
+        B.tune(ht.handle, B.TUNE_DENSE_MID, args.fiber_row_gather)
     B.tune(ht.handle, B.TUNE_PROFILE, order * args.steps)
     for _ in range(args.warmup):
         step()
@@ -530,6 +538,8 @@ def main() -> int:
                     help="1: COO / CSL / CSF chosen per fiber inside heavy slices (host builder only)")
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--kernel-steps", type=int, default=0)
+    ap.add_argument("--fiber-row-gather", type=int, default=0,
+                    help="B-CSF kernel variant: 1 = fiber-level rows gathered through an LDS row cache")
     ap.add_argument("--als-iterations", type=int, default=3,
                     help="after the timed MTTKRP steps, time this many CPD-ALS iterations built on the same "
                          "library (reported under \"als\", not part of `value`); 0 skips them")

@@ -357,14 +357,21 @@ int hbcsf_sym_pinv(const double *v, int n, double *out);
 void hbcsf_als_free(hbcsf_als *a);
 
 /* Diagnostic, not part of the MTTKRP path: launches a kernel that only gathers rows of 32 floats
- * (128 bytes, the R = 32 factor row) with the B-CSF kernel's lane mapping and discards them, so
- * that the row-gather rate the memory system sustains can be put beside the kernels' rates.
+ * (128 bytes, the R = 32 factor row) with the B-CSF kernel's lane mapping (8 lanes per row, 8 rows
+ * per wavefront-level load instruction, 8 such instructions in flight) and discards them, so that
+ * the row-gather rate the memory system sustains can be put beside the kernels' rates.
  *   idx        device [n] row numbers, each < table_rows (the caller guarantees this; n >= 65536).
  *   table      device [table_rows][32] floats.     sink  device, at least 4 bytes.
- *   rows_gathered  host, receives the number of rows the launch gathers (<= n).
+ *   active_lane_groups  1..8: how many of a wavefront's 8 lane groups take part in each load
+ *              instruction (8: every lane loads; fewer: the B-CSF kernel's fiber-row loads, which
+ *              only the lane groups whose segment ends at that step execute).  The entries of idx
+ *              that fall to a lane group sitting an instruction out are skipped.
+ *   rows_gathered      host, receives the number of rows the launch gathers (<= n).
+ *   load_instructions  host or NULL, receives the wavefront-level row-load instructions issued.
  * Asynchronous on hip_stream; the caller times it. */
 int hbcsf_probe_row_gather(const uint32_t *idx, uint64_t n, const float *table, uint64_t table_rows,
-                           float *sink, void *hip_stream, uint64_t *rows_gathered);
+                           int active_lane_groups, float *sink, void *hip_stream, uint64_t *rows_gathered,
+                           uint64_t *load_instructions);
 
 void hbcsf_free(hbcsf_tensor *t);
 

@@ -88,7 +88,7 @@ def lib():
         L.hbcsf_kernel_ms.restype = i32
         L.hbcsf_kernel_ms.argtypes = [vp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_float * 4)]
         L.hbcsf_probe_row_gather.restype = i32
-        L.hbcsf_probe_row_gather.argtypes = [vp, u64, vp, u64, vp, vp, ctypes.POINTER(u64)]
+        L.hbcsf_probe_row_gather.argtypes = [vp, u64, vp, u64, i32, vp, vp, ctypes.POINTER(u64), ctypes.POINTER(u64)]
         L.hbcsf_free.restype = None
         L.hbcsf_free.argtypes = [vp]
         L.hbcsf_strerror.restype = ctypes.c_char_p
@@ -249,12 +249,14 @@ def kernel_ms(h, calls_back: int = 0):
     return [float(x) for x in ms]
 
 
-def probe_row_gather(idx_ptr: int, n: int, table_ptr: int, table_rows: int, sink_ptr: int, stream: int = 0) -> int:
-    """hbcsf_probe_row_gather: returns the number of rows the launch gathers."""
-    rows = ctypes.c_uint64()
+def probe_row_gather(idx_ptr: int, n: int, table_ptr: int, table_rows: int, sink_ptr: int, stream: int = 0,
+                     active_lane_groups: int = 8):
+    """hbcsf_probe_row_gather: returns (rows the launch gathers, wavefront-level row-load instructions it issues)."""
+    rows, instr = ctypes.c_uint64(), ctypes.c_uint64()
     _check(lib().hbcsf_probe_row_gather(ctypes.c_void_p(idx_ptr), n, ctypes.c_void_p(table_ptr), table_rows,
-                                        ctypes.c_void_p(sink_ptr), ctypes.c_void_p(stream), ctypes.byref(rows)))
-    return int(rows.value)
+                                        active_lane_groups, ctypes.c_void_p(sink_ptr), ctypes.c_void_p(stream),
+                                        ctypes.byref(rows), ctypes.byref(instr)))
+    return int(rows.value), int(instr.value)
 
 
 def als_workspace_bytes(h, rank: int) -> int:

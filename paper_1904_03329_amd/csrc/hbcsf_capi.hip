@@ -491,8 +491,10 @@ int hbcsf_kernel_ms(hbcsf_tensor* t, uint32_t calls_back, float ms[4]) try {
 } HBCSF_CATCH_ALL
 
 int hbcsf_probe_row_gather(const uint32_t* idx, uint64_t n, const float* table, uint64_t table_rows,
-                           float* sink, void* hip_stream, uint64_t* rows_gathered) try {
+                           int active_lane_groups, float* sink, void* hip_stream, uint64_t* rows_gathered,
+                           uint64_t* load_instructions) try {
   if (!idx || !table || !sink || !rows_gathered) return fail(HBCSF_EINVAL, "null argument");
+  if (active_lane_groups < 1 || active_lane_groups > 8) return fail(HBCSF_EINVAL, "active lane groups must be 1..8");
   if (table_rows == 0 || n < 64 * 1024) return fail(HBCSF_EINVAL, "need a table and at least 65536 indices");
   int dev = 0, cu = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -507,9 +509,11 @@ int hbcsf_probe_row_gather(const uint32_t* idx, uint64_t n, const float* table, 
   }
   waves = waves / 4 * 4;
   if (perWave == 0 || waves == 0) return fail(HBCSF_EINVAL, "too few indices");
-  e = launch_probe_gather(idx, n, table, sink, (uint32_t)waves, (uint32_t)perWave, (hipStream_t)hip_stream);
+  e = launch_probe_gather(idx, n, table, sink, (uint32_t)waves, (uint32_t)perWave, active_lane_groups,
+                          (hipStream_t)hip_stream);
   if (e != hipSuccess) return fail_hip(e, "launch of the gather probe");
-  *rows_gathered = waves * perWave;
+  *rows_gathered = waves * perWave / 8 * (uint64_t)active_lane_groups;
+  if (load_instructions) *load_instructions = waves * perWave / 8;  // row loads: one per 8 index entries walked
   return HBCSF_OK;
 } HBCSF_CATCH_ALL
 

@@ -122,10 +122,11 @@ hipError_t launch_nonroot_n3(int level, bool wide, const GroupArgs& a, uint32_t 
 hipError_t launch_nonroot_n4(int level, bool wide, const GroupArgs& a, uint32_t threads, size_t ldsBytes, hipStream_t s);
 hipError_t launch_nonroot_n5(int level, bool wide, const GroupArgs& a, uint32_t threads, size_t ldsBytes, hipStream_t s);
 
-// Diagnostic row-gather probe: `waves` (a multiple of 4) wavefronts, each gathering `perWave`
-// (a multiple of 64) rows of 32 floats listed in idx.
+// Diagnostic row-gather probe: `waves` (a multiple of 4) wavefronts, each walking `perWave`
+// (a multiple of 64) entries of idx (row numbers of a table of 32-float rows); `active` (1..8) of a
+// wavefront's 8 lane groups take part in each load instruction.
 hipError_t launch_probe_gather(const uint32_t* idx, uint64_t n, const float* table, float* sink,
-                               uint32_t waves, uint32_t perWave, hipStream_t s);
+                               uint32_t waves, uint32_t perWave, int active, hipStream_t s);
 
 }  // namespace hbcsf
 

@@ -1211,10 +1211,13 @@ hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, i
 // Diagnostic: the row-gather rate the memory system sustains for this access shape (128-byte
 // rows, 8 lanes x float4, 8 gathers in flight per lane group), with none of the MTTKRP work
 // around it.  Used to put a measured ceiling beside the kernels' achieved rates.
+// `active` (1..8): load instruction t of a block of 8 is executed by the lane groups g with
+// (g - t) mod 8 < active only, the others sit it out, as the lane groups without a segment end
+// do in the B-CSF kernel's fiber-row loads; every instruction is still issued by the wavefront.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void probe_gather_kernel(const uint32_t* __restrict__ idx, uint64_t n,
                                                            const float* __restrict__ table,
-                                                           float* __restrict__ sink, uint32_t perWave) {
+                                                           float* __restrict__ sink, uint32_t perWave, int active) {
   constexpr int S = 8;
   const int lane = threadIdx.x & 63;
   const int g = lane >> 3, c = lane & 7;
@@ -1224,13 +1227,17 @@ __global__ __launch_bounds__(256) void probe_gather_kernel(const uint32_t* __res
   const uint64_t pEnd = p + per;
   float4 acc = f4zero();
   for (; p + S <= pEnd && p + S <= n; p += S) {
+    // one index load per block: lane c of a lane group fetches the index of step c
+    const uint32_t mine = idx[p + c];
     uint32_t k[S];
     float4 r[S];
 #pragma unroll
-    for (int t = 0; t < S; ++t) k[t] = idx[p + t];
+    for (int t = 0; t < S; ++t) k[t] = __shfl(mine, (g << 3) + t);
 #pragma unroll
-    for (int t = 0; t < S; ++t)
-      r[t] = *reinterpret_cast<const float4*>(table + ((size_t)k[t] * 32 + (size_t)(4 * c)));
+    for (int t = 0; t < S; ++t) {
+      r[t] = f4zero();
+      if (((g - t) & 7) < active) r[t] = *reinterpret_cast<const float4*>(table + ((size_t)k[t] * 32 + (size_t)(4 * c)));
+    }
 #pragma unroll
     for (int t = 0; t < S; ++t) {
       acc.x += r[t].x;
@@ -1243,8 +1250,8 @@ __global__ __launch_bounds__(256) void probe_gather_kernel(const uint32_t* __res
 }
 
 hipError_t launch_probe_gather(const uint32_t* idx, uint64_t n, const float* table, float* sink,
-                               uint32_t waves, uint32_t perWave, hipStream_t s) {
-  hipLaunchKernelGGL(probe_gather_kernel, dim3(waves / 4), dim3(256), 0, s, idx, n, table, sink, perWave);
+                               uint32_t waves, uint32_t perWave, int active, hipStream_t s) {
+  hipLaunchKernelGGL(probe_gather_kernel, dim3(waves / 4), dim3(256), 0, s, idx, n, table, sink, perWave, active);
   return hipGetLastError();
 }
 #endif  // HBCSF_WITH_DEFINE

@@ -7,7 +7,7 @@ from paper_1904_03329_amd import HbcsfTensor, binding as B
 REL_TOL = 1e-4
 
 
-def gpu_mttkrp_all_modes(dims, inds, vals, facs, tune_ts=None, tune_dense=None, **opts):
+def gpu_mttkrp_all_modes(dims, inds, vals, facs, tune_ts=None, tune_dense=None, tune_steps=None, **opts):
     """Returns (list of float32 numpy results per mode, per-mode stats)."""
     import torch
 
@@ -16,6 +16,8 @@ def gpu_mttkrp_all_modes(dims, inds, vals, facs, tune_ts=None, tune_dense=None, 
         B.tune(t.handle, B.TUNE_SLICE_THRESHOLD, tune_ts)
     if tune_dense is not None:
         B.tune(t.handle, B.TUNE_DENSE_MID, tune_dense)
+    if tune_steps is not None:
+        B.tune(t.handle, B.TUNE_STEPS, tune_steps)
     dfacs = [torch.from_numpy(np.ascontiguousarray(f)).cuda() for f in facs]
     outs, stats = [], []
     for mode in range(len(dims)):

@@ -57,7 +57,8 @@ def test_ranks_and_orders(oracle, dims, nnz, rank):
                                   dict(hybrid_granularity=1), dict(hybrid_granularity=1, fiber_threshold=8),
                                   dict(coo_row_flags=1), dict(mid_blocking=4), dict(mid_blocking=2, fiber_threshold=8),
                                   dict(tune_dense=1),
-                                  dict(tune_dense=1, fiber_threshold=32), dict(tune_dense=1, group_mask=4, tune_ts=256)])
+                                  dict(tune_dense=1, fiber_threshold=32), dict(tune_dense=1, group_mask=4, tune_ts=256),
+                                  dict(tune_dense=1, tune_steps=4)])
 @pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000),
                                       ((1500, 80, 20, 9, 6), 90_000)])
 def test_build_options_do_not_change_the_result(oracle, dims, nnz, opts):
@@ -294,9 +295,14 @@ def test_launch_variants_and_diagnostics(oracle):
     idx = torch.randint(0, 1000, (1 << 17,), device="cuda").to(torch.int32)
     table = torch.ones((1000, 32), device="cuda")
     sink = torch.zeros(4, device="cuda")
-    rows = B.probe_row_gather(idx.data_ptr(), idx.numel(), table.data_ptr(), 1000, sink.data_ptr())
+    rows, instr = B.probe_row_gather(idx.data_ptr(), idx.numel(), table.data_ptr(), 1000, sink.data_ptr())
     torch.cuda.synchronize()
-    assert 0 < rows <= idx.numel()
+    assert 0 < rows <= idx.numel() and rows == 8 * instr
+    rows2, instr2 = B.probe_row_gather(idx.data_ptr(), idx.numel(), table.data_ptr(), 1000, sink.data_ptr(), 0, 2)
+    torch.cuda.synchronize()
+    assert instr2 == instr and rows2 == 2 * instr
+    with pytest.raises(B.HbcsfError):
+        B.probe_row_gather(idx.data_ptr(), idx.numel(), table.data_ptr(), 1000, sink.data_ptr(), 0, 9)
     with pytest.raises(B.HbcsfError):
         B.probe_row_gather(idx.data_ptr(), 10, table.data_ptr(), 1000, sink.data_ptr())
 
