@@ -10,8 +10,9 @@
  * setting of Section VI-A).
  *
  * Conventions (Algorithm "COO-MTTKRP" inputs and Section VI-A): indices are
- * 0-based uint32, values and factor matrices fp32, factor matrices and the
- * output are dense row-major [dims[m]][rank] with leading dimension = rank.
+ * 0-based uint32, values and factor matrices fp32 (hbcsf_mttkrp_f64: fp64
+ * factor matrices and output), factor matrices and the output are dense
+ * row-major [dims[m]][rank] with leading dimension = rank.
  *
  * Every function returns 0 on success or a negative HBCSF_E* code; the text of
  * the last failure on the calling thread is kept for hbcsf_last_error().  No
@@ -150,6 +151,19 @@ int hbcsf_upload(hbcsf_tensor *t, void *device_arena, uint64_t bytes, void *hip_
  * host wait), so it can be recorded into a HIP graph and replayed. */
 int hbcsf_mttkrp(const hbcsf_tensor *t, int mode, int rank, const float *const *factors,
                  float *out, void *hip_stream);
+
+/* The same operation with fp64 factor matrices, partial sums and output (Section VI-A fixes fp32 for the
+ * paper's measurements; this is the double-precision form of Eq. 3 / Algorithm "COO-MTTKRP").  The tensor's
+ * values stay the fp32 values the handle was created from and are widened where they are multiplied, so the
+ * result is the fp64 sum of exactly the products the fp32 path rounds; slices that span several work units
+ * are merged with fp64 atomic adds.
+ *   rank     16, 32 or 64.
+ *   factors, out   as for hbcsf_mttkrp, with double elements ([dims[m]][rank] row-major, 16-byte aligned).
+ * Same kernels, launches, format options and tuning keys as hbcsf_mttkrp (a row is split over rank / 2
+ * lanes of two doubles instead of rank / 4 lanes of four floats); not available on a
+ * single_representation handle (HBCSF_EINVAL). */
+int hbcsf_mttkrp_f64(const hbcsf_tensor *t, int mode, int rank, const double *const *factors,
+                     double *out, void *hip_stream);
 
 int hbcsf_get_stats(const hbcsf_tensor *t, int mode, hbcsf_stats *stats);
 

@@ -41,6 +41,8 @@ def _load():
         lib.oracle_mttkrp.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p,
                                       ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
                                       ctypes.c_void_p]
+        lib.oracle_mttkrp_f64.restype = ctypes.c_int
+        lib.oracle_mttkrp_f64.argtypes = lib.oracle_mttkrp.argtypes
         lib.oracle_mttkrp_rows.restype = ctypes.c_int
         lib.oracle_mttkrp_rows.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p,
                                            ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
@@ -49,7 +51,7 @@ def _load():
     return _lib
 
 
-def _marshal(dims, inds, vals, factors, mode):
+def _marshal(dims, inds, vals, factors, mode, fdtype=np.float32):
     order = len(dims)
     if len(inds) != order or len(factors) != order:
         raise ValueError("need one index array and one factor matrix per mode")
@@ -62,7 +64,7 @@ def _marshal(dims, inds, vals, factors, mode):
         if m == mode:
             facs.append(None)
             continue
-        f = np.ascontiguousarray(factors[m], dtype=np.float32)
+        f = np.ascontiguousarray(factors[m], dtype=fdtype)
         if f.ndim != 2 or f.shape[0] != dims[m]:
             raise ValueError(f"factor {m} must be [{dims[m]}, R]")
         rank = f.shape[1] if rank is None else rank
@@ -85,6 +87,18 @@ def mttkrp(dims, inds, vals, factors, mode) -> np.ndarray:
                                out.ctypes.data)
     if rc != 0:
         raise RuntimeError(f"oracle_mttkrp failed with code {rc}")
+    return out
+
+
+def mttkrp_f64(dims, inds, vals, factors, mode) -> np.ndarray:
+    """The same sum with fp64 factor matrices (the values stay fp32): fp64 [dims[mode], R]."""
+    order, d, nnz, iptr, vals, rank, fptr, keep = _marshal(dims, inds, vals, factors, mode, np.float64)
+    out = np.empty((int(dims[mode]), rank), dtype=np.float64)
+    rc = _load().oracle_mttkrp_f64(order, d.ctypes.data, nnz, ctypes.cast(iptr, ctypes.c_void_p),
+                                   vals.ctypes.data, rank, ctypes.cast(fptr, ctypes.c_void_p), mode,
+                                   out.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_mttkrp_f64 failed with code {rc}")
     return out
 
 

@@ -19,6 +19,9 @@
  * uint32, values and factor matrices fp32 (Section V-A), factor matrices are
  * row-major [dims[m]][R] (inputs of Algorithm "COO-MTTKRP").
  *
+ * oracle_mttkrp_f64 is the same sum with fp64 factor matrices (nothing is
+ * widened but the value), the reference for the library's fp64 entry point.
+ *
  * Pins (tests/test_oracle_pins.py): dense matricised-tensor times explicit
  * Khatri-Rao product (Eq. 4-5) on tiny tensors, the rank-1 closed form, the
  * cross-mode invariant sum(M^(n) * A_n), nonzero-order and partition
@@ -82,6 +85,32 @@ int oracle_mttkrp_rows(int order, const uint64_t *dims, uint64_t nnz,
             for (int m = 0; m < order; ++m) {
                 if (m == mode) continue;
                 p *= (double)factors[m][(uint64_t)inds[m][z] * (uint64_t)rank + (uint64_t)r];
+            }
+            y[r] += p;
+        }
+    }
+    return 0;
+}
+
+/* The same definition with fp64 factor matrices: M[i_n][r] += (double)v * prod_{m != n} A_m[i_m][r]. */
+int oracle_mttkrp_f64(int order, const uint64_t *dims, uint64_t nnz,
+                      const uint32_t *const *inds, const float *vals, int rank,
+                      const double *const *factors, int mode, double *out)
+{
+    if (order < 2 || order > ORACLE_MAX_ORDER || mode < 0 || mode >= order || rank < 1) return -1;
+    if (!dims || !inds || !vals || !factors || !out) return -1;
+    const uint64_t rows = dims[mode];
+    for (uint64_t t = 0; t < rows * (uint64_t)rank; ++t) out[t] = 0.0;
+    for (uint64_t z = 0; z < nnz; ++z) {
+        for (int m = 0; m < order; ++m)
+            if (inds[m][z] >= dims[m]) return -2;
+        double *y = out + (uint64_t)inds[mode][z] * (uint64_t)rank;
+        const double v = (double)vals[z];
+        for (int r = 0; r < rank; ++r) {
+            double p = v;
+            for (int m = 0; m < order; ++m) {
+                if (m == mode) continue;
+                p *= factors[m][(uint64_t)inds[m][z] * (uint64_t)rank + (uint64_t)r];
             }
             y[r] += p;
         }

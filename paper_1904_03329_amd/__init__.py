@@ -68,18 +68,21 @@ class HbcsfTensor:
         return self
 
     def mttkrp(self, mode: int, factors, out=None):
-        """factors: one CUDA float32 [dims[m], R] tensor per mode (entry `mode` may be None)."""
+        """factors: one CUDA [dims[m], R] tensor per mode (entry `mode` may be None), all float32 or all float64
+        (float64: fp64 partial sums and output, hbcsf_mttkrp_f64)."""
         import torch
 
         rank = None
+        dtype = None
         ptrs = []
         for m in range(self.order):
             f = factors[m]
             if m == mode or f is None:
                 ptrs.append(0)
                 continue
-            if f.dtype != torch.float32 or not f.is_cuda or not f.is_contiguous():
-                raise ValueError("factors must be contiguous float32 CUDA tensors")
+            dtype = f.dtype if dtype is None else dtype
+            if f.dtype not in (torch.float32, torch.float64) or f.dtype != dtype or not f.is_cuda or not f.is_contiguous():
+                raise ValueError("factors must be contiguous CUDA tensors, all float32 or all float64")
             if f.shape[0] != self.dims[m]:
                 raise ValueError(f"factor {m} must have {self.dims[m]} rows")
             rank = f.shape[1] if rank is None else rank
@@ -87,11 +90,12 @@ class HbcsfTensor:
                 raise ValueError("factor matrices disagree on the rank")
             ptrs.append(f.data_ptr())
         if out is None:
-            out = torch.empty((self.dims[mode], rank), dtype=torch.float32, device="cuda")
-        elif (out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous()
+            out = torch.empty((self.dims[mode], rank), dtype=dtype, device="cuda")
+        elif (out.dtype != dtype or not out.is_cuda or not out.is_contiguous()
               or tuple(out.shape) != (self.dims[mode], rank)):
-            raise ValueError("out must be a contiguous float32 CUDA tensor [dims[mode], R]")
-        binding.mttkrp(self.handle, mode, rank, ptrs, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            raise ValueError("out must be a contiguous CUDA tensor [dims[mode], R] of the factors' dtype")
+        call = binding.mttkrp_f64 if dtype == torch.float64 else binding.mttkrp
+        call(self.handle, mode, rank, ptrs, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
         return out
 
     def close(self):

@@ -25,7 +25,7 @@ ALS_KEEP_GRAMS = 1
 ALS_LAZY_NORMALISATION = 2
 
 EXPORTS = (
-    "hbcsf_build_format", "hbcsf_device_bytes", "hbcsf_upload", "hbcsf_mttkrp", "hbcsf_get_stats",
+    "hbcsf_build_format", "hbcsf_device_bytes", "hbcsf_upload", "hbcsf_mttkrp", "hbcsf_mttkrp_f64", "hbcsf_get_stats",
     "hbcsf_host_array", "hbcsf_tune", "hbcsf_kernel_ms", "hbcsf_probe_row_gather", "hbcsf_free",
     "hbcsf_strerror", "hbcsf_last_error",
     "hbcsf_als_workspace_bytes", "hbcsf_als_create", "hbcsf_als_iteration", "hbcsf_als_normalise", "hbcsf_als_run", "hbcsf_als_phase_ms", "hbcsf_als_free", "hbcsf_sym_pinv",
@@ -79,6 +79,8 @@ def lib():
         L.hbcsf_upload.argtypes = [vp, vp, u64, vp]
         L.hbcsf_mttkrp.restype = i32
         L.hbcsf_mttkrp.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.hbcsf_mttkrp_f64.restype = i32
+        L.hbcsf_mttkrp_f64.argtypes = [vp, i32, i32, vp, vp, vp]
         L.hbcsf_get_stats.restype = i32
         L.hbcsf_get_stats.argtypes = [vp, i32, ctypes.POINTER(hbcsf_stats)]
         L.hbcsf_host_array.restype = i32
@@ -210,6 +212,13 @@ def mttkrp(h, mode: int, rank: int, factor_ptrs, out_ptr: int, stream: int = 0):
     arr = (ctypes.c_void_p * len(factor_ptrs))(*[(p if p else None) for p in factor_ptrs])
     _check(lib().hbcsf_mttkrp(h, mode, rank, ctypes.cast(arr, ctypes.c_void_p), ctypes.c_void_p(out_ptr),
                               ctypes.c_void_p(stream)))
+
+
+def mttkrp_f64(h, mode: int, rank: int, factor_ptrs, out_ptr: int, stream: int = 0):
+    """hbcsf_mttkrp_f64: as mttkrp, the factor matrices and the output hold doubles."""
+    arr = (ctypes.c_void_p * len(factor_ptrs))(*[(p if p else None) for p in factor_ptrs])
+    _check(lib().hbcsf_mttkrp_f64(h, mode, rank, ctypes.cast(arr, ctypes.c_void_p), ctypes.c_void_p(out_ptr),
+                                  ctypes.c_void_p(stream)))
 
 
 def get_stats(h, mode: int) -> dict:

@@ -38,6 +38,13 @@ def build(verbose: bool = False) -> str:
             defs = [f"-DHBCSF_G={g}", f"-DHBCSF_N={n}"] + (["-DHBCSF_WITH_DEFINE"] if (g, n) == (8, 3) else [])
             jobs.append(["hipcc"] + HIP_FLAGS + inc + defs + ["-c", os.path.join(CSRC, "hbcsf_kernels.hip"), "-o", o])
             objs.append(o)
+    # fp64 factor matrices and output: ranks 16, 32, 64 = 8, 16, 32 lanes of 16 bytes per row
+    for g in (8, 16, 32):
+        for n in (3, 4, 5):
+            o = os.path.join(CSRC, f"hbcsf_kernels_f64_g{g}_n{n}.o")
+            defs = [f"-DHBCSF_G={g}", f"-DHBCSF_N={n}", "-DHBCSF_F64"]
+            jobs.append(["hipcc"] + HIP_FLAGS + inc + defs + ["-c", os.path.join(CSRC, "hbcsf_kernels.hip"), "-o", o])
+            objs.append(o)
     for name in ("hbcsf_capi", "hbcsf_als", "hbcsf_devbuild"):
         o = os.path.join(CSRC, name + ".o")
         jobs.append(["hipcc"] + HIP_FLAGS + inc + ["-c", os.path.join(CSRC, name + ".hip"), "-o", o])

@@ -211,12 +211,22 @@ int hbcsf_upload(hbcsf_tensor* t, void* device_arena, uint64_t bytes, void* hip_
   return HBCSF_OK;
 } HBCSF_CATCH_ALL
 
-int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* factors, float* out,
-                 void* hip_stream) try {
+}  // extern "C"
+
+namespace {
+
+// The MTTKRP of both element types: `elem` = bytes per element of the factor matrices and the output (4: fp32,
+// 8: fp64; the tensor's values are fp32 either way).  The kernels see a row as G = rank * elem / 16 lanes of 16 bytes
+// and GroupArgs' float pointers as row addresses, so everything below the launch dispatch is shared.
+int mttkrp_any(const hbcsf_tensor* t, int mode, int rank, int elem, const float* const* factors, float* out,
+               void* hip_stream) {
   if (!t || !factors || !out) return fail(HBCSF_EINVAL, "null argument");
   if (mode < 0 || mode >= t->order) return fail(HBCSF_EINVAL, "mode out of range");
-  if (!(rank == 8 || rank == 16 || rank == 32 || rank == 64 || rank == 128))
+  const bool f64 = elem == 8;
+  if (!f64 && !(rank == 8 || rank == 16 || rank == 32 || rank == 64 || rank == 128))
     return fail(HBCSF_EINVAL, "rank must be 8, 16, 32, 64 or 128");
+  if (f64 && !(rank == 16 || rank == 32 || rank == 64)) return fail(HBCSF_EINVAL, "fp64: rank must be 16, 32 or 64");
+  if (f64 && t->single) return fail(HBCSF_EINVAL, "fp64: the single-representation variant is fp32 only");
   if (!t->uploaded) return fail(HBCSF_ESTATE, "hbcsf_upload has not been called");
   if (((uintptr_t)out & 15) != 0) return fail(HBCSF_EINVAL, "out must be 16-byte aligned");
   for (int m = 0; m < t->order; ++m) {
@@ -227,13 +237,14 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
   if (t->single && mode != 0) return mttkrp_from_mode0(t, mode, rank, factors, out, (hipStream_t)hip_stream);
   const ModeFormat& f = *t->modes[mode];
   const int N = t->order;
-  const int G = rank / 4;
+  const int G = rank * elem / 16;
   const int NG = 64 / G;
   const uint32_t L = f.L;
   uint32_t lshift = 0;
   while ((1u << lshift) < L) ++lshift;
   hipStream_t s = (hipStream_t)hip_stream;
   const uint8_t* base = t->arena + f.devOffset;
+  const uint64_t rowBytes = (uint64_t)rank * (uint64_t)elem;
   hipError_t e;
 
   hbcsf_tensor::EventSet* es = nullptr;
@@ -257,14 +268,14 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
     return a;
   };
   bool wide = false;  // some gathered factor matrix needs 64-bit row addressing
-  for (int l = 1; l < N; ++l) wide = wide || t->dims[f.levelMode[l]] * (uint64_t)rank * 4ull >= (1ull << 32);
+  for (int l = 1; l < N; ++l) wide = wide || t->dims[f.levelMode[l]] * rowBytes >= (1ull << 32);
 
   // 1. define every output row that no plain store will write; the COO group's rows are written
   //    in the same pass
   // (measured: the fused pass saves a launch on small outputs but hides latency worse on large ones)
   // (without stored root indices only the fused pass can place the COO group's rows)
   const bool wantFuse = f.cooRowFlags || t->fuseCoo == 1 ||
-                        (t->fuseCoo == 2 && f.rows * (uint64_t)rank * 4ull <= (64ull << 20));
+                        (t->fuseCoo == 2 && f.rows * rowBytes <= (64ull << 20));
   const bool fuseCoo = wantFuse && (t->kernelMask & 3u) == 3u && f.g[kCoo].nnz > 0;
   if (t->kernelMask & 1u) {
     // one wavefront per 8 x 32 rows, capped at 64 wavefronts per compute unit
@@ -280,7 +291,7 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
       a.val = (const float*)(base + f.g[kCoo].val.off);
       a.out = out;
       a.nnz = (uint32_t)f.g[kCoo].nnz;
-      e = launch_define_coo(N, G, wide, a, (const uint32_t*)(base + f.ownedBits.off),
+      e = launch_define_coo(f64, N, G, wide, a, (const uint32_t*)(base + f.ownedBits.off),
                             (const uint32_t*)(base + f.cooBits.off), (const uint32_t*)(base + f.cooPtr.off),
                             f.rows, (uint32_t)blocks, s);
     } else {
@@ -346,10 +357,10 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
         a.streamLevel = 0;
         if (g == kCsf)
           for (int l = 1; l < N - 1; ++l)
-            if (t->dims[f.levelMode[l]] * (uint64_t)rank * 4ull >= t->streamBytes) a.streamLevel |= 1u << l;
+            if (t->dims[f.levelMode[l]] * rowBytes >= t->streamBytes) a.streamLevel |= 1u << l;
         blocks = (uint32_t)t->numCU;  // the launcher sizes the grid
       }
-      e = launch_group(g, N, G, t->steps, wide, a, blocks, threads, lds, s);
+      e = launch_group(f64, g, N, G, t->steps, wide, a, blocks, threads, lds, s);
       if (e != hipSuccess) return fail_hip(e, "launch of a group kernel");
       launched = true;
     }
@@ -363,6 +374,21 @@ int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* 
     ++t->calls;
   }
   return HBCSF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hbcsf_mttkrp(const hbcsf_tensor* t, int mode, int rank, const float* const* factors, float* out,
+                 void* hip_stream) try {
+  return mttkrp_any(t, mode, rank, 4, factors, out, hip_stream);
+} HBCSF_CATCH_ALL
+
+int hbcsf_mttkrp_f64(const hbcsf_tensor* t, int mode, int rank, const double* const* factors, double* out,
+                     void* hip_stream) try {
+  return mttkrp_any(t, mode, rank, 8, reinterpret_cast<const float* const*>(factors), reinterpret_cast<float*>(out),
+                    hip_stream);
 } HBCSF_CATCH_ALL
 
 int hbcsf_get_stats(const hbcsf_tensor* t, int mode, hbcsf_stats* stats) try {

@@ -42,7 +42,8 @@ struct GroupArgs {
   uint32_t traceCapacity;       // records the buffer can hold
 };
 
-// kind: KernelKind; order 3, 4 or 5; G = rank / 4 lanes per factor row (2, 4, 8, 16 or 32);
+// kind: KernelKind; order 3, 4 or 5; G = row bytes / 16 lanes per factor row (fp32: rank / 4 = 2, 4, 8, 16 or 32;
+// fp64: rank / 2 = 8, 16 or 32, the launch functions named ...64...);
 // steps = records a lane group keeps in flight (4 or 8); wide = some gathered factor matrix
 // is 4 GiB or larger (64-bit row addressing).  One launch function per (G, order) pair, each
 // compiled in its own object file.  For the CSL and B-CSF kernels `blocks` is the number of compute
@@ -69,9 +70,41 @@ HBCSF_DECLARE_LAUNCH(8, 5)
 HBCSF_DECLARE_LAUNCH(16, 5)
 HBCSF_DECLARE_LAUNCH(32, 5)
 #undef HBCSF_DECLARE_LAUNCH
+#define HBCSF_DECLARE_LAUNCH64(G, N)                                                                  \
+  hipError_t launch_group64_g##G##_n##N(int kind, int steps, bool wide, const GroupArgs& a,          \
+                                        uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s); \
+  hipError_t launch_define_coo64_g##G##_n##N(bool wide, const GroupArgs& a, const uint32_t* ownedBits,   \
+                                             const uint32_t* cooBits, const uint32_t* cooPtr, uint64_t rows, \
+                                             uint32_t blocks, hipStream_t s);
+HBCSF_DECLARE_LAUNCH64(8, 3)
+HBCSF_DECLARE_LAUNCH64(16, 3)
+HBCSF_DECLARE_LAUNCH64(32, 3)
+HBCSF_DECLARE_LAUNCH64(8, 4)
+HBCSF_DECLARE_LAUNCH64(16, 4)
+HBCSF_DECLARE_LAUNCH64(32, 4)
+HBCSF_DECLARE_LAUNCH64(8, 5)
+HBCSF_DECLARE_LAUNCH64(16, 5)
+HBCSF_DECLARE_LAUNCH64(32, 5)
+#undef HBCSF_DECLARE_LAUNCH64
 
-inline hipError_t launch_group(int kind, int order, int G, int steps, bool wide, const GroupArgs& a,
+// f64: the factor matrices and the output hold doubles (GroupArgs' float pointers then address doubles).
+inline hipError_t launch_group(bool f64, int kind, int order, int G, int steps, bool wide, const GroupArgs& a,
                                uint32_t blocks, uint32_t threads, size_t ldsBytes, hipStream_t s) {
+#define HBCSF_CASE64(GV)                                                                              \
+  case GV:                                                                                            \
+    return order == 3   ? launch_group64_g##GV##_n3(kind, steps, wide, a, blocks, threads, ldsBytes, s) \
+           : order == 4 ? launch_group64_g##GV##_n4(kind, steps, wide, a, blocks, threads, ldsBytes, s) \
+                        : launch_group64_g##GV##_n5(kind, steps, wide, a, blocks, threads, ldsBytes, s);
+  if (f64) {
+    switch (G) {
+      HBCSF_CASE64(8)
+      HBCSF_CASE64(16)
+      HBCSF_CASE64(32)
+      default:
+        return hipErrorInvalidValue;
+    }
+  }
+#undef HBCSF_CASE64
 #define HBCSF_CASE(GV)                                                                              \
   case GV:                                                                                          \
     return order == 3   ? launch_group_g##GV##_n3(kind, steps, wide, a, blocks, threads, ldsBytes, s) \
@@ -90,9 +123,24 @@ inline hipError_t launch_group(int kind, int order, int G, int steps, bool wide,
 }
 
 // Output definition fused with the COO group (a: the COO group's arguments).
-inline hipError_t launch_define_coo(int order, int G, bool wide, const GroupArgs& a, const uint32_t* ownedBits,
-                                    const uint32_t* cooBits, const uint32_t* cooPtr, uint64_t rows,
-                                    uint32_t blocks, hipStream_t s) {
+inline hipError_t launch_define_coo(bool f64, int order, int G, bool wide, const GroupArgs& a,
+                                    const uint32_t* ownedBits, const uint32_t* cooBits, const uint32_t* cooPtr,
+                                    uint64_t rows, uint32_t blocks, hipStream_t s) {
+#define HBCSF_CASE64(GV)                                                                                     \
+  case GV:                                                                                                   \
+    return order == 3   ? launch_define_coo64_g##GV##_n3(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s) \
+           : order == 4 ? launch_define_coo64_g##GV##_n4(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s) \
+                        : launch_define_coo64_g##GV##_n5(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s);
+  if (f64) {
+    switch (G) {
+      HBCSF_CASE64(8)
+      HBCSF_CASE64(16)
+      HBCSF_CASE64(32)
+      default:
+        return hipErrorInvalidValue;
+    }
+  }
+#undef HBCSF_CASE64
 #define HBCSF_CASE(GV)                                                                                     \
   case GV:                                                                                                 \
     return order == 3   ? launch_define_coo_g##GV##_n3(wide, a, ownedBits, cooBits, cooPtr, rows, blocks, s) \
@@ -110,6 +158,7 @@ inline hipError_t launch_define_coo(int order, int G, bool wide, const GroupArgs
 #undef HBCSF_CASE
 }
 
+// Zero fill of the rows whose bit in ownedBits is clear; a row is G 16-byte pieces (fp32 or fp64 alike).
 hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, int G,
                          uint32_t blocks, hipStream_t s);
 

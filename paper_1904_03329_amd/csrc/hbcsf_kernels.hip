@@ -2,7 +2,9 @@
 //
 // Mapping (wave64).  One factor row of R = 4G floats is held by G adjacent lanes, a float4
 // each, so a wavefront has NG = 64/G lane groups and a row gather is one 16-byte load per
-// lane.  The nonzero stream of a group is cut into runs of L nonzeros (L = fiber threshold);
+// lane.  (Built with HBCSF_F64 the factor matrices, the partial sums and the output are fp64: a lane
+// then holds two doubles, R = 2G, and every address computation stays the same; the tensor's
+// values are stored as fp32 either way and widened where they are multiplied.)  The nonzero stream of a group is cut into runs of L nonzeros (L = fiber threshold);
 // a lane group walks one run sequentially with its partial sums in registers, so every lane
 // group has exactly the same amount of work whatever the slice and fiber lengths are.  A
 // unit is NG consecutive runs (one per lane group); a wavefront works through a contiguous
@@ -30,78 +32,134 @@ namespace {
 constexpr int kDenseCache = kDenseCacheRows;  // rows of the dense variant's per-wavefront row cache
 
 
-__device__ __forceinline__ float4 f4zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
+// A lane's 16 bytes of a row: four floats, or two doubles.
+#ifdef HBCSF_F64
+typedef double real;
+struct __attribute__((aligned(16))) rowvec {
+  double x, y;
+};
+typedef double vec16 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ rowvec rv_zero() { return rowvec{0.0, 0.0}; }
+__device__ __forceinline__ rowvec rv_ones() { return rowvec{1.0, 1.0}; }
+__device__ __forceinline__ vec16 to_vec16(const rowvec& a) { return vec16{a.x, a.y}; }
+__device__ __forceinline__ rowvec from_vec16(const vec16& v) { return rowvec{v.x, v.y}; }
+#else
+typedef float real;
+typedef float4 rowvec;
+typedef float vec16 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ rowvec rv_zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ rowvec rv_ones() { return make_float4(1.f, 1.f, 1.f, 1.f); }
+__device__ __forceinline__ vec16 to_vec16(const rowvec& a) { return vec16{a.x, a.y, a.z, a.w}; }
+__device__ __forceinline__ rowvec from_vec16(const vec16& v) { return make_float4(v.x, v.y, v.z, v.w); }
+#endif
 
 // Streaming 16-byte store: the data is not read again by the kernel that writes it.
-__device__ __forceinline__ void store_streaming(float4* p, const float4& a) {
-  f32x4 v = {a.x, a.y, a.z, a.w};
-  __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+__device__ __forceinline__ void store_streaming(rowvec* p, const rowvec& a) {
+  __builtin_nontemporal_store(to_vec16(a), reinterpret_cast<vec16*>(p));
 }
 
-// WIDE = false: the factor matrix is smaller than 4 GiB, so a 32-bit byte offset from a
+// Rows are addressed in bytes (16 G per row, 16 per lane) from a base typed `const float*` whatever the
+// element type.  WIDE = false: the factor matrix is smaller than 4 GiB, so a 32-bit byte offset from a
 // scalar base is enough (one VALU instruction per gather); WIDE = true: 64-bit arithmetic.
 template <int G, bool WIDE>
-__device__ __forceinline__ float4 row_load(const float* __restrict__ base, uint32_t row, int c) {
+__device__ __forceinline__ rowvec row_load(const float* __restrict__ base, uint32_t row, int c) {
   if (WIDE) {
-    return *reinterpret_cast<const float4*>(base + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c)));
+    return *reinterpret_cast<const rowvec*>(base + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c)));
   } else {
     const uint32_t off = row * (uint32_t)(16 * G) + (uint32_t)(16 * c);
-    return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(base) + off);
+    return *reinterpret_cast<const rowvec*>(reinterpret_cast<const char*>(base) + off);
   }
 }
 
 // Streaming variant: the row is not expected to be used again while it could still be cached, so
 // it should not push reusable rows out of the L2.
 template <int G, bool WIDE>
-__device__ __forceinline__ float4 row_load_streaming(const float* __restrict__ base, uint32_t row, int c) {
-  const f32x4* p;
+__device__ __forceinline__ rowvec row_load_streaming(const float* __restrict__ base, uint32_t row, int c) {
+  const vec16* p;
   if (WIDE) {
-    p = reinterpret_cast<const f32x4*>(base + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c)));
+    p = reinterpret_cast<const vec16*>(base + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c)));
   } else {
     const uint32_t off = row * (uint32_t)(16 * G) + (uint32_t)(16 * c);
-    p = reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(base) + off);
+    p = reinterpret_cast<const vec16*>(reinterpret_cast<const char*>(base) + off);
   }
-  const f32x4 v = __builtin_nontemporal_load(p);
-  return make_float4(v.x, v.y, v.z, v.w);
+  return from_vec16(__builtin_nontemporal_load(p));
 }
 
 template <int G>
-__device__ __forceinline__ void row_store(float* __restrict__ out, uint32_t row, int c, float4 a) {
-  store_streaming(reinterpret_cast<float4*>(out + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c))), a);
+__device__ __forceinline__ void row_store(float* __restrict__ out, uint32_t row, int c, rowvec a) {
+  store_streaming(reinterpret_cast<rowvec*>(out + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c))), a);
 }
 
 template <int G>
-__device__ __forceinline__ void row_atomic(float* __restrict__ out, uint32_t row, int c, float4 a) {
-  float* p = out + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c));
+__device__ __forceinline__ void row_atomic(float* __restrict__ out, uint32_t row, int c, rowvec a) {
+  real* p = reinterpret_cast<real*>(out + ((size_t)row * (size_t)(4 * G) + (size_t)(4 * c)));
   unsafeAtomicAdd(p + 0, a.x);
   unsafeAtomicAdd(p + 1, a.y);
+#ifndef HBCSF_F64
   unsafeAtomicAdd(p + 2, a.z);
   unsafeAtomicAdd(p + 3, a.w);
+#endif
 }
 
-__device__ __forceinline__ void fma4(float4& d, float s, const float4& x) {
+#ifdef HBCSF_F64
+__device__ __forceinline__ void fma4(rowvec& d, float s, const rowvec& x) {
+  d.x = fma((double)s, x.x, d.x);
+  d.y = fma((double)s, x.y, d.y);
+}
+
+__device__ __forceinline__ void fma4(rowvec& d, const rowvec& a, const rowvec& x) {
+  d.x = fma(a.x, x.x, d.x);
+  d.y = fma(a.y, x.y, d.y);
+}
+
+__device__ __forceinline__ rowvec mul4(const rowvec& a, const rowvec& x) { return rowvec{a.x * x.x, a.y * x.y}; }
+
+__device__ __forceinline__ rowvec scale4(float s, const rowvec& x) { return rowvec{(double)s * x.x, (double)s * x.y}; }
+
+// Sum over the lanes 2^k * G apart (the same row position in every lane group).
+template <int G>
+__device__ __forceinline__ void sum_lane_groups(rowvec& a) {
+#pragma unroll
+  for (int o = G; o < 64; o <<= 1) {
+    a.x += __shfl_xor(a.x, o);
+    a.y += __shfl_xor(a.y, o);
+  }
+}
+#else
+__device__ __forceinline__ void fma4(rowvec& d, float s, const rowvec& x) {
   d.x = fmaf(s, x.x, d.x);
   d.y = fmaf(s, x.y, d.y);
   d.z = fmaf(s, x.z, d.z);
   d.w = fmaf(s, x.w, d.w);
 }
 
-__device__ __forceinline__ void fma4(float4& d, const float4& a, const float4& x) {
+__device__ __forceinline__ void fma4(rowvec& d, const rowvec& a, const rowvec& x) {
   d.x = fmaf(a.x, x.x, d.x);
   d.y = fmaf(a.y, x.y, d.y);
   d.z = fmaf(a.z, x.z, d.z);
   d.w = fmaf(a.w, x.w, d.w);
 }
 
-__device__ __forceinline__ float4 mul4(const float4& a, const float4& x) {
+__device__ __forceinline__ rowvec mul4(const rowvec& a, const rowvec& x) {
   return make_float4(a.x * x.x, a.y * x.y, a.z * x.z, a.w * x.w);
 }
 
-__device__ __forceinline__ float4 scale4(float s, const float4& x) {
+__device__ __forceinline__ rowvec scale4(float s, const rowvec& x) {
   return make_float4(s * x.x, s * x.y, s * x.z, s * x.w);
 }
+
+// Sum over the lanes 2^k * G apart (the same row position in every lane group).
+template <int G>
+__device__ __forceinline__ void sum_lane_groups(rowvec& a) {
+#pragma unroll
+  for (int o = G; o < 64; o <<= 1) {
+    a.x += __shfl_xor(a.x, o);
+    a.y += __shfl_xor(a.y, o);
+    a.z += __shfl_xor(a.z, o);
+    a.w += __shfl_xor(a.w, o);
+  }
+}
+#endif
 
 // Which spans a wavefront works through.  Blocks are dealt round-robin to the 8 XCDs and the
 // grid is a multiple of 8, so XCD x = blockIdx % 8 is given the x-th eighth of the stream: one
@@ -134,17 +192,11 @@ __device__ __forceinline__ SpanWalk span_walk(const GroupArgs& a, int wib, int w
 // Pending partial row of a lane group, merged at the end of the wavefront's span.
 template <int G>
 __device__ __forceinline__ void final_merge(float* __restrict__ out, bool pend, uint32_t pendRow,
-                                            float4 acc, int g, int c) {
+                                            rowvec acc, int g, int c) {
   const uint32_t first = __builtin_amdgcn_readfirstlane(pendRow);
   const bool uniform = __all(pend ? 1 : 0) && __all(pendRow == first ? 1 : 0);
   if (uniform) {
-#pragma unroll
-    for (int o = G; o < 64; o <<= 1) {
-      acc.x += __shfl_xor(acc.x, o);
-      acc.y += __shfl_xor(acc.y, o);
-      acc.z += __shfl_xor(acc.z, o);
-      acc.w += __shfl_xor(acc.w, o);
-    }
+    sum_lane_groups<G>(acc);
     if (g == 0) row_atomic<G>(out, pendRow, c, acc);
   } else if (pend) {
     row_atomic<G>(out, pendRow, c, acc);
@@ -399,6 +451,12 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
 
 }  // namespace
 
+// The fp64 objects instantiate the same kernel templates with the same arguments as the fp32 ones: a namespace of
+// their own keeps the two sets of kernels apart at link time.
+#ifdef HBCSF_F64
+namespace f64 {
+#endif
+
 // ---------------------------------------------------------------------------------------
 // Output definition: rows that no plain store will write (empty slices and rows merged with
 // atomic adds) are set to zero; the others are left to their single store.
@@ -406,7 +464,7 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
 #ifdef HBCSF_WITH_DEFINE
 // One wavefront takes one bitmap word (32 rows) at a time: the word is read once through the
 // scalar path and each lane then stores its share of the 32 rows' float4s.
-__global__ __launch_bounds__(256) void define_rows_kernel(float4* __restrict__ out,
+__global__ __launch_bounds__(256) void define_rows_kernel(rowvec* __restrict__ out,
                                                           const uint32_t* __restrict__ ownedBits,
                                                           uint64_t nvec, int gshift) {
   const int lane = threadIdx.x & 63;
@@ -423,9 +481,9 @@ __global__ __launch_bounds__(256) void define_rows_kernel(float4* __restrict__ o
       const uint32_t w = ownedBits[wd];
       const uint64_t base = wd * perWord;
       for (int q = 0; q < reps; ++q) {
-        const uint32_t f = (uint32_t)q * 64u + lane;        // float4 within the word's 32 rows
+        const uint32_t f = (uint32_t)q * 64u + lane;        // rowvec within the word's 32 rows
         const uint64_t t = base + f;
-        if (t < nvec && !((w >> (f >> gshift)) & 1u)) store_streaming(out + t, f4zero());
+        if (t < nvec && !((w >> (f >> gshift)) & 1u)) store_streaming(out + t, rv_zero());
       }
     }
   }
@@ -465,7 +523,7 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
   constexpr uint32_t waveWords = recWords + (DENSE ? 64u + (uint32_t)kDenseCache * G * 4u : 0u);
   uint32_t* rec = lds + (size_t)wib * waveWords;
   uint32_t* list = rec + recWords;                                   // DENSE: row numbers by slot
-  float4* cache = reinterpret_cast<float4*>(rec + recWords + 64);    // DENSE: rows by slot, G float4 each
+  rowvec* cache = reinterpret_cast<rowvec*>(rec + recWords + 64);    // DENSE: rows by slot, G rowvec each
 
 
   const float* __restrict__ facLeaf = a.fac[N - 1];
@@ -478,7 +536,7 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
   for (uint32_t span = walk.first; span < walk.end; span += walk.stride) {
   uint32_t u = span * a.unitsPerWave;
   const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
-  float4 acc = f4zero();
+  rowvec acc = rv_zero();
   bool pend = false;
   uint32_t pendRow = 0;
 
@@ -503,21 +561,21 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
     {
       if (ng > 0 && pend && pendRow != headRow) {
         row_atomic<G>(a.out, pendRow, c, acc);
-        acc = f4zero();
+        acc = rv_zero();
       }
       // tmp: sum over the leaves of the open deepest-level segment; tmp1 / tmp2: sums over the closed segments
       // of the next levels up (N >= 4 / N = 5); acc: the slice's row.  Marks are nested: a segment of a level
       // can only end where one of every deeper level ends.
-      float4 tmp = f4zero();
-      float4 tmp1 = f4zero();
-      float4 tmp2 = f4zero();
+      rowvec tmp = rv_zero();
+      rowvec tmp1 = rv_zero();
+      rowvec tmp2 = rv_zero();
       const uint32_t* myrec = rec + (size_t)g * (L + 1) * RW;
       if constexpr (DENSE) {
       for (uint32_t sb = 0; sb < L; sb += kSteps) {
         uint4 rr[kSteps];
         uint32_t mi[kSteps];   // slice mark
         uint32_t sl[kSteps];   // slot (within this lane group) of the deepest level's mark, then of the next level's
-        float4 cr[kSteps];
+        rowvec cr[kSteps];
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
           const uint4* src = reinterpret_cast<const uint4*>(myrec + (size_t)(sb + t) * RW);
@@ -550,7 +608,7 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
         // the rows, NG per load instruction
         const uint32_t nq = min(total, (uint32_t)kDenseCache);
         constexpr int kRounds = kDenseCache / NG;
-        float4 mr[kRounds];
+        rowvec mr[kRounds];
 #pragma unroll
         for (int u2 = 0; u2 < kRounds; ++u2) {
           const uint32_t q = (uint32_t)u2 * NG + g;
@@ -580,25 +638,25 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
         for (int t = 0; t < kSteps; ++t) {
           fma4(tmp, __uint_as_float(rr[t].y), cr[t]);
           if (rr[t].z) {
-            const float4 br = sl[t] < (uint32_t)kDenseCache ? cache[(size_t)sl[t] * G + c]
+            const rowvec br = sl[t] < (uint32_t)kDenseCache ? cache[(size_t)sl[t] * G + c]
                                                              : row_load<G, WIDE>(facDeep, rr[t].z - 1u, c);
             if (N == 3) {
               fma4(acc, tmp, br);
             } else {
               fma4(tmp1, tmp, br);
               if (rr[t].w) {
-                const float4 nr = sl[t] + 1u < (uint32_t)kDenseCache ? cache[(size_t)(sl[t] + 1u) * G + c]
+                const rowvec nr = sl[t] + 1u < (uint32_t)kDenseCache ? cache[(size_t)(sl[t] + 1u) * G + c]
                                                                       : row_load<G, WIDE>(facNext, rr[t].w - 1u, c);
                 fma4(acc, tmp1, nr);
-                tmp1 = f4zero();
+                tmp1 = rv_zero();
               }
             }
-            tmp = f4zero();
+            tmp = rv_zero();
             if (mi[t]) {  // a slice can only end where a segment ends
               const uint32_t row = (mi[t] & 0x7fffffffu) - 1u;
               if (mi[t] & 0x80000000u) row_store<G>(a.out, row, c, acc);
               else row_atomic<G>(a.out, row, c, acc);
-              acc = f4zero();
+              acc = rv_zero();
             }
           }
         }
@@ -610,7 +668,7 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
         uint4 rr[kSteps];
         uint32_t m1[kSteps];   // N = 5: mark of fiber level 1
         uint32_t mi[kSteps];   // slice mark
-        float4 cr[kSteps], br[kSteps], nr[kSteps], ar[kSteps];
+        rowvec cr[kSteps], br[kSteps], nr[kSteps], ar[kSteps];
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
           const uint4* src = reinterpret_cast<const uint4*>(myrec + (size_t)(sb + t) * RW);
@@ -661,18 +719,18 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
                   fma4(tmp2, tmp1, nr[t]);
                   if (m1[t]) {
                     fma4(acc, tmp2, ar[t]);
-                    tmp2 = f4zero();
+                    tmp2 = rv_zero();
                   }
                 }
-                tmp1 = f4zero();
+                tmp1 = rv_zero();
               }
             }
-            tmp = f4zero();
+            tmp = rv_zero();
             if (mi[t]) {  // a slice can only end where a segment ends
               const uint32_t row = (mi[t] & 0x7fffffffu) - 1u;
               if (mi[t] & 0x80000000u) row_store<G>(a.out, row, c, acc);
               else row_atomic<G>(a.out, row, c, acc);
-              acc = f4zero();
+              acc = rv_zero();
             }
           }
         }
@@ -757,19 +815,19 @@ __global__ __launch_bounds__(256) void csf_nonroot_kernel(const GroupArgs a) {
       const uint32_t ng = ends.ng;
       if (ng > 0) {
         // rows of the levels above the leaf (lr[T] unused), their products above / below the target level
-        float4 lr[LEAF];
+        rowvec lr[LEAF];
 #pragma unroll
-        for (int l = 0; l < LEAF; ++l) lr[l] = make_float4(1.f, 1.f, 1.f, 1.f);
+        for (int l = 0; l < LEAF; ++l) lr[l] = rv_ones();
         lr[0] = row_load<G, WIDE>(a.fac[0], ends.headRow, c);   // the slice may have begun in an earlier run
-        float4 up = make_float4(1.f, 1.f, 1.f, 1.f), dn = make_float4(1.f, 1.f, 1.f, 1.f);
-        float4 acc = f4zero();
+        rowvec up = rv_ones(), dn = rv_ones();
+        rowvec acc = rv_zero();
         uint32_t curT = 0;
         bool open = false;
         const uint32_t* myrec = rec + (size_t)g * (L + 1) * RW;
         for (uint32_t sb = 0; sb < ng; sb += kSteps) {
           uint4 rr[kSteps];
           uint32_t hi0[kSteps], hi1[kSteps];   // record words 4 and 5 (N >= 4)
-          float4 cr[kSteps];
+          rowvec cr[kSteps];
 #pragma unroll
           for (int t = 0; t < kSteps; ++t) {
             const uint4* src = reinterpret_cast<const uint4*>(myrec + (size_t)(sb + t) * RW);
@@ -801,7 +859,7 @@ __global__ __launch_bounds__(256) void csf_nonroot_kernel(const GroupArgs a) {
                 if (T < LEAF && mk[T < LEAF ? T : 0] != 0u) {
                   if (open) {
                     row_atomic<G>(a.out, curT, c, mul4(acc, up));
-                    acc = f4zero();
+                    acc = rv_zero();
                   }
                   curT = mk[T < LEAF ? T : 0] - 1u;
                   open = true;
@@ -812,7 +870,7 @@ __global__ __launch_bounds__(256) void csf_nonroot_kernel(const GroupArgs a) {
                 up = lr[0];
 #pragma unroll
                 for (int l = 1; l < T && l < LEAF; ++l) up = mul4(up, lr[l]);
-                dn = make_float4(1.f, 1.f, 1.f, 1.f);
+                dn = rv_ones();
 #pragma unroll
                 for (int l = T + 1; l < LEAF; ++l) dn = mul4(dn, lr[l]);
               }
@@ -856,7 +914,7 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
   for (uint32_t span = walk.first; span < walk.end; span += walk.stride) {
   uint32_t u = span * a.unitsPerWave;
   const uint32_t uEnd = min(u + a.unitsPerWave, a.nUnits);
-  float4 acc = f4zero();
+  rowvec acc = rv_zero();
   bool pend = false;
   uint32_t pendRow = 0;
 
@@ -872,14 +930,14 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
     if (ng > 0) {
       if (pend && pendRow != headRow) {
         row_atomic<G>(a.out, pendRow, c, acc);
-        acc = f4zero();
+        acc = rv_zero();
       }
       const uint32_t* myrec = rec + (size_t)g * (L + 1) * RW;
       for (uint32_t sb = 0; sb < L; sb += kSteps) {
         uint4 rr[kSteps];
         uint32_t vv[kSteps];   // value bits
         uint32_t mi[kSteps];   // slice mark
-        float4 x1[kSteps], x2[kSteps], x3[kSteps], x4[kSteps];
+        rowvec x1[kSteps], x2[kSteps], x3[kSteps], x4[kSteps];
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
           const uint4* src = reinterpret_cast<const uint4*>(myrec + (size_t)(sb + t) * RW);
@@ -905,7 +963,7 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
         }
 #pragma unroll
         for (int t = 0; t < kSteps; ++t) {
-          float4 pr = mul4(x1[t], x2[t]);
+          rowvec pr = mul4(x1[t], x2[t]);
           if (N >= 4) pr = mul4(pr, x3[t]);
           if (N >= 5) pr = mul4(pr, x4[t]);
           fma4(acc, __uint_as_float(vv[t]), pr);
@@ -913,7 +971,7 @@ __global__ __launch_bounds__(256) void csl_group_kernel(const GroupArgs a) {
             const uint32_t row = (mi[t] & 0x7fffffffu) - 1u;
             if (mi[t] & 0x80000000u) row_store<G>(a.out, row, c, acc);
             else row_atomic<G>(a.out, row, c, acc);
-            acc = f4zero();
+            acc = rv_zero();
           }
         }
       }
@@ -959,7 +1017,7 @@ __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
 #pragma unroll
     for (int sb = 0; sb < G; sb += kU) {
       uint32_t i0[kU], v[kU];
-      float4 x1[kU], x2[kU], x3[kU], x4[kU];
+      rowvec x1[kU], x2[kU], x3[kU], x4[kU];
       bool ok[kU];
 #pragma unroll
       for (int t = 0; t < kU; ++t) {
@@ -980,7 +1038,7 @@ __global__ __launch_bounds__(256) void coo_group_kernel(const GroupArgs a) {
 #pragma unroll
       for (int t = 0; t < kU; ++t) {
         if (ok[t]) {
-          float4 pr = mul4(x1[t], x2[t]);
+          rowvec pr = mul4(x1[t], x2[t]);
           if (N >= 4) pr = mul4(pr, x3[t]);
           if (N >= 5) pr = mul4(pr, x4[t]);
           row_store<G>(a.out, i0[t], c, scale4(__uint_as_float(v[t]), pr));
@@ -1036,7 +1094,7 @@ __global__ __launch_bounds__(256) void define_coo_kernel(const GroupArgs a, cons
           v[q] = valb[z];
         }
       }
-      float4 x1[CH], x2[CH], x3[CH], x4[CH];
+      rowvec x1[CH], x2[CH], x3[CH], x4[CH];
 #pragma unroll
       for (int q = 0; q < CH; ++q) {
         if (isCoo[q]) {
@@ -1049,19 +1107,24 @@ __global__ __launch_bounds__(256) void define_coo_kernel(const GroupArgs a, cons
 #pragma unroll
       for (int q = 0; q < CH; ++q) {
         const uint32_t bit = (uint32_t)(g * RPG + qb + q);
-        float4* dst = reinterpret_cast<float4*>(a.out + (((wd << 5) + bit) * (uint64_t)(4 * G) + (uint64_t)(4 * c)));
+        rowvec* dst = reinterpret_cast<rowvec*>(a.out + (((wd << 5) + bit) * (uint64_t)(4 * G) + (uint64_t)(4 * c)));
         if (isCoo[q]) {
-          float4 pr = mul4(x1[q], x2[q]);
+          rowvec pr = mul4(x1[q], x2[q]);
           if (N >= 4) pr = mul4(pr, x3[q]);
           if (N >= 5) pr = mul4(pr, x4[q]);
           store_streaming(dst, scale4(__uint_as_float(v[q]), pr));
         } else if (fill[q]) {
-          store_streaming(dst, f4zero());
+          store_streaming(dst, rv_zero());
         }
       }
     }
   }
 }
+
+#ifdef HBCSF_F64
+}  // namespace f64
+using namespace f64;
+#endif
 
 // ---------------------------------------------------------------------------------------
 // Launch helpers (host)
@@ -1134,8 +1197,15 @@ hipError_t launch_g(int kind, int steps, bool wide, const GroupArgs& a, dim3 gri
 #endif
 #define HBCSF_CAT2(a, b, c, d) a##b##c##d
 #define HBCSF_CAT(a, b, c, d) HBCSF_CAT2(a, b, c, d)
+#ifdef HBCSF_F64
+#define HBCSF_LAUNCH_DEFINE_COO launch_define_coo64_g
+#define HBCSF_LAUNCH_GROUP launch_group64_g
+#else
+#define HBCSF_LAUNCH_DEFINE_COO launch_define_coo_g
+#define HBCSF_LAUNCH_GROUP launch_group_g
+#endif
 
-hipError_t HBCSF_CAT(launch_define_coo_g, HBCSF_G, _n, HBCSF_N)(bool wide, const GroupArgs& a,
+hipError_t HBCSF_CAT(HBCSF_LAUNCH_DEFINE_COO, HBCSF_G, _n, HBCSF_N)(bool wide, const GroupArgs& a,
                                                                const uint32_t* ownedBits, const uint32_t* cooBits,
                                                                const uint32_t* cooPtr, uint64_t rows, uint32_t blocks,
                                                                hipStream_t s) {
@@ -1148,13 +1218,13 @@ hipError_t HBCSF_CAT(launch_define_coo_g, HBCSF_G, _n, HBCSF_N)(bool wide, const
   return hipGetLastError();
 }
 
-hipError_t HBCSF_CAT(launch_group_g, HBCSF_G, _n, HBCSF_N)(int kind, int steps, bool wide, const GroupArgs& a,
+hipError_t HBCSF_CAT(HBCSF_LAUNCH_GROUP, HBCSF_G, _n, HBCSF_N)(int kind, int steps, bool wide, const GroupArgs& a,
                                                           uint32_t blocks, uint32_t threads, size_t ldsBytes,
                                                           hipStream_t s) {
   return launch_g<HBCSF_G, HBCSF_N>(kind, steps, wide, a, dim3(blocks), dim3(threads), ldsBytes, s);
 }
 
-#if HBCSF_G == 8
+#if HBCSF_G == 8 && !defined(HBCSF_F64)
 namespace {
 template <int N, int LS, int T>
 hipError_t launch_nonroot_t(bool wide, const GroupArgs& a, uint32_t threads, size_t lds, hipStream_t s) {
@@ -1184,17 +1254,17 @@ hipError_t HBCSF_CAT(launch_nonroot_n, HBCSF_N, , )(int level, bool wide, const 
     default: return hipErrorInvalidValue;
   }
 }
-#endif  // HBCSF_G == 8
+#endif  // HBCSF_G == 8, fp32
 
 #ifdef HBCSF_WITH_DEFINE
 // Plain zero fill of an output every row of which is then reached by atomic adds (the single-representation kernel).
-__global__ __launch_bounds__(256) void zero_rows_kernel(float4* __restrict__ out, uint64_t nvec) {
+__global__ __launch_bounds__(256) void zero_rows_kernel(rowvec* __restrict__ out, uint64_t nvec) {
   for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (uint64_t)gridDim.x * 256)
-    store_streaming(out + i, f4zero());
+    store_streaming(out + i, rv_zero());
 }
 
 hipError_t launch_zero_rows(float* out, uint64_t nvec, uint32_t blocks, hipStream_t s) {
-  hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<float4*>(out), nvec);
+  hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<rowvec*>(out), nvec);
   return hipGetLastError();
 }
 
@@ -1202,14 +1272,14 @@ hipError_t launch_define(float* out, const uint32_t* ownedBits, uint64_t rows, i
                          hipStream_t s) {
   int gshift = 0;
   while ((1 << gshift) < G) ++gshift;
-  hipLaunchKernelGGL(define_rows_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<float4*>(out),
+  hipLaunchKernelGGL(define_rows_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<rowvec*>(out),
                      ownedBits, rows * (uint64_t)G, gshift);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------
 // Diagnostic: the row-gather rate the memory system sustains for this access shape (128-byte
-// rows, 8 lanes x float4, 8 gathers in flight per lane group), with none of the MTTKRP work
+// rows, 8 lanes x rowvec, 8 gathers in flight per lane group), with none of the MTTKRP work
 // around it.  Used to put a measured ceiling beside the kernels' achieved rates.
 // `active` (1..8): load instruction t of a block of 8 is executed by the lane groups g with
 // (g - t) mod 8 < active only, the others sit it out, as the lane groups without a segment end
@@ -1225,18 +1295,18 @@ __global__ __launch_bounds__(256) void probe_gather_kernel(const uint32_t* __res
   const uint32_t per = perWave / 8;
   uint64_t p = wave * perWave + (uint64_t)g * per;
   const uint64_t pEnd = p + per;
-  float4 acc = f4zero();
+  rowvec acc = rv_zero();
   for (; p + S <= pEnd && p + S <= n; p += S) {
     // one index load per block: lane c of a lane group fetches the index of step c
     const uint32_t mine = idx[p + c];
     uint32_t k[S];
-    float4 r[S];
+    rowvec r[S];
 #pragma unroll
     for (int t = 0; t < S; ++t) k[t] = __shfl(mine, (g << 3) + t);
 #pragma unroll
     for (int t = 0; t < S; ++t) {
-      r[t] = f4zero();
-      if (((g - t) & 7) < active) r[t] = *reinterpret_cast<const float4*>(table + ((size_t)k[t] * 32 + (size_t)(4 * c)));
+      r[t] = rv_zero();
+      if (((g - t) & 7) < active) r[t] = *reinterpret_cast<const rowvec*>(table + ((size_t)k[t] * 32 + (size_t)(4 * c)));
     }
 #pragma unroll
     for (int t = 0; t < S; ++t) {

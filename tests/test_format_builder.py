@@ -287,7 +287,7 @@ def test_library_exports_every_declared_symbol():
     import ctypes
     import re
     header = open(os.path.join(os.path.dirname(GOLDEN), "..", "include", "hbcsf.h")).read()
-    declared = set(re.findall(r"\b(hbcsf_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(hbcsf_[a-z0-9_]+)\s*\(", header))
     assert declared == set(B.EXPORTS)
     L = ctypes.CDLL(B.LIB_PATH)
     for name in declared:

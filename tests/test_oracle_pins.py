@@ -252,3 +252,24 @@ def test_all_cores_variant_equals_the_oracle(oracle, dims):
     bad[0][3] = dims[0]
     with pytest.raises(RuntimeError):
         oracle.mttkrp_all_cores(dims, bad, vals, facs, 1)
+
+
+@pytest.mark.parametrize("dims", [(5, 4, 3), (3, 4, 2, 5), (2, 3, 4, 2, 3)])
+def test_fp64_factor_variant_against_the_dense_definition(oracle, dims):
+    """oracle.mttkrp_f64 (fp64 factor matrices, nothing widened but the value) against Eq. 4 with factors whose
+    values need all 53 mantissa bits; it must differ from the fp32-factor oracle fed the rounded factors (so a
+    variant that narrowed its factors would fail the first check), and agree with it on fp32-valued factors."""
+    rng = np.random.default_rng(97 + len(dims))
+    inds, vals = _random_coo(rng, dims, max(1, int(0.5 * np.prod(dims))))
+    facs = [rng.uniform(0.1, 1, size=(d, 5)) for d in dims]
+    x = _dense(dims, inds, vals)
+    for n in range(len(dims)):
+        want = _unfold(x, n) @ _khatri_rao_all_but(facs, n)
+        got = oracle.mttkrp_f64(dims, inds, vals, facs, n)
+        assert got.dtype == np.float64 and got.shape == (dims[n], 5)
+        np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-14)
+        narrowed = oracle.mttkrp(dims, inds, vals, [f.astype(np.float32) for f in facs], n)
+        assert np.max(np.abs(narrowed - want)) > 1e-9
+        f32 = [f.astype(np.float32) for f in facs]
+        np.testing.assert_array_equal(oracle.mttkrp_f64(dims, inds, vals, [f.astype(np.float64) for f in f32], n),
+                                      oracle.mttkrp(dims, inds, vals, f32, n))
