@@ -28,6 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # fp32 formation off, so the vector ALUs can retire one FMA per lane and cycle: half of the published figure
 # (256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz = 78.6 TFLOP/s).
 FP32_VECTOR_PEAK_GFLOPS = 157300.0 / 2
+FP64_VECTOR_PEAK_GFLOPS = 78600.0   # published fp64 vector peak: one FMA per lane and cycle
 KERNELS = ("define", "coo", "csl", "csf")
 OTHER_WORKLOADS = ("cfg3", "cfg4", "cfg2")   # measured after the headline workload, same process
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
@@ -85,9 +86,9 @@ def ingest_counters(fetch_csv: str, write_csv: str, workload: str, commit: str, 
     return 0
 
 
-def algorithmic_bytes(st: dict, rank: int, order: int) -> dict:
-    """Algorithmic HBM bytes of one mode's kernels from the builder's statistics."""
-    row = 4 * rank
+def algorithmic_bytes(st: dict, rank: int, order: int, elem: int = 4) -> dict:
+    """Algorithmic HBM bytes of one mode's kernels from the builder's statistics (elem = bytes per factor element)."""
+    row = elem * rank
     rows_total = st["rows"]
     out = {}
     for g, name in enumerate(("coo", "csl", "csf")):
@@ -105,10 +106,10 @@ def algorithmic_bytes(st: dict, rank: int, order: int) -> dict:
     return out
 
 
-def gather_bytes(st: dict, rank: int, order: int) -> int:
+def gather_bytes(st: dict, rank: int, order: int, elem: int = 4) -> int:
     """Bytes through the cache hierarchy when every row gather is counted (not HBM bytes): format arrays +
     one factor row per leaf-level gather and per fiber-segment gather + the output once."""
-    row = 4 * rank
+    row = elem * rank
     coo, csl, csf = st["group_nnz"]
     gathers = (order - 1) * (coo + csl) + csf + sum(st["segments"][: order - 2])
     return sum(st["stream_bytes"]) + row * gathers + row * st["rows"]
@@ -393,8 +394,11 @@ def measure(name: str, args, headline: bool, log) -> dict:
     log(f"[bench] format built in {build_s:.1f}s, uploaded {B.device_bytes(ht.handle) / 1e9:.2f} GB in {upload_s:.1f}s")
     dev_build = (time_device_build(torch, np, B, HbcsfTensor, t, ht, args, log)
                  if headline and not args.hybrid_granularity else None)
-    dfacs = [torch.from_numpy(f).cuda() for f in facs]
-    outs = [torch.empty((t.dims[m], rank), dtype=torch.float32, device="cuda") for m in range(order)]
+    f64 = args.dtype == "f64"
+    elem = 8 if f64 else 4
+    dfacs = [torch.from_numpy(f).cuda().double() if f64 else torch.from_numpy(f).cuda() for f in facs]
+    outs = [torch.empty((t.dims[m], rank), dtype=torch.float64 if f64 else torch.float32, device="cuda")
+            for m in range(order)]
 
     def step():
         for m in range(order):
@@ -432,7 +436,7 @@ def measure(name: str, args, headline: bool, log) -> dict:
     per_mode = []
     csf_bytes, csf_ms, csf_launches = 0.0, 0.0, 0
     for m in range(order):
-        ab = algorithmic_bytes(stats[m], rank, order)
+        ab = algorithmic_bytes(stats[m], rank, order, elem)
         tot_ms = float(kmean[m].sum())
         entry = {
             "mode": m,
@@ -453,8 +457,8 @@ def measure(name: str, args, headline: bool, log) -> dict:
         # the two roofs side by side: time the algorithmic bytes need at the HBM peak, time the multiply-adds really
         # done need at the vector fp32 peak without packed FMA, and the larger of the two over the measured time
         t_hbm = ab["total"] / (HBM_PEAK_GBS * 1e9) * 1e3
-        t_alu = stats[m]["flops_real"] * rank / (FP32_VECTOR_PEAK_GFLOPS * 1e9) * 1e3
-        gb = gather_bytes(stats[m], rank, order)
+        t_alu = stats[m]["flops_real"] * rank / ((FP64_VECTOR_PEAK_GFLOPS if f64 else FP32_VECTOR_PEAK_GFLOPS) * 1e9) * 1e3
+        gb = gather_bytes(stats[m], rank, order, elem)
         entry.update({"t_hbm_ms": round(t_hbm, 4), "t_alu_ms": round(t_alu, 4),
                       "roof_frac": round(max(t_hbm, t_alu) / tot_ms, 4),
                       "gather_model_bytes": gb, "gather_gbs": round(gb / (tot_ms * 1e-3) / 1e9, 1)})
@@ -469,13 +473,13 @@ def measure(name: str, args, headline: bool, log) -> dict:
 
     achieved = csf_bytes / (csf_ms * 1e-3) / 1e9 if csf_ms > 0 else 0.0
     roofline = {
-        "kernel": f"csf_group_kernel<{rank // 4},{order}>",
+        "kernel": f"{'f64::' if f64 else ''}csf_group_kernel<{rank * elem // 16},{order}>",
         "bound": "hbm",
         "achieved": round(achieved, 1),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": measured_traffic(name),
+        "traffic": None if f64 else measured_traffic(name),
         "bytes_per_launch": round(csf_bytes / max(csf_launches, 1)),
         "ms_per_launch": round(csf_ms / max(csf_launches, 1), 4),
         "launches_per_step": csf_launches,
@@ -505,7 +509,7 @@ def measure(name: str, args, headline: bool, log) -> dict:
         if args.cu_spread:
             res["cu_busy_spread"] = trace_cu_spread(torch, np, B, ht, dfacs, outs, order, log)
         res["als"] = (time_als(torch, ht, dfacs, rank, args.als_iterations, build_s, dev_build, log)
-                      if args.als_iterations > 0 else None)
+                      if args.als_iterations > 0 and not f64 else None)
     del outs, dfacs
     ht.close()
     torch.cuda.empty_cache()
@@ -538,6 +542,9 @@ def main() -> int:
                     help="1: COO / CSL / CSF chosen per fiber inside heavy slices (host builder only)")
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--kernel-steps", type=int, default=0)
+    ap.add_argument("--dtype", choices=("f32", "f64"), default="f32",
+                    help="element type of the factor matrices, partial sums and output (f64: hbcsf_mttkrp_f64; the "
+                         "ALS timing and the single-representation comparison are fp32 only)")
     ap.add_argument("--fiber-row-gather", type=int, default=0,
                     help="B-CSF kernel variant: 1 = fiber-level rows gathered through an LDS row cache")
     ap.add_argument("--als-iterations", type=int, default=3,
@@ -599,7 +606,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": args.dtype,
         "data": "synthetic",
         "config": {
             "workload": head["workload"],
