@@ -135,11 +135,11 @@ struct Carried {  // what rides along while one 64-bit half of a wide key is bei
 // stable 64-bit passes, so the low half goes to K (as uint64_t) and the high half rides in C.
 template <typename Key>
 __global__ void pack_kernel(IndPtrs inds, const float* vals, size_t M, Spec sp, uint64_t dim0, uint64_t dim1,
-                            uint64_t dim2, uint64_t dim3, uint64_t* K, uint32_t* V, Carried* C,
+                            uint64_t dim2, uint64_t dim3, uint64_t dim4, uint64_t* K, uint32_t* V, Carried* C,
                             unsigned long long* cnt) {
   const size_t z = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (z >= M) return;
-  const uint64_t dims[HBCSF_MAX_ORDER] = {dim0, dim1, dim2, dim3};
+  const uint64_t dims[HBCSF_MAX_ORDER] = {dim0, dim1, dim2, dim3, dim4};
   Key key = 0;
   bool bad = false;
   for (int l = 0; l < sp.N; ++l) {
@@ -186,15 +186,16 @@ __global__ void slice_start_kernel(const Key* K, const uint32_t* sidp, size_t M,
 }
 
 // Section V / VI-D: one nonzero -> COO; every fiber a single nonzero -> CSL; otherwise CSF
-__global__ void classify_kernel(const uint32_t* sStart, const uint32_t* F0, const uint32_t* F1, size_t S, Spec sp,
-                                uint8_t* grp, unsigned long long* cnt) {
-  unsigned long long c0 = 0, c1 = 0;
+__global__ void classify_kernel(const uint32_t* sStart, const uint32_t* F0, const uint32_t* F1, const uint32_t* F2,
+                                size_t S, Spec sp, uint8_t* grp, unsigned long long* cnt) {
+  unsigned long long c0 = 0, c1 = 0, c2 = 0;
   for (size_t s = (size_t)blockIdx.x * blockDim.x + threadIdx.x; s < S; s += (size_t)gridDim.x * blockDim.x) {
     const uint32_t b = sStart[s], e = sStart[s + 1];
     const uint32_t n = e - b;
     const uint32_t nf0 = F0[e - 1] - (b ? F0[b - 1] : 0u);
-    const uint32_t nf1 = sp.NF == 2 ? F1[e - 1] - (b ? F1[b - 1] : 0u) : 0u;
-    const uint32_t deep = sp.NF == 2 ? nf1 : nf0;
+    const uint32_t nf1 = sp.NF >= 2 ? F1[e - 1] - (b ? F1[b - 1] : 0u) : 0u;
+    const uint32_t nf2 = sp.NF >= 3 ? F2[e - 1] - (b ? F2[b - 1] : 0u) : 0u;
+    const uint32_t deep = sp.NF == 3 ? nf2 : sp.NF == 2 ? nf1 : nf0;
     uint8_t g;
     if (n == 1 && sp.cooOn) g = kCoo;
     else if (deep == n && sp.cslOn) g = kCsl;
@@ -203,10 +204,12 @@ __global__ void classify_kernel(const uint32_t* sStart, const uint32_t* F0, cons
     if (g == kCsf) {
       c0 += nf0;
       c1 += nf1;
+      c2 += nf2;
     }
   }
   wave_add(cnt + 2, c0);
   wave_add(cnt + 3, c1);
+  wave_add(cnt + 5, c2);
 }
 
 struct OutArrays {
@@ -233,7 +236,7 @@ __device__ __forceinline__ void mark_row(uint32_t* bitmap, uint32_t r) {
 // every nonzero writes itself into its group's stream; segment starts write the fiber-level entries
 template <typename Key>
 __global__ void fill_nonzeros_kernel(const Key* K, const uint32_t* V, size_t M, Spec sp, Tables t,
-                                     const uint32_t* seg0, const uint32_t* seg1, OutArrays o) {
+                                     const uint32_t* seg0, const uint32_t* seg1, const uint32_t* seg2, OutArrays o) {
   const size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= M) return;
   uint32_t s, pos;
@@ -268,7 +271,7 @@ __global__ void fill_nonzeros_kernel(const Key* K, const uint32_t* V, size_t M, 
   for (int l = 1; l <= sp.NF; ++l) {
     const bool fresh = p == 0 || (key >> sp.shift[l]) != (prev >> sp.shift[l]);
     if (cut || fresh) {
-      const uint32_t id = (l == 1 ? seg0 : seg1)[p];
+      const uint32_t id = (l == 1 ? seg0 : l == 2 ? seg1 : seg2)[p];
       o.csfInd[l][id] = idx[l];
       o.csfPtr[l][id] = pos;
       mark_row(o.seen[kCsf][l], idx[l]);
@@ -342,6 +345,7 @@ struct Workspace {
   uint32_t* V[2];        // values riding along a 64-bit key sort, double buffered
   Carried* C[2];         // wide keys only: the other half + value, double buffered
   u128* K128;            // wide keys only: the sorted keys put together again
+  uint32_t* seg2;        // order 5 only: the third fiber level's scan
   uint32_t* sStart;
   uint8_t* grp;
   C6* c6;
@@ -397,7 +401,7 @@ hipError_t temp_bytes(size_t M, size_t maxWords, int totalBits, size_t* out) {
   return hipSuccess;
 }
 
-void carve(Workspace& w, uint8_t* base, size_t M, uint64_t maxDim, size_t tempBytes, bool wide) {
+void carve(Workspace& w, uint8_t* base, int order, size_t M, uint64_t maxDim, size_t tempBytes, bool wide) {
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) {
     uint8_t* p = base ? base + off : nullptr;
@@ -408,6 +412,7 @@ void carve(Workspace& w, uint8_t* base, size_t M, uint64_t maxDim, size_t tempBy
   for (int i = 0; i < 2; ++i) w.V[i] = (uint32_t*)take((M + 1) * 4);
   for (int i = 0; i < 2; ++i) w.C[i] = wide ? (Carried*)take((M + 1) * sizeof(Carried)) : nullptr;
   w.K128 = wide ? (u128*)take((M + 1) * 16) : nullptr;
+  w.seg2 = order >= 5 ? (uint32_t*)take((M + 2) * 4) : nullptr;
   w.sStart = (uint32_t*)take((M + 2) * 4);
   w.grp = (uint8_t*)take(M + 1);
   w.c6 = (C6*)take((M + 2) * sizeof(C6));
@@ -432,8 +437,7 @@ uint64_t arena_bound(int N, const uint64_t* dims, uint64_t M, uint32_t L) {
 // totalBits: bits of the packed (root, .., leaf) key; maxBits: the widest key of any mode, block bits included
 int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* opts, hbcsf_opts* o, int* totalBits,
                int* maxBits) {
-  if (order != 3 && order != 4)
-    return fail(HBCSF_EINVAL, "the device-side builder handles orders 3 and 4 (order 5: hbcsf_build_format)");
+  if (order < 3 || order > HBCSF_MAX_ORDER) return fail(HBCSF_EINVAL, "order must be 3, 4 or 5");
   if (!dims) return fail(HBCSF_EINVAL, "dims is null");
   if (nnz >= 0xffff0000ull) return fail(HBCSF_ERANGE, "nnz must be below 2^32 - 2^16");
   int total = 0;
@@ -454,6 +458,8 @@ int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* 
     return fail(HBCSF_EINVAL, "hybrid_granularity = 1 is built by hbcsf_build_format (host) only");
   if (o->single_representation != 0)
     return fail(HBCSF_EINVAL, "single_representation = 1 is built by hbcsf_build_format (host) only");
+  if (total > 128)
+    return fail(HBCSF_ERANGE, "the packed coordinates exceed 128 bits: build this tensor with hbcsf_build_format");
   *totalBits = total;
   int bbMax = 0;
   for (int m = 0; m < order; ++m) {
@@ -510,21 +516,21 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   const Key* K = nullptr;
   const uint32_t* V = w.V[0];
   uint32_t* sidp = nullptr;
-  uint32_t* seg[2] = {nullptr, nullptr};
+  uint32_t* seg[3] = {nullptr, nullptr, w.seg2};
   Tables tb{};
   auto cit = rocprim::counting_iterator<size_t>(0);
 
   if (M > 0) {
     // ---- packed keys, sorted; the value rides along ----
     IndPtrs ip{};
-    uint64_t dl[HBCSF_MAX_ORDER] = {1, 1, 1, 1};
+    uint64_t dl[HBCSF_MAX_ORDER] = {1, 1, 1, 1, 1};
     for (int l = 0; l < N; ++l) {
       ip.p[l] = inds[lv[l]];
       dl[l] = dims[lv[l]];
     }
     constexpr bool kWide = sizeof(Key) == 16;
     hipLaunchKernelGGL(pack_kernel<Key>, dim3(grid_for(M)), dim3(256), 0, st, ip, vals, M, sp, dl[0], dl[1], dl[2],
-                       dl[3], w.K[0], w.V[0], w.C[0], w.cnt);
+                       dl[3], dl[4], w.K[0], w.V[0], w.C[0], w.cnt);
     rocprim::double_buffer<uint64_t> kb(w.K[0], w.K[1]);
     size_t tb_ = w.tempBytes;
     if (!kWide) {
@@ -566,7 +572,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
       HIP_TRY(rocprim::inclusive_scan(w.temp, tb_, rocprim::make_transform_iterator(cit, FreshFlag<Key>{K, sp.shift[1 + f]}),
                                       seg[f], M, rocprim::plus<uint32_t>(), st), "scan");
     }
-    uint32_t tail[3] = {0, 0, 0};
+    uint32_t tail[4] = {0, 0, 0, 0};
     HIP_TRY(hipMemcpyAsync(&tail[0], sidp + (M - 1), 4, hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
     for (int f = 0; f < sp.NF; ++f)
       HIP_TRY(hipMemcpyAsync(&tail[1 + f], seg[f] + (M - 1), 4, hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
@@ -576,10 +582,11 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
     S = tail[0];
     fibNat[0] = tail[1];
     fibNat[1] = tail[2];
+    fibNat[2] = tail[3];
 
     // ---- groups, and where every slice starts inside its group ----
-    hipLaunchKernelGGL(classify_kernel, dim3(grid_capped(S)), dim3(256), 0, st, w.sStart, seg[0], seg[1], S, sp, w.grp,
-                       w.cnt);
+    hipLaunchKernelGGL(classify_kernel, dim3(grid_capped(S)), dim3(256), 0, st, w.sStart, seg[0], seg[1], seg[2], S, sp,
+                       w.grp, w.cnt);
     tb_ = w.tempBytes;
     HIP_TRY(rocprim::exclusive_scan(w.temp, tb_, rocprim::make_transform_iterator(cit, SliceIn{w.grp, w.sStart, S}),
                                     w.c6, C6{{0, 0, 0}, {0, 0, 0}}, S + 1, C6Plus(), st), "scan");
@@ -592,7 +599,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
                                       seg[f], 0u, M + 1, rocprim::plus<uint32_t>(), st), "scan");
     }
     C6 totals{};
-    uint32_t segTotal[2] = {0, 0};
+    uint32_t segTotal[3] = {0, 0, 0};
     HIP_TRY(hipMemcpyAsync(&totals, w.c6 + S, sizeof(C6), hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
     for (int f = 0; f < sp.NF; ++f)
       HIP_TRY(hipMemcpyAsync(&segTotal[f], seg[f] + M, 4, hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
@@ -603,6 +610,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
     }
     nSeg[0] = segTotal[0];
     nSeg[1] = segTotal[1];
+    nSeg[2] = segTotal[2];
   }
 
   // ---- layout, then fill ----
@@ -637,7 +645,8 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
     hipLaunchKernelGGL(zero_words_kernel, dim3(grid_for(all)), dim3(256), 0, st, w.bitmap, all);
   }
   if (M > 0) {
-    hipLaunchKernelGGL(fill_nonzeros_kernel<Key>, dim3(grid_for(M)), dim3(256), 0, st, K, V, M, sp, tb, seg[0], seg[1], o);
+    hipLaunchKernelGGL(fill_nonzeros_kernel<Key>, dim3(grid_for(M)), dim3(256), 0, st, K, V, M, sp, tb, seg[0], seg[1],
+                       seg[2], o);
     hipLaunchKernelGGL(fill_slices_kernel<Key>, dim3(grid_capped(S)), dim3(256), 0, st, K, S, sp, tb, o, w.cnt);
   }
   Sentinels z{};
@@ -666,7 +675,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   HIP_TRY(hipGetLastError(), "format kernels");
   HIP_TRY(hipMemcpyAsync(hostCnt, w.cnt, kCounters * 8, hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
   HIP_TRY(hipStreamSynchronize(st), "hipStreamSynchronize");
-  const uint64_t fibNatCsf[HBCSF_MAX_FIBER_LEVELS] = {hostCnt[2], hostCnt[3], 0};
+  const uint64_t fibNatCsf[HBCSF_MAX_FIBER_LEVELS] = {hostCnt[2], hostCnt[3], hostCnt[5]};
   fill_count_stats(out, N, M, S, fibNat, fibNatCsf, nSeg, gS, gM, hostCnt[1]);
   out->stats.owned_rows = hostCnt[4];
   for (int g = 0; g < 3; ++g)
@@ -691,7 +700,7 @@ int hbcsf_device_build_bytes(int order, const uint64_t* dims, uint64_t nnz, cons
   size_t tbytes = 0;
   HIP_TRY(temp_bytes((size_t)nnz, (size_t)((maxDim + 31) / 32), maxBits, &tbytes), "rocPRIM scratch query");
   Workspace w{};
-  carve(w, nullptr, (size_t)nnz, maxDim, tbytes, maxBits > 64);
+  carve(w, nullptr, order, (size_t)nnz, maxDim, tbytes, maxBits > 64);
   *workspace_bytes = w.total;
   *arena_bytes = arena_bound(order, dims, nnz, o.fiber_threshold);
   return HBCSF_OK;
@@ -718,7 +727,7 @@ int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, con
   size_t tbytes = 0;
   HIP_TRY(temp_bytes((size_t)nnz, (size_t)((maxDim + 31) / 32), maxBits, &tbytes), "rocPRIM scratch query");
   Workspace w{};
-  carve(w, (uint8_t*)workspace, (size_t)nnz, maxDim, tbytes, maxBits > 64);
+  carve(w, (uint8_t*)workspace, order, (size_t)nnz, maxDim, tbytes, maxBits > 64);
   if (workspace_bytes < w.total) return fail(HBCSF_ENOMEM, "workspace is smaller than hbcsf_device_build_bytes");
 
   std::unique_ptr<hbcsf_tensor> t(new (std::nothrow) hbcsf_tensor);

@@ -106,7 +106,8 @@ def test_cfg1_arrays_walks_and_mttkrp(oracle, synth):
                                   dict(group_mask=1), dict(group_mask=2), dict(mode_order_policy=1),
                                   dict(mode_order_policy=2), dict(coo_row_flags=1), dict(mid_blocking=3),
                                   dict(mid_blocking=5, fiber_threshold=16)])
-@pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000)])
+@pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000),
+                                      ((1500, 80, 20, 9, 6), 90_000)])
 def test_same_arrays_as_the_host_builder(dims, nnz, opts):
     rng = np.random.default_rng(len(dims) * 1000 + nnz)
     inds, vals = _skewed(rng, dims, nnz)
@@ -118,8 +119,8 @@ def test_random_small_tensors(oracle, seed):
     import torch
 
     rng = np.random.default_rng(7000 + seed)
-    order = 3 + seed % 2
-    dims = tuple(int(rng.integers(1, 200)) for _ in range(order))
+    order = 3 + seed % 3
+    dims = tuple(int(rng.integers(1, 200 if order < 5 else 40)) for _ in range(order))
     nnz = int(rng.integers(1, 3000))
     inds, vals = _random(rng, dims, nnz)
     rank = [8, 16, 32][seed % 3]
@@ -168,9 +169,10 @@ def test_degenerate_shapes():
     assert_same_format((1_000_000, 7_000, n), inds, np.ones(n, dtype=np.float32)).close()
 
 
-@pytest.mark.parametrize("dims", [(100_000, 90_000, 80_000, 70_000), (2_000_000_000, 1_500_000_000, 3_000)])
+@pytest.mark.parametrize("dims", [(100_000, 90_000, 80_000, 70_000), (2_000_000_000, 1_500_000_000, 3_000),
+                                  (100_000, 90_000, 80_000, 700, 60)])
 def test_wide_coordinates_sort_in_two_passes(oracle, dims):
-    """Packed coordinates above 64 bits (68 and 74 here) take the 128-bit key path of both builders."""
+    """Packed coordinates above 64 bits (68, 74 and, at order 5, 67 here) take the 128-bit key path of both builders."""
     import torch
 
     rng = np.random.default_rng(len(dims))
@@ -210,6 +212,9 @@ def test_errors():
     with pytest.raises(B.HbcsfError) as e:
         B.device_build_bytes(dims, 10, fiber_threshold=5)
     assert e.value.code == -1
+    with pytest.raises(B.HbcsfError) as e:                      # five 30-bit modes: a 150-bit key
+        B.device_build_bytes((1 << 30,) * 5, 10)
+    assert e.value.code == -2
     arena_bytes, ws_bytes = B.device_build_bytes(dims, len(vals))
     di = [torch.from_numpy(x.view(np.int32)).cuda() for x in inds]
     dv = torch.from_numpy(vals).cuda()
