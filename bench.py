@@ -410,6 +410,8 @@ def measure(name: str, args, headline: bool, log) -> dict:
         B.tune(ht.handle, B.TUNE_STEPS, args.kernel_steps)
     if args.fiber_row_gather:
         B.tune(ht.handle, B.TUNE_DENSE_MID, args.fiber_row_gather)
+    if args.fuse_coo >= 0:
+        B.tune(ht.handle, B.TUNE_FUSE_COO, args.fuse_coo)
     B.tune(ht.handle, B.TUNE_PROFILE, order * args.steps)
     for _ in range(args.warmup):
         step()
@@ -542,6 +544,9 @@ def main() -> int:
                     help="1: COO / CSL / CSF chosen per fiber inside heavy slices (host builder only)")
     ap.add_argument("--waves-per-cu", type=int, default=0)
     ap.add_argument("--kernel-steps", type=int, default=0)
+    ap.add_argument("--fuse-coo", type=int, default=-1,
+                    help="HBCSF_TUNE_FUSE_COO: 0 separate COO kernel, 1 COO rows in the output-definition pass, 2 that "
+                         "for small outputs (library default)")
     ap.add_argument("--dtype", choices=("f32", "f64"), default="f32",
                     help="element type of the factor matrices, partial sums and output (f64: hbcsf_mttkrp_f64; the "
                          "ALS timing and the single-representation comparison are fp32 only)")

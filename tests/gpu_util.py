@@ -10,7 +10,8 @@ REL_TOL = 1e-4
 REL_TOL_F64 = 1e-12
 
 
-def gpu_mttkrp_all_modes(dims, inds, vals, facs, tune_ts=None, tune_dense=None, tune_steps=None, **opts):
+def gpu_mttkrp_all_modes(dims, inds, vals, facs, tune_ts=None, tune_dense=None, tune_steps=None, tune_fuse=None,
+                         **opts):
     """Returns (list of float32 numpy results per mode, per-mode stats)."""
     import torch
 
@@ -21,6 +22,8 @@ def gpu_mttkrp_all_modes(dims, inds, vals, facs, tune_ts=None, tune_dense=None, 
         B.tune(t.handle, B.TUNE_DENSE_MID, tune_dense)
     if tune_steps is not None:
         B.tune(t.handle, B.TUNE_STEPS, tune_steps)
+    if tune_fuse is not None:
+        B.tune(t.handle, B.TUNE_FUSE_COO, tune_fuse)
     dfacs = [torch.from_numpy(np.ascontiguousarray(f)).cuda() for f in facs]
     outs, stats = [], []
     for mode in range(len(dims)):
