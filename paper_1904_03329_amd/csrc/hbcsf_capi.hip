@@ -329,7 +329,7 @@ int mttkrp_any(const hbcsf_tensor* t, int mode, int rank, int elem, const float*
         blocks = round_up8(b);
         a.unitsPerWave = 0;
       } else {
-        const int RW = N == 3 ? 4 : 8;  // LDS words per nonzero record
+        int RW = N == 3 ? 4 : 8;  // LDS words per nonzero record
         size_t ldsWave = (size_t)NG * (L + 1) * RW * 4;
         // B-CSF tuning variant: the fiber-level rows gathered densely through an LDS row cache (off by default:
         // it lowered the vector-memory instruction count as intended but lengthened every block's dependent chain
@@ -338,6 +338,10 @@ int mttkrp_any(const hbcsf_tensor* t, int mode, int rank, int elem, const float*
         if (g == kCsf && t->denseMid == 1 && dense_mid_available(N, G, lshift)) {
           a.denseMid = 1;
           ldsWave += dense_mid_lds_bytes(G);
+        } else if (g == kCsf && N == 4) {
+          // the order-4 B-CSF kernel packs a record into 4 words and keeps the slices' rows in a list of NG * L words
+          RW = 4;
+          ldsWave = (size_t)NG * (L + 1) * RW * 4 + (size_t)NG * L * 4;
         }
         int wpb = 4;
         while (wpb > 1 && ldsWave * wpb > 48 * 1024) wpb >>= 1;

@@ -258,18 +258,24 @@ struct UnitEnds {
   uint32_t headRow;  // output row of the slice holding this lane group's first nonzero
   uint32_t tailRow;  // output row of the slice holding the first nonzero of the next run
   uint32_t ng;       // nonzeros in this lane group's run (0 beyond the end of the stream)
+  uint32_t sideAt;   // PACK: where the slices that end in this lane group's run start in the unit's slice list
 };
 
 // fLo: first segment of this unit per fiber level (wave-uniform; = previous unit's fHi).
 // START = false: end marks (index + 1 at the LAST nonzero of a segment / slice; slice marks carry the owned bit).
 // START = true : start marks (index + 1 at the FIRST nonzero), for the kernel that needs a level's index while
 //                its segment is still open; a slice that began before the unit has no mark in it (headRow tells).
-template <int G, int N, int LS, bool CSF, bool START = false>
+// PACK (B-CSF, order 4, end marks): 16-byte records {leaf, value, level-2 mark, level-1 mark | slice-end flag in bit
+//                31} instead of 32-byte ones; the marks of slices (row | owned bit, as stored) go to `side`, one
+//                word per slice that ends in the unit, in slice order (`side` holds NG * L words).
+template <int G, int N, int LS, bool CSF, bool START = false, bool PACK = false>
 __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __restrict__ rec, uint32_t u,
-                                               const UnitBounds& b, const uint32_t (&fLo)[3], int lane) {
+                                               const UnitBounds& b, const uint32_t (&fLo)[3], int lane,
+                                               uint32_t* __restrict__ side = nullptr) {
+  static_assert(!PACK || (CSF && N == 4 && !START), "packed records: the order-4 B-CSF kernel");
   constexpr int NG = 64 / G;
   constexpr int NF = N - 2;
-  constexpr int RW = (N == 3) ? 4 : 8;
+  constexpr int RW = (N == 3 || PACK) ? 4 : 8;
   constexpr int KV = 8;  // stream loads per lane issued together (covers 512 nonzeros)
   constexpr int KF = 4;  // segment loads per lane and level issued together (256 segments)
   constexpr int KS = 2;  // slice loads per lane issued together (128 slices)
@@ -367,7 +373,7 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
       uint4* dst = reinterpret_cast<uint4*>(rec + (size_t)(p + (p >> ls)) * RW);
       if (CSF) {
         dst[0] = make_uint4(w0[t], w1[t], 0u, 0u);
-        if (N >= 4) dst[1] = make_uint4(0u, 0u, 0u, 0u);
+        if (N >= 4 && !PACK) dst[1] = make_uint4(0u, 0u, 0u, 0u);
       } else if (N == 3) {
         dst[0] = make_uint4(w0[t], w1[t], w2[t], 0u);
       } else {
@@ -394,7 +400,7 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
     uint4* dst = reinterpret_cast<uint4*>(rec + (size_t)(p + (p >> ls)) * RW);
     if (CSF) {
       dst[0] = make_uint4(x0, x1, 0u, 0u);
-      if (N >= 4) dst[1] = make_uint4(0u, 0u, 0u, 0u);
+      if (N >= 4 && !PACK) dst[1] = make_uint4(0u, 0u, 0u, 0u);
     } else if (N == 3) {
       dst[0] = make_uint4(x0, x1, x2, 0u);
     } else {
@@ -414,12 +420,16 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
         const uint32_t f = fLo[l - 1] + (uint32_t)t * 64u + lane;
         if (f < b.fHi[l - 1]) {
           const uint32_t p = fe[l - 1][t] - (START ? 0u : 1u) - z0;
-          rec[(size_t)(p + (p >> ls)) * RW + word] = fi[l - 1][t] + 1u;
+          uint32_t* at = rec + (size_t)(p + (p >> ls)) * RW + word;
+          if (PACK && l == 1) atomicOr(at, fi[l - 1][t] + 1u);   // the slice-end flag may land in the same word
+          else *at = fi[l - 1][t] + 1u;
         }
       }
       for (uint32_t f = fLo[l - 1] + (uint32_t)KF * 64u + lane; f < b.fHi[l - 1]; f += 64) {
         const uint32_t p = a.ptr[l][f + (START ? 0 : 1)] - (START ? 0u : 1u) - z0;
-        rec[(size_t)(p + (p >> ls)) * RW + word] = a.ind[l][f] + 1u;
+        uint32_t* at = rec + (size_t)(p + (p >> ls)) * RW + word;
+        if (PACK && l == 1) atomicOr(at, a.ind[l][f] + 1u);
+        else *at = a.ind[l][f] + 1u;
       }
     }
   }
@@ -429,7 +439,12 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
     const uint32_t sl = s0 + (uint32_t)t * 64u + lane;
     if (sl < s1 && (!START || (se[t] >= z0 && se[t] < z0 + slots && se[t] < a.nnz))) {
       const uint32_t p = se[t] - (START ? 0u : 1u) - z0;
-      rec[(size_t)(p + (p >> ls)) * RW + markWord] = START ? (si[t] & 0x7fffffffu) + 1u : mark_of_slice(si[t]);
+      if (PACK) {
+        atomicOr(rec + (size_t)(p + (p >> ls)) * RW + 3, 0x80000000u);
+        side[sl - s0] = si[t];
+      } else {
+        rec[(size_t)(p + (p >> ls)) * RW + markWord] = START ? (si[t] & 0x7fffffffu) + 1u : mark_of_slice(si[t]);
+      }
     }
   }
   for (uint32_t sl = s0 + (uint32_t)KS * 64u + lane; sl < s1; sl += 64) {
@@ -437,7 +452,12 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
     if (START && (at < z0 || at >= z0 + slots || at >= a.nnz)) continue;
     const uint32_t p = at - (START ? 0u : 1u) - z0;
     const uint32_t sv = a.ind[0][sl];
-    rec[(size_t)(p + (p >> ls)) * RW + markWord] = START ? (sv & 0x7fffffffu) + 1u : mark_of_slice(sv);
+    if (PACK) {
+      atomicOr(rec + (size_t)(p + (p >> ls)) * RW + 3, 0x80000000u);
+      side[sl - s0] = sv;
+    } else {
+      rec[(size_t)(p + (p >> ls)) * RW + markWord] = START ? (sv & 0x7fffffffu) + 1u : mark_of_slice(sv);
+    }
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 
@@ -446,6 +466,7 @@ __device__ __forceinline__ UnitEnds stage_unit(const GroupArgs& a, uint32_t* __r
   e.headRow = headRaw & 0x7fffffffu;
   e.tailRow = tailRaw & 0x7fffffffu;
   e.ng = r < a.runs ? min(L, a.nnz - (r << ls)) : 0u;
+  e.sideAt = hs - s0;
   return e;
 }
 
@@ -493,7 +514,10 @@ __global__ __launch_bounds__(256) void define_rows_kernel(rowvec* __restrict__ o
 // ---------------------------------------------------------------------------------------
 // B-CSF group.  N = tensor order (3, 4 or 5); G = lanes per factor row.
 // LDS record per nonzero: N = 3: {leaf, val, seg1 mark, slice mark};
-//                         N = 4: {leaf, val, seg2 mark, seg1 mark, slice mark, -, -, -};
+//                         N = 4: {leaf, val, seg2 mark, seg1 mark | slice-end flag} (16 bytes; the marks of the
+//                                slices that end in the unit sit in a list beside the records, in slice order,
+//                                and a lane group takes them one after the other as it meets the flags);
+//                                the dense-gather variant keeps {leaf, val, seg2, seg1, slice mark, -, -, -};
 //                         N = 5: {leaf, val, seg3 mark, seg2 mark, seg1 mark, slice mark, -, -}.
 // A segment mark is index+1 at the segment's last nonzero, else 0.  A slice mark is
 // (row+1) | owned bit at the slice's last nonzero, else 0.
@@ -511,7 +535,10 @@ template <int G, int N, int LS, int kSteps, bool WIDE, bool DENSE>
 __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
   constexpr int NG = 64 / G;
   constexpr int NF = N - 2;
-  constexpr int RW = (N == 3) ? 4 : 8;
+  // order 4 (the plain variant): 16-byte records, the level-1 mark and the slice-end flag in one word, the slices'
+  // rows in a per-unit list beside the records
+  constexpr bool PACK = N == 4 && !DENSE;
+  constexpr int RW = (N == 3 || PACK) ? 4 : 8;
   static_assert(!DENSE || N <= 4, "the dense fiber-row gather handles orders 3 and 4");
   extern __shared__ uint32_t lds[];
   const int lane = threadIdx.x & 63;
@@ -520,8 +547,9 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
   const int g = lane / G, c = lane % G;
   constexpr uint32_t L = 1u << LS;
   constexpr uint32_t recWords = NG * (L + 1) * RW;
-  constexpr uint32_t waveWords = recWords + (DENSE ? 64u + (uint32_t)kDenseCache * G * 4u : 0u);
+  constexpr uint32_t waveWords = recWords + (DENSE ? 64u + (uint32_t)kDenseCache * G * 4u : 0u) + (PACK ? NG * L : 0u);
   uint32_t* rec = lds + (size_t)wib * waveWords;
+  uint32_t* side = rec + recWords;                                   // PACK: marks of the slices that end in the unit
   uint32_t* list = rec + recWords;                                   // DENSE: row numbers by slot
   rowvec* cache = reinterpret_cast<rowvec*>(rec + recWords + 64);    // DENSE: rows by slot, G rowvec each
 
@@ -548,8 +576,9 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
   for (; u < uEnd; ++u) {
     // run-table entries of the next unit: in flight while this unit is staged and processed
     const UnitBounds nxt = load_bounds<G, N, true>(a, min(u + 1, a.nUnits - 1), lane);
-    const UnitEnds ends = stage_unit<G, N, LS, true>(a, rec, u, cur, fLo, lane);
+    const UnitEnds ends = stage_unit<G, N, LS, true, false, PACK>(a, rec, u, cur, fLo, lane, side);
     const uint32_t headRow = ends.headRow, tailRow = ends.tailRow, ng = ends.ng;
+    uint32_t sideAt = ends.sideAt;   // PACK: the next slice of this lane group's run in the unit's slice list
     fLo[0] = cur.fHi[0];
     fLo[1] = cur.fHi[1];
     fLo[2] = cur.fHi[2];
@@ -676,6 +705,10 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
           if (N == 3) {
             mi[t] = rr[t].w;
             m1[t] = 0;
+          } else if (PACK) {
+            mi[t] = rr[t].w & 0x80000000u;   // slice-end flag; the slice's mark is next in the unit's slice list
+            rr[t].w &= 0x7fffffffu;
+            m1[t] = 0;
           } else if (N == 4) {
             mi[t] = reinterpret_cast<const uint32_t*>(src)[4];
             m1[t] = 0;
@@ -727,8 +760,10 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
             }
             tmp = rv_zero();
             if (mi[t]) {  // a slice can only end where a segment ends
-              const uint32_t row = (mi[t] & 0x7fffffffu) - 1u;
-              if (mi[t] & 0x80000000u) row_store<G>(a.out, row, c, acc);
+              // PACK: the stored root entry (row | owned bit) of the next slice of this run; else the mark itself
+              const uint32_t sm = PACK ? side[sideAt++] : mi[t];
+              const uint32_t row = (sm & 0x7fffffffu) - (PACK ? 0u : 1u);
+              if (sm & 0x80000000u) row_store<G>(a.out, row, c, acc);
               else row_atomic<G>(a.out, row, c, acc);
               acc = rv_zero();
             }
@@ -738,7 +773,8 @@ __device__ __forceinline__ void csf_group_body(const GroupArgs& a) {
       }  // classic / dense
       // the run leaves a partial row behind unless its last nonzero ends a slice
       if (ng > 0) {
-        pend = myrec[(size_t)(ng - 1) * RW + (N == 3 ? 3 : N)] == 0u;
+        pend = PACK ? (myrec[(size_t)(ng - 1) * RW + 3] & 0x80000000u) == 0u
+                    : myrec[(size_t)(ng - 1) * RW + (N == 3 ? 3 : N)] == 0u;
         pendRow = tailRow;
       }
     }
