@@ -240,7 +240,8 @@ def time_device_build(torch, np, B, HbcsfTensor, t, host_tensor, args, log):
             dev = HbcsfTensor.from_device_coo(t.dims, di, dv, compact=False, fiber_threshold=args.fiber_threshold,
                                               slice_threshold=args.slice_threshold,
                                               mode_order_policy=args.mode_order_policy, group_mask=args.group_mask,
-                                              coo_row_flags=args.coo_row_flags, mid_blocking=args.mid_blocking)
+                                              coo_row_flags=args.coo_row_flags, mid_blocking=args.mid_blocking,
+                                              hybrid_granularity=args.hybrid_granularity)
             torch.cuda.synchronize()
             times.append(time.perf_counter() - t0)
             same = B.device_bytes(dev.handle) == B.device_bytes(host_tensor.handle)
@@ -392,8 +393,7 @@ def measure(name: str, args, headline: bool, log) -> dict:
         st["rows"] = t.dims[m]
         stats.append(st)
     log(f"[bench] format built in {build_s:.1f}s, uploaded {B.device_bytes(ht.handle) / 1e9:.2f} GB in {upload_s:.1f}s")
-    dev_build = (time_device_build(torch, np, B, HbcsfTensor, t, ht, args, log)
-                 if headline and not args.hybrid_granularity else None)
+    dev_build = time_device_build(torch, np, B, HbcsfTensor, t, ht, args, log) if headline else None
     f64 = args.dtype == "f64"
     elem = 8 if f64 else 4
     dfacs = [torch.from_numpy(f).cuda().double() if f64 else torch.from_numpy(f).cuda() for f in facs]

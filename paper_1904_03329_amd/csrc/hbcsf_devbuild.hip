@@ -35,6 +35,7 @@ struct Spec {
   int shift[HBCSF_MAX_ORDER];
   uint64_t mask[HBCSF_MAX_ORDER];
   uint32_t L, cooOn, cslOn, cooRowFlags;
+  uint32_t perFiber;  // hybrid_granularity = 1: heavy slices are split into a CSL piece and a CSF piece
   int blockBits, blockShift, blockDrop;  // level-1 blocking: (index of level 1 >> blockDrop) << blockShift tops the key
 };
 
@@ -52,17 +53,48 @@ struct C6Plus {
   }
 };
 
+constexpr uint8_t kSplit = 3;  // a slice stored as a CSL piece (its singleton-fiber nonzeros) and a CSF piece
+
 struct Tables {
   const uint32_t* sidp;    // [M] 1 + slice number of every sorted nonzero
   const uint32_t* sStart;  // [S + 1] first nonzero of every slice
-  const uint8_t* grp;      // [S] group of every slice
+  const uint8_t* grp;      // [S] group of every slice (kSplit: both)
   const C6* c6;            // [S + 1] slices / nonzeros of each group before every slice
+  // per-fiber group choice only (else nullptr):
+  const uint32_t* sgScan;        // [M] singleton-fiber nonzeros at or before every sorted nonzero
+  const uint32_t* nat[2];        // [M] natural fiber number (inclusive scan) at fiber levels 1 and 2, where such a
+                                 // level lies above the deepest one
+  const uint32_t* firstKept[2];  // by natural fiber of that level: its first nonzero that stays in the CSF group
 };
 
+// Is nonzero p the only one of its deepest-level fiber?  (shiftDeep: key shift of that level)
+template <typename Key>
+__device__ __forceinline__ bool single_at(const Key* K, size_t p, size_t M, int shiftDeep) {
+  const bool freshHere = p == 0 || (K[p] >> shiftDeep) != (K[p - 1] >> shiftDeep);
+  const bool freshNext = p + 1 == M || (K[p + 1] >> shiftDeep) != (K[p] >> shiftDeep);
+  return freshHere && freshNext;
+}
+
+// Group and position of sorted nonzero p.  In a split slice the singleton-fiber nonzeros go, in order, to the
+// slice's CSL piece and the others to its CSF piece; sgScan counts the former.
 __device__ __forceinline__ void locate(const Tables& t, size_t p, uint32_t& s, int& g, uint32_t& pos) {
   s = t.sidp[p] - 1;
   g = t.grp[s];
-  pos = t.c6[s].m[g] + (uint32_t)(p - t.sStart[s]);
+  const uint32_t b = t.sStart[s];
+  if (g != kSplit) {
+    pos = t.c6[s].m[g] + (uint32_t)(p - b);
+    return;
+  }
+  const uint32_t before = b ? t.sgScan[b - 1] : 0u;
+  const uint32_t upTo = t.sgScan[p] - before;                 // singles of the slice at or before p
+  const bool single = upTo != (p > b ? t.sgScan[p - 1] - before : 0u);
+  if (single) {
+    g = kCsl;
+    pos = t.c6[s].m[kCsl] + upTo - 1u;
+  } else {
+    g = kCsf;
+    pos = t.c6[s].m[kCsf] + (uint32_t)(p - b) - upTo;
+  }
 }
 
 template <typename Key>
@@ -74,6 +106,16 @@ struct FreshFlag {  // 1 where the index at some tree level (and everything abov
   }
 };
 
+// Does a fiber of the CSF group start at nonzero p (of that group) at the level whose key shift is `shift`?  Without
+// the per-fiber choice: where the index at that level or above changes.  With it, nonzeros may have left the slice
+// for the CSL piece, so: where p is the first nonzero of its natural fiber that stayed (`upper` = 0 / 1 selects the
+// tables of fiber level 1 / 2; the deepest level needs none: a nonzero that left was a fiber of its own).
+template <typename Key>
+__device__ __forceinline__ bool fiber_starts(const Key* K, size_t p, int shift, const Tables& t, int upper) {
+  if (upper >= 0 && t.firstKept[upper]) return t.firstKept[upper][t.nat[upper][p] - 1u] == (uint32_t)p;
+  return p == 0 || (K[p] >> shift) != (K[p - 1] >> shift);
+}
+
 template <typename Key>
 struct SegFlag {  // 1 where a fiber segment of the CSF group starts
   const Key* K;
@@ -81,26 +123,45 @@ struct SegFlag {  // 1 where a fiber segment of the CSF group starts
   Tables t;
   uint32_t L;
   size_t M;
+  int upper;  // 0 / 1: fiber level 1 / 2 lies above the deepest level (per-fiber tables apply); -1: deepest level
   __device__ uint32_t operator()(size_t p) const {
     if (p >= M) return 0u;
     uint32_t s, pos;
     int g;
     locate(t, p, s, g, pos);
     if (g != kCsf) return 0u;
-    return ((pos % L) == 0 || p == 0 || (K[p] >> shift) != (K[p - 1] >> shift)) ? 1u : 0u;
+    return ((pos % L) == 0 || fiber_starts(K, p, shift, t, upper)) ? 1u : 0u;
   }
+};
+
+template <typename Key>
+struct SingleFlag {  // 1 where a nonzero is the only one of its deepest-level fiber
+  const Key* K;
+  int shiftDeep;
+  size_t M;
+  __device__ uint32_t operator()(size_t p) const { return p < M && single_at(K, p, M, shiftDeep) ? 1u : 0u; }
 };
 
 struct SliceIn {  // what a slice adds to the running group counts
   const uint8_t* grp;
   const uint32_t* sStart;
   size_t S;
+  const uint32_t* sgScan;  // per-fiber choice only
   __device__ C6 operator()(size_t s) const {
     C6 r{{0, 0, 0}, {0, 0, 0}};
     if (s < S) {
       const int g = grp[s];
-      r.s[g] = 1;
-      r.m[g] = sStart[s + 1] - sStart[s];
+      const uint32_t b = sStart[s], e = sStart[s + 1];
+      if (g == kSplit) {
+        const uint32_t ns = sgScan[e - 1] - (b ? sgScan[b - 1] : 0u);
+        r.s[kCsl] = 1;
+        r.m[kCsl] = ns;
+        r.s[kCsf] = 1;
+        r.m[kCsf] = (e - b) - ns;
+      } else {
+        r.s[g] = 1;
+        r.m[g] = e - b;
+      }
     }
     return r;
   }
@@ -187,7 +248,7 @@ __global__ void slice_start_kernel(const Key* K, const uint32_t* sidp, size_t M,
 
 // Section V / VI-D: one nonzero -> COO; every fiber a single nonzero -> CSL; otherwise CSF
 __global__ void classify_kernel(const uint32_t* sStart, const uint32_t* F0, const uint32_t* F1, const uint32_t* F2,
-                                size_t S, Spec sp, uint8_t* grp, unsigned long long* cnt) {
+                                size_t S, Spec sp, const uint32_t* sgScan, uint8_t* grp, unsigned long long* cnt) {
   unsigned long long c0 = 0, c1 = 0, c2 = 0;
   for (size_t s = (size_t)blockIdx.x * blockDim.x + threadIdx.x; s < S; s += (size_t)gridDim.x * blockDim.x) {
     const uint32_t b = sStart[s], e = sStart[s + 1];
@@ -200,8 +261,13 @@ __global__ void classify_kernel(const uint32_t* sStart, const uint32_t* F0, cons
     if (n == 1 && sp.cooOn) g = kCoo;
     else if (deep == n && sp.cslOn) g = kCsl;
     else g = kCsf;
+    if (sp.perFiber && g == kCsf && n >= 2u * sp.L) {
+      // heavy enough to be merged with atomic adds anyway, and at least an eighth of it in singleton fibers
+      const uint32_t ns = sgScan[e - 1] - (b ? sgScan[b - 1] : 0u);
+      if ((unsigned long long)ns * 8ull >= (unsigned long long)n) g = kSplit;
+    }
     grp[s] = g;
-    if (g == kCsf) {
+    if (g == kCsf && !sp.perFiber) {  // with the per-fiber choice the fibers that stay are counted after the split
       c0 += nf0;
       c1 += nf1;
       c2 += nf2;
@@ -210,6 +276,40 @@ __global__ void classify_kernel(const uint32_t* sStart, const uint32_t* F0, cons
   wave_add(cnt + 2, c0);
   wave_add(cnt + 3, c1);
   wave_add(cnt + 5, c2);
+}
+
+// per-fiber choice: for every natural fiber of an upper fiber level, the first of its nonzeros that stays in the
+// CSF group (atomic minimum over the nonzeros of CSF and split slices)
+__global__ void first_kept_kernel(size_t M, Tables t, uint32_t* first0, uint32_t* first1) {
+  const size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= M) return;
+  uint32_t s, pos;
+  int g;
+  locate(t, p, s, g, pos);
+  if (g != kCsf) return;
+  if (first0) atomicMin(&first0[t.nat[0][p] - 1u], (uint32_t)p);
+  if (first1) atomicMin(&first1[t.nat[1][p] - 1u], (uint32_t)p);
+}
+
+__global__ void fill_words_kernel(uint32_t* p, size_t n, uint32_t v) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// per-fiber choice: fibers per level among the nonzeros that stay in the CSF group (statistics)
+template <typename Key>
+__global__ void count_kept_fibers_kernel(const Key* K, size_t M, Spec sp, Tables t, unsigned long long* cnt) {
+  unsigned long long c[3] = {0, 0, 0};
+  for (size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x; p < M; p += (size_t)gridDim.x * blockDim.x) {
+    uint32_t s, pos;
+    int g;
+    locate(t, p, s, g, pos);
+    if (g != kCsf) continue;
+    for (int l = 1; l <= sp.NF; ++l) c[l - 1] += fiber_starts(K, p, sp.shift[l], t, l < sp.NF ? l - 1 : -1) ? 1u : 0u;
+  }
+  wave_add(cnt + 2, c[0]);
+  wave_add(cnt + 3, c[1]);
+  wave_add(cnt + 5, c[2]);
 }
 
 struct OutArrays {
@@ -267,9 +367,8 @@ __global__ void fill_nonzeros_kernel(const Key* K, const uint32_t* V, size_t M, 
   mark_row(o.seen[kCsf][sp.N - 1], idx[sp.N - 1]);
   o.csfVal[pos] = v;
   if (cut) o.csfRun[0][pos / sp.L] = ord;
-  const Key prev = p ? K[p - 1] : (Key)0;
   for (int l = 1; l <= sp.NF; ++l) {
-    const bool fresh = p == 0 || (key >> sp.shift[l]) != (prev >> sp.shift[l]);
+    const bool fresh = fiber_starts(K, p, sp.shift[l], t, l < sp.NF ? l - 1 : -1);
     if (cut || fresh) {
       const uint32_t id = (l == 1 ? seg0 : l == 2 ? seg1 : seg2)[p];
       o.csfInd[l][id] = idx[l];
@@ -287,7 +386,14 @@ __global__ void fill_slices_kernel(const Key* K, size_t S, Spec sp, Tables t, Ou
   unsigned long long shared = 0;
   for (size_t s = (size_t)blockIdx.x * blockDim.x + threadIdx.x; s < S; s += (size_t)gridDim.x * blockDim.x) {
     const int g = t.grp[s];
-    if (g != kCoo) {
+    if (g == kSplit) {  // two pieces with the same root index, neither owns the row
+      const uint32_t root = (uint32_t)((uint64_t)(K[t.sStart[s]] >> sp.shift[0]) & sp.mask[0]);
+      o.cslInd[0][t.c6[s].s[kCsl]] = root;
+      o.cslPtr[t.c6[s].s[kCsl]] = t.c6[s].m[kCsl];
+      o.csfInd[0][t.c6[s].s[kCsf]] = root;
+      o.csfPtr[0][t.c6[s].s[kCsf]] = t.c6[s].m[kCsf];
+      ++shared;
+    } else if (g != kCoo) {
       const uint32_t b = t.sStart[s], n = t.sStart[s + 1] - b;
       const uint32_t a = t.c6[s].m[g], ord = t.c6[s].s[g];
       const uint32_t root = (uint32_t)((uint64_t)(K[b] >> sp.shift[0]) & sp.mask[0]);
@@ -346,6 +452,9 @@ struct Workspace {
   Carried* C[2];         // wide keys only: the other half + value, double buffered
   u128* K128;            // wide keys only: the sorted keys put together again
   uint32_t* seg2;        // order 5 only: the third fiber level's scan
+  uint32_t* sgScan;      // per-fiber choice only: scan of the singleton-fiber flags
+  uint32_t* nat[2];      // per-fiber choice, orders 4 / 5: natural fiber numbers of the upper fiber levels
+  uint32_t* firstKept[2];  // ... and the first nonzero of each such fiber that stays in the CSF group
   uint32_t* sStart;
   uint8_t* grp;
   C6* c6;
@@ -381,11 +490,15 @@ hipError_t temp_bytes(size_t M, size_t maxWords, int totalBits, size_t* out) {
                               (uint32_t*)nullptr, M + 1, rocprim::plus<uint32_t>());
   if (e != hipSuccess) return e;
   need = b > need ? b : need;
-  e = rocprim::exclusive_scan(nullptr, b, rocprim::make_transform_iterator(cnt, SegFlag<u128>{nullptr, 0, Tables{}, 1, 0}),
+  e = rocprim::inclusive_scan(nullptr, b, rocprim::make_transform_iterator(cnt, SingleFlag<u128>{nullptr, 0, 0}),
+                              (uint32_t*)nullptr, M + 1, rocprim::plus<uint32_t>());
+  if (e != hipSuccess) return e;
+  need = b > need ? b : need;
+  e = rocprim::exclusive_scan(nullptr, b, rocprim::make_transform_iterator(cnt, SegFlag<u128>{nullptr, 0, Tables{}, 1, 0, -1}),
                               (uint32_t*)nullptr, 0u, M + 1, rocprim::plus<uint32_t>());
   if (e != hipSuccess) return e;
   need = b > need ? b : need;
-  e = rocprim::exclusive_scan(nullptr, b, rocprim::make_transform_iterator(cnt, SliceIn{nullptr, nullptr, 0}),
+  e = rocprim::exclusive_scan(nullptr, b, rocprim::make_transform_iterator(cnt, SliceIn{nullptr, nullptr, 0, nullptr}),
                               (C6*)nullptr, C6{{0, 0, 0}, {0, 0, 0}}, M + 1, C6Plus());
   if (e != hipSuccess) return e;
   need = b > need ? b : need;
@@ -401,7 +514,8 @@ hipError_t temp_bytes(size_t M, size_t maxWords, int totalBits, size_t* out) {
   return hipSuccess;
 }
 
-void carve(Workspace& w, uint8_t* base, int order, size_t M, uint64_t maxDim, size_t tempBytes, bool wide) {
+void carve(Workspace& w, uint8_t* base, int order, size_t M, uint64_t maxDim, size_t tempBytes, bool wide,
+           bool perFiber) {
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) {
     uint8_t* p = base ? base + off : nullptr;
@@ -413,6 +527,12 @@ void carve(Workspace& w, uint8_t* base, int order, size_t M, uint64_t maxDim, si
   for (int i = 0; i < 2; ++i) w.C[i] = wide ? (Carried*)take((M + 1) * sizeof(Carried)) : nullptr;
   w.K128 = wide ? (u128*)take((M + 1) * 16) : nullptr;
   w.seg2 = order >= 5 ? (uint32_t*)take((M + 2) * 4) : nullptr;
+  w.sgScan = perFiber ? (uint32_t*)take((M + 2) * 4) : nullptr;
+  for (int f = 0; f < 2; ++f) {
+    const bool upper = perFiber && f < order - 3;   // fiber level f + 1 lies above the deepest one
+    w.nat[f] = upper ? (uint32_t*)take((M + 2) * 4) : nullptr;
+    w.firstKept[f] = upper ? (uint32_t*)take((M + 2) * 4) : nullptr;
+  }
   w.sStart = (uint32_t*)take((M + 2) * 4);
   w.grp = (uint8_t*)take(M + 1);
   w.c6 = (C6*)take((M + 2) * sizeof(C6));
@@ -454,8 +574,7 @@ int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* 
   if (o->group_mask > 4) return fail(HBCSF_EINVAL, "group_mask must be 0..4");
   if (o->coo_row_flags > 1) return fail(HBCSF_EINVAL, "coo_row_flags must be 0 or 1");
   if (o->mid_blocking > 13) return fail(HBCSF_EINVAL, "mid_blocking must be 0 or 1 (off) or 2..13 bits");
-  if (o->hybrid_granularity != 0)
-    return fail(HBCSF_EINVAL, "hybrid_granularity = 1 is built by hbcsf_build_format (host) only");
+  if (o->hybrid_granularity > 1) return fail(HBCSF_EINVAL, "hybrid_granularity must be 0 or 1");
   if (o->single_representation != 0)
     return fail(HBCSF_EINVAL, "single_representation = 1 is built by hbcsf_build_format (host) only");
   if (total > 128)
@@ -490,6 +609,7 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
   sp.cooOn = (gmask & 1u) && sp.blockBits == 0 ? 1u : 0u;   // with blocking no piece owns its row
   sp.cslOn = (gmask & 2u) ? 1u : 0u;
   sp.cooRowFlags = opts.coo_row_flags == 1 ? 1u : 0u;
+  sp.perFiber = opts.hybrid_granularity == 1 && sp.cslOn ? 1u : 0u;
   int lv[HBCSF_MAX_ORDER];
   level_order(N, dims, mode, opts.mode_order_policy, lv);
   int total = 0;
@@ -584,18 +704,42 @@ int build_mode_device(int N, const uint64_t* dims, size_t M, const uint32_t* con
     fibNat[1] = tail[2];
     fibNat[2] = tail[3];
 
+    // ---- per-fiber group choice: which nonzeros are whole fibers of their own; the natural fiber numbers of the
+    //      upper fiber levels are kept (the segment scans below overwrite seg[]) ----
+    if (sp.perFiber) {
+      tb_ = w.tempBytes;
+      HIP_TRY(rocprim::inclusive_scan(w.temp, tb_,
+                                      rocprim::make_transform_iterator(cit, SingleFlag<Key>{K, sp.shift[sp.NF], M}),
+                                      w.sgScan, M, rocprim::plus<uint32_t>(), st), "scan");
+      for (int f = 0; f + 1 < sp.NF; ++f)
+        HIP_TRY(hipMemcpyAsync(w.nat[f], seg[f], M * 4, hipMemcpyDeviceToDevice, st), "hipMemcpyAsync");
+    }
     // ---- groups, and where every slice starts inside its group ----
     hipLaunchKernelGGL(classify_kernel, dim3(grid_capped(S)), dim3(256), 0, st, w.sStart, seg[0], seg[1], seg[2], S, sp,
-                       w.grp, w.cnt);
+                       sp.perFiber ? w.sgScan : nullptr, w.grp, w.cnt);
     tb_ = w.tempBytes;
-    HIP_TRY(rocprim::exclusive_scan(w.temp, tb_, rocprim::make_transform_iterator(cit, SliceIn{w.grp, w.sStart, S}),
+    HIP_TRY(rocprim::exclusive_scan(w.temp, tb_,
+                                    rocprim::make_transform_iterator(cit, SliceIn{w.grp, w.sStart, S, w.sgScan}),
                                     w.c6, C6{{0, 0, 0}, {0, 0, 0}}, S + 1, C6Plus(), st), "scan");
-    tb = Tables{sidp, w.sStart, w.grp, w.c6};
+    tb = Tables{sidp, w.sStart, w.grp, w.c6, sp.perFiber ? w.sgScan : nullptr, {nullptr, nullptr}, {nullptr, nullptr}};
+    if (sp.perFiber) {
+      // the first nonzero of every upper-level fiber that stays in the CSF group, then the fibers that stay
+      for (int f = 0; f + 1 < sp.NF; ++f) {
+        tb.nat[f] = w.nat[f];
+        hipLaunchKernelGGL(fill_words_kernel, dim3(grid_for(M + 1)), dim3(256), 0, st, w.firstKept[f], M + 1, 0xffffffffu);
+      }
+      if (sp.NF >= 2)
+        hipLaunchKernelGGL(first_kept_kernel, dim3(grid_for(M)), dim3(256), 0, st, M, tb, w.firstKept[0],
+                           sp.NF >= 3 ? w.firstKept[1] : nullptr);
+      for (int f = 0; f + 1 < sp.NF; ++f) tb.firstKept[f] = w.firstKept[f];
+      hipLaunchKernelGGL(count_kept_fibers_kernel<Key>, dim3(grid_capped(M)), dim3(256), 0, st, K, M, sp, tb, w.cnt);
+    }
     // ---- fiber segments of the CSF group: numbered by a scan over the sorted order ----
     for (int f = 0; f < sp.NF; ++f) {
       tb_ = w.tempBytes;
       HIP_TRY(rocprim::exclusive_scan(w.temp, tb_,
-                                      rocprim::make_transform_iterator(cit, SegFlag<Key>{K, sp.shift[1 + f], tb, sp.L, M}),
+                                      rocprim::make_transform_iterator(
+                                          cit, SegFlag<Key>{K, sp.shift[1 + f], tb, sp.L, M, f + 1 < sp.NF ? f : -1}),
                                       seg[f], 0u, M + 1, rocprim::plus<uint32_t>(), st), "scan");
     }
     C6 totals{};
@@ -700,7 +844,7 @@ int hbcsf_device_build_bytes(int order, const uint64_t* dims, uint64_t nnz, cons
   size_t tbytes = 0;
   HIP_TRY(temp_bytes((size_t)nnz, (size_t)((maxDim + 31) / 32), maxBits, &tbytes), "rocPRIM scratch query");
   Workspace w{};
-  carve(w, nullptr, order, (size_t)nnz, maxDim, tbytes, maxBits > 64);
+  carve(w, nullptr, order, (size_t)nnz, maxDim, tbytes, maxBits > 64, o.hybrid_granularity == 1);
   *workspace_bytes = w.total;
   *arena_bytes = arena_bound(order, dims, nnz, o.fiber_threshold);
   return HBCSF_OK;
@@ -727,7 +871,7 @@ int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, con
   size_t tbytes = 0;
   HIP_TRY(temp_bytes((size_t)nnz, (size_t)((maxDim + 31) / 32), maxBits, &tbytes), "rocPRIM scratch query");
   Workspace w{};
-  carve(w, (uint8_t*)workspace, order, (size_t)nnz, maxDim, tbytes, maxBits > 64);
+  carve(w, (uint8_t*)workspace, order, (size_t)nnz, maxDim, tbytes, maxBits > 64, o.hybrid_granularity == 1);
   if (workspace_bytes < w.total) return fail(HBCSF_ENOMEM, "workspace is smaller than hbcsf_device_build_bytes");
 
   std::unique_ptr<hbcsf_tensor> t(new (std::nothrow) hbcsf_tensor);

@@ -105,13 +105,24 @@ def test_cfg1_arrays_walks_and_mttkrp(oracle, synth):
 @pytest.mark.parametrize("opts", [dict(), dict(fiber_threshold=8), dict(fiber_threshold=16), dict(group_mask=4),
                                   dict(group_mask=1), dict(group_mask=2), dict(mode_order_policy=1),
                                   dict(mode_order_policy=2), dict(coo_row_flags=1), dict(mid_blocking=3),
-                                  dict(mid_blocking=5, fiber_threshold=16)])
+                                  dict(mid_blocking=5, fiber_threshold=16), dict(hybrid_granularity=1),
+                                  dict(hybrid_granularity=1, fiber_threshold=8),
+                                  dict(hybrid_granularity=1, fiber_threshold=16, mid_blocking=3),
+                                  dict(hybrid_granularity=1, group_mask=2, mode_order_policy=1)])
 @pytest.mark.parametrize("dims,nnz", [((5000, 400, 60), 120_000), ((2000, 100, 30, 12), 90_000),
                                       ((1500, 80, 20, 9, 6), 90_000)])
 def test_same_arrays_as_the_host_builder(dims, nnz, opts):
     rng = np.random.default_rng(len(dims) * 1000 + nnz)
     inds, vals = _skewed(rng, dims, nnz)
-    assert_same_format(dims, inds, vals, **opts).close()
+    dev = assert_same_format(dims, inds, vals, **opts)
+    if opts.get("hybrid_granularity") and opts.get("fiber_threshold", 64) <= 16:
+        # the per-fiber choice really splits slices of these tensors: nonzeros move from the CSF to the CSL group
+        from paper_1904_03329_amd import HbcsfTensor
+        plain = HbcsfTensor(dims, inds, vals, **{k: v for k, v in opts.items() if k != "hybrid_granularity"})
+        moved = [dev.stats(m)["group_nnz"][1] - plain.stats(m)["group_nnz"][1] for m in range(len(dims))]
+        plain.close()
+        assert max(moved) > 0 and min(moved) >= 0, moved
+    dev.close()
 
 
 @pytest.mark.parametrize("seed", range(8))

@@ -73,13 +73,14 @@ def _run_workload(oracle, synth, name, extra_opts=None):
     spread = (max(invariant) - min(invariant)) / max(scale)
     assert spread < 1e-5, f"{name}: cross-mode invariant differs by {spread:.2e}: {invariant}"
     del dfacs
-    if variant is not None:
-        variant.close()
     _device_build_matches(t, ht, name)
     ht.close()
+    if variant is not None:
+        _device_build_matches(t, variant, f"{name} with {extra_opts}", **extra_opts)
+        variant.close()
 
 
-def _device_build_matches(t, host, name):
+def _device_build_matches(t, host, name, **opts):
     """The device-side builder must produce the host builder's arrays, which the checks above validated."""
     import torch
     from paper_1904_03329_amd import HbcsfTensor, binding as B
@@ -89,7 +90,7 @@ def _device_build_matches(t, host, name):
     dv = torch.from_numpy(t.vals).cuda()
     torch.cuda.synchronize()
     t1 = time.time()
-    dev = HbcsfTensor.from_device_coo(t.dims, di, dv)
+    dev = HbcsfTensor.from_device_coo(t.dims, di, dv, **opts)
     torch.cuda.synchronize()
     print(f"{name}: device build {time.time() - t1:.2f}s (COO upload {t1 - t0:.2f}s)", flush=True)
     del di, dv
