@@ -235,8 +235,7 @@ int hbcsf_kernel_ms(hbcsf_tensor *t, uint32_t calls_back, float ms[4]);
  * caller's device arena.  Packed coordinates (sum over the modes of ceil(log2(dim)) bits) above
  * 64 bits are sorted in two stable 64-bit passes; above 128 bits (possible at order 5 only) the
  * build is refused with HBCSF_ERANGE and hbcsf_build_format has to be used.  Orders 3 to 5 and
- * every option but single_representation = 1, which is the host builder's only (HBCSF_EINVAL
- * here).
+ * every option of hbcsf_opts.
  * ------------------------------------------------------------------------------------------- */
 
 /* Sizes to allocate before hbcsf_build_format_device: arena_bytes is an upper bound over every

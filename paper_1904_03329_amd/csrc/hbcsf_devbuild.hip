@@ -575,8 +575,13 @@ int check_args(int order, const uint64_t* dims, uint64_t nnz, const hbcsf_opts* 
   if (o->coo_row_flags > 1) return fail(HBCSF_EINVAL, "coo_row_flags must be 0 or 1");
   if (o->mid_blocking > 13) return fail(HBCSF_EINVAL, "mid_blocking must be 0 or 1 (off) or 2..13 bits");
   if (o->hybrid_granularity > 1) return fail(HBCSF_EINVAL, "hybrid_granularity must be 0 or 1");
-  if (o->single_representation != 0)
-    return fail(HBCSF_EINVAL, "single_representation = 1 is built by hbcsf_build_format (host) only");
+  if (o->single_representation > 1) return fail(HBCSF_EINVAL, "single_representation must be 0 or 1");
+  if (o->single_representation) {
+    if ((opts->fiber_threshold && opts->fiber_threshold != default_fiber_threshold(order)) || o->group_mask ||
+        o->hybrid_granularity || o->coo_row_flags || o->mid_blocking > 1)
+      return fail(HBCSF_EINVAL, "single_representation goes with default options only");
+    o->group_mask = 4;  // plain B-CSF: the kernel for the other modes walks one group
+  }
   if (total > 128)
     return fail(HBCSF_ERANGE, "the packed coordinates exceed 128 bits: build this tensor with hbcsf_build_format");
   *totalBits = total;
@@ -887,7 +892,8 @@ int hbcsf_build_format_device(int order, const uint64_t* dims, uint64_t nnz, con
   HIP_TRY(hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev), "hipDeviceGetAttribute");
   t->numCU = cu > 0 ? cu : 256;
   uint64_t used = 0;
-  for (int m = 0; m < order; ++m) {
+  t->single = o.single_representation == 1;
+  for (int m = 0; m < (t->single ? 1 : order); ++m) {  // single representation: only mode 0's tree is stored
     t->modes[m].reset(new (std::nothrow) ModeFormat);
     if (!t->modes[m]) return fail(HBCSF_ENOMEM, "out of host memory");
     const int modeBits = totalBits + mid_block_bits(order, dims, o, m);   // this mode's key width

@@ -19,9 +19,9 @@ def _device_tensor(dims, inds, vals, **opts):
     return HbcsfTensor.from_device_coo(dims, di, dv, **opts)
 
 
-def _arrays(h, order):
+def _arrays(h, order, modes=None):
     out = {}
-    for mode in range(order):
+    for mode in (range(order) if modes is None else modes):
         for aid in (B.ARR_OWNED_BITS, B.ARR_COO_BITS, B.ARR_COO_PTR):
             out[(mode, aid)] = B.host_array(h, mode, 0, 0, aid)
         for g in range(3):
@@ -46,11 +46,12 @@ def assert_same_format(dims, inds, vals, **opts):
     with pytest.raises(B.HbcsfError):
         B.host_array(dev.handle, 0, 0, 0, B.ARR_VAL)          # no host copy yet
     B.download(dev.handle)
-    for mode in range(order):
+    modes = [0] if opts.get("single_representation") else list(range(order))   # one stored tree / one per mode
+    for mode in modes:
         sh, sd = host.stats(mode), dev.stats(mode)
         sh.pop("build_seconds"), sd.pop("build_seconds")
         assert sh == sd, f"mode {mode}: statistics differ"
-    ah, ad = _arrays(host.handle, order), _arrays(dev.handle, order)
+    ah, ad = _arrays(host.handle, order, modes), _arrays(dev.handle, order, modes)
     assert ah.keys() == ad.keys()
     for k in ah:
         assert np.array_equal(ah[k], ad[k]), f"array {k} differs"
@@ -122,6 +123,29 @@ def test_same_arrays_as_the_host_builder(dims, nnz, opts):
         moved = [dev.stats(m)["group_nnz"][1] - plain.stats(m)["group_nnz"][1] for m in range(len(dims))]
         plain.close()
         assert max(moved) > 0 and min(moved) >= 0, moved
+    dev.close()
+
+
+@pytest.mark.parametrize("dims,nnz", [((3000, 700, 90), 200_000), ((900, 300, 40, 25), 150_000),
+                                      ((600, 200, 30, 12, 8), 120_000)])
+def test_single_representation(oracle, dims, nnz):
+    """single_representation = 1 built on the device: mode 0's plain B-CSF tree only, equal to the host's, and every
+    mode's MTTKRP from it against the oracle (rank 32)."""
+    import torch
+
+    rng = np.random.default_rng(len(dims) * 13 + 1)
+    inds, vals = _skewed(rng, dims, nnz)
+    dev = assert_same_format(dims, inds, vals, single_representation=1)
+    facs = [rng.uniform(0, 1, size=(d, 32)).astype(np.float32) for d in dims]
+    dfacs = [torch.from_numpy(f).cuda() for f in facs]
+    for mode in range(len(dims)):
+        out = torch.full((dims[mode], 32), float("nan"), dtype=torch.float32, device="cuda")
+        dev.mttkrp(mode, dfacs, out)
+        torch.cuda.synchronize()
+        GU.assert_close(out.cpu().numpy(), oracle.mttkrp(dims, inds, vals, facs, mode), f"single, device-built, mode {mode}")
+    with pytest.raises(B.HbcsfError) as e:
+        _device_tensor(dims, inds, vals, single_representation=1, group_mask=1)
+    assert e.value.code == -1
     dev.close()
 
 
