@@ -149,17 +149,23 @@ def test_single_representation(oracle, dims, nnz):
     dev.close()
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(24))
 def test_random_small_tensors(oracle, seed):
+    """Random small tensors (duplicates allowed in some) with the build options drawn at random: both builders give the
+    same arrays, and the MTTKRP from the device-built handle matches the oracle."""
     import torch
 
     rng = np.random.default_rng(7000 + seed)
     order = 3 + seed % 3
     dims = tuple(int(rng.integers(1, 200 if order < 5 else 40)) for _ in range(order))
     nnz = int(rng.integers(1, 3000))
-    inds, vals = _random(rng, dims, nnz)
+    inds, vals = _random(rng, dims, nnz, distinct=bool(seed % 4))
     rank = [8, 16, 32][seed % 3]
-    dev = assert_same_format(dims, inds, vals, fiber_threshold=[8, 64][seed % 2])
+    opts = dict(fiber_threshold=int(rng.choice([8, 16, 32, 64])), mode_order_policy=int(rng.integers(0, 3)),
+                group_mask=int(rng.choice([0, 0, 1, 2, 4])), hybrid_granularity=int(rng.integers(0, 2)),
+                coo_row_flags=int(rng.integers(0, 2)), mid_blocking=int(rng.choice([0, 0, 2, 3])))
+    print("random", dims, nnz, rank, opts, flush=True)
+    dev = assert_same_format(dims, inds, vals, **opts)
     facs = [rng.uniform(0, 1, size=(d, rank)).astype(np.float32) for d in dims]
     dfacs = [torch.from_numpy(f).cuda() for f in facs]
     for mode in range(order):
