@@ -375,6 +375,9 @@ def measure(name: str, args, headline: bool, log) -> dict:
     w = synthgen.WORKLOADS[name]
     t0 = time.time()
     t, facs, rank = synthgen.workload(name)
+    if args.rank and args.rank != rank:   # the workload's tensor with factor matrices of another rank
+        rank = args.rank
+        facs = synthgen.factors(t.dims, rank, w.seed)
     gen_s = time.time() - t0
     log(f"[bench] {name}: dims={t.dims} nnz={t.nnz} draws={t.draws} R={rank} generated in {gen_s:.1f}s")
     t0 = time.time()
@@ -547,6 +550,9 @@ def main() -> int:
     ap.add_argument("--fuse-coo", type=int, default=-1,
                     help="HBCSF_TUNE_FUSE_COO: 0 separate COO kernel, 1 COO rows in the output-definition pass, 2 that "
                          "for small outputs (library default)")
+    ap.add_argument("--rank", type=int, default=0,
+                    help="factor-matrix rank other than the workload's 32 (8, 16, 64, 128; fp64: 16, 64); the ALS "
+                         "timing then uses the plain vector-ALU dense kernels")
     ap.add_argument("--dtype", choices=("f32", "f64"), default="f32",
                     help="element type of the factor matrices, partial sums and output (f64: hbcsf_mttkrp_f64; the "
                          "ALS timing and the single-representation comparison are fp32 only)")
@@ -601,7 +607,7 @@ def main() -> int:
 
     order = head["order"]
     line = {
-        "metric": "sparse MTTKRP GFLOP/s (3*R*nnz per mode, all modes) at rank R=32",
+        "metric": f"sparse MTTKRP GFLOP/s (3*R*nnz per mode, all modes) at rank R={args.rank or 32}",
         "value": head["value"],
         "unit": "GFLOP/s",
         "n_gpus": 1,
