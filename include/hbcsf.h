@@ -47,7 +47,10 @@ typedef struct hbcsf_tensor hbcsf_tensor; /* opaque, owned by the library, freed
 typedef struct hbcsf_opts {
   uint32_t fiber_threshold;   /* T_f of fbr-split (Section IV-B, VI-B): no fiber segment holds more
                                  than T_f nonzeros.  Cuts fall on multiples of T_f in a group's
-                                 nonzero stream.  8, 16, 32 or 64.  Default 64 (order 3), 32 (orders 4, 5). */
+                                 nonzero stream.  8, 16, 32 or 64.  Default 64 (order 3), 32 (orders 4, 5),
+                                 chosen for rank 32; a wavefront keeps 64 / (rank / 4) runs in LDS at a time, so
+                                 for ranks 16 / 8 half / a quarter of the default keeps the same number of
+                                 wavefronts resident and is markedly faster.                                 */
   uint32_t slice_threshold;   /* T_s of slc-split (Section IV-A): nonzeros one wavefront works
                                  through before it merges its partial rows; a slice of n nonzeros
                                  is shared by at most ceil(n/T_s)+1 wavefronts.  0 = sized from
