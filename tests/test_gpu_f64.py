@@ -122,6 +122,15 @@ def test_cfg2_every_element(oracle, synth):
     _check_all_modes(oracle, t.dims, t.inds, t.vals, facs64, "f64 cfg2")
 
 
+def test_cfg3_every_element(oracle, synth):
+    """The 100 M-nonzero power-law benchmark workload at full size in fp64: slices of up to 11.6 M nonzeros merged with
+    fp64 atomic adds, all modes, every element."""
+    t, facs, rank = synth.workload("cfg3")
+    facs64 = [f.astype(np.float64) + 1e-9 * np.cos(np.arange(f.size, dtype=np.float64)).reshape(f.shape) for f in facs]
+    print("f64 cfg3", t.dims, t.nnz, rank, flush=True)
+    _check_all_modes(oracle, t.dims, t.inds, t.vals, facs64, "f64 cfg3")
+
+
 def test_argument_errors():
     import torch
 
